@@ -1,0 +1,218 @@
+/*
+ * libspd -- Superposed Decoding (arXiv 2405.18400) hot path for AMD MI355X (gfx950).
+ *
+ * One SPD timestep (Section 3; Algorithm 1, else-branch), entirely on the GPU:
+ *   superposition weights (Section 3.1, Eq. 2) -> superposed input embedding (Eq. 1) ->
+ *   batch-1 decoder forward over one shared key/value cache (Section 3, "Next Timesteps")
+ *   -> full-vocabulary log-softmax with temperature and KeepTopK (Algorithm 1) ->
+ *   k x k draft options -> n-gram mixture (Section 3.2, Eq. 3) -> interpolation (Eq. 4)
+ *   or the no-overlap penalty form (Eq. 5) -> keep the k most probable options and update
+ *   their probabilities (Section 3, Eq. for D and P).
+ *
+ * Conventions
+ *   - Every function returns SPD_OK (0) or a negative spd_status.  No exceptions, no global
+ *     state.  spd_last_error() gives a human-readable reason for the last failure on a ctx.
+ *   - "device" pointers are HIP device memory owned by the CALLER (the library never
+ *     allocates or frees device memory); "host" pointers are ordinary host memory.
+ *   - All GPU work is enqueued on the hipStream_t given to spd_create (passed as void*;
+ *     NULL = the default stream).  A call that fills host outputs synchronises that stream
+ *     before returning; a call with no host outputs does not synchronise.
+ *   - Scores cross this boundary as natural-log probabilities.
+ *   - Matrices are row-major [out_features, in_features], contiguous, 16-byte aligned,
+ *     stored in cfg.dtype (fp32, or bf16 bit patterns).  Norm gains use the same dtype.
+ *   - One ctx serves one generation at a time; calls on one ctx must not overlap.
+ */
+#ifndef SPD_H
+#define SPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPD_K_MAX 16      /* compile-time ceiling on the number of drafts k            */
+#define SPD_MIN_ORDER 2   /* n-gram orders n = 2..6 (Section 3.2)                      */
+#define SPD_MAX_ORDER 6
+#define SPD_N_ORDERS 5
+#define SPD_TAIL 5        /* tokens of history an order-6 context needs                */
+
+typedef enum {
+    SPD_OK = 0,
+    SPD_EINVAL = -1,        /* bad argument (null pointer, shape, alignment, range)      */
+    SPD_ESTATE = -2,        /* call out of order (e.g. step before prefill)              */
+    SPD_ECTX_OVERFLOW = -3, /* the key/value cache would exceed cfg.max_ctx              */
+    SPD_EWORKSPACE = -4,    /* workspace / table buffer too small or misaligned          */
+    SPD_ETABLE = -5,        /* n-gram table rejected (duplicate key, id >= vocab, ...)   */
+    SPD_EHIP = -6           /* a HIP runtime call failed                                 */
+} spd_status;
+
+typedef enum { SPD_DTYPE_FP32 = 0, SPD_DTYPE_BF16 = 1 } spd_dtype;
+
+/* Decoder-only transformer f_theta: RMSNorm, rotary on adjacent pairs (x_2i, x_2i+1) with
+ * angle pos * rope_theta^(-2i/d_head), causal attention scaled by 1/sqrt(d_head), SwiGLU
+ * feed-forward, untied embedding / LM head, no biases.  d_head = d_model / n_heads. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
+    int32_t max_ctx;   /* key/value cache capacity in positions (prefix + generated)        */
+    int32_t k_max;     /* largest k any spd_step will use, 1..SPD_K_MAX                     */
+    int32_t dtype;     /* spd_dtype of weights; the KV cache uses the same type             */
+    float rms_eps, rope_theta;
+} spd_model_cfg;
+
+typedef struct {
+    const void *attn_norm; /* [d_model]                                                    */
+    const void *wqkv;      /* [(n_heads + 2 n_kv_heads) d_head, d_model]: q rows, k, v      */
+    const void *wo;        /* [d_model, n_heads d_head]                                     */
+    const void *ffn_norm;  /* [d_model]                                                    */
+    const void *w_gate;    /* [d_ffn, d_model]                                              */
+    const void *w_up;      /* [d_ffn, d_model]                                              */
+    const void *w_down;    /* [d_model, d_ffn]                                              */
+} spd_layer_weights;
+
+/* Borrowed device pointers; they must stay valid until spd_destroy. `layers` is a HOST
+ * array of n_layers structs (copied by spd_create). */
+typedef struct {
+    const void *embed;      /* [vocab, d_model] token embeddings z (Section 3.1)            */
+    const spd_layer_weights *layers;
+    const void *final_norm; /* [d_model]                                                   */
+    const void *lm_head;    /* [vocab, d_model]                                             */
+} spd_weight_ptrs;
+
+/* N-gram frequency tables (Section 4: every unique n-gram with its count), HOST memory.
+ * Order n uses index n-2.  keys[n-2] is int32 [n_entries[n-2], n] row-major (oldest token
+ * first, predicted token last); counts[n-2] is uint32 [n_entries[n-2]].  An order may be
+ * empty (n_entries 0, pointers may be NULL).  lambda[n-2] is that order's mixture weight
+ * (Eq. 3); the paper's values are 0.01, 0.04, 0.15, 0.18, 0.12 (Appendix B). */
+typedef struct {
+    const int32_t *keys[SPD_N_ORDERS];
+    const uint32_t *counts[SPD_N_ORDERS];
+    int64_t n_entries[SPD_N_ORDERS];
+    float lambda[SPD_N_ORDERS];
+} spd_ngram_host_tables;
+
+/* Per-call decoding parameters (Appendix B): number of drafts k, interpolation weight
+ * alpha in [0,1] (0 = n-gram smoothing disabled), temperature tau > 0 applied to the logits
+ * of the full-vocabulary softmax, no-overlap penalty delta > 0 (Eq. 5). */
+typedef struct {
+    int32_t k;
+    float alpha, tau, delta;
+} spd_decode_cfg;
+
+typedef struct spd_ctx spd_ctx;
+
+/* Bytes of device workspace spd_create needs for this shape (KV cache, activations,
+ * attention partials, draft state, token history). Host-only; touches no GPU. */
+int spd_workspace_bytes(const spd_model_cfg *cfg, size_t *out_bytes);
+
+/* Create a decoding context.  `workspace` is caller-owned DEVICE memory of at least
+ * spd_workspace_bytes() bytes, 256-byte aligned, untouched by the caller until
+ * spd_destroy.  `hip_stream` is a hipStream_t (or NULL).  Validates shapes and alignment
+ * before any GPU work.  *out is set only on success and is freed by spd_destroy. */
+int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *weights, void *workspace,
+               size_t workspace_bytes, void *hip_stream, spd_ctx **out);
+void spd_destroy(spd_ctx *ctx);
+
+/* Bytes of DEVICE memory spd_load_ngrams needs for these tables (exact-key hash table of
+ * all n-grams plus one context-total entry per distinct context).  Host-only. */
+int spd_ngram_table_bytes(const spd_ngram_host_tables *tables, size_t *out_bytes);
+
+/* Build the device-resident n-gram store (Section 3.2; the paper keeps these in host
+ * dictionaries, Section 4.3) in `dev_buf` (caller-owned DEVICE memory, 256-byte aligned,
+ * kept alive while in use) and attach it to ctx.  Rejects (SPD_ETABLE) a duplicate key, a
+ * token id outside [0, vocab) or a zero count.  May be called again at any time outside a
+ * step to swap tables.  Synchronises the stream.  Without tables only alpha = 0 is legal. */
+int spd_load_ngrams(spd_ctx *ctx, const spd_ngram_host_tables *tables, void *dev_buf,
+                    size_t dev_bytes);
+
+/* First-timestep forward (Section 3, "First Timestep"): reset the generation, run the
+ * model over prefix[0..m-1] (HOST int32 ids in [0, vocab), 1 <= m < max_ctx), fill cache
+ * positions 0..m-1 and keep the last position's logits.  Does not synchronise. */
+int spd_prefill(spd_ctx *ctx, const int32_t *prefix, int32_t m);
+
+/* Advance every draft by one token.  The first call after spd_prefill gives draft i the
+ * i-th most probable token of p_theta(. | M) with that token's log-probability as its
+ * score (no n-gram term); later calls run one full SPD timestep.  dc->k must stay the same
+ * between a prefill and the end of its generation.  Outputs are HOST arrays of k entries,
+ * best draft first, each may be NULL: the newest token of each surviving draft, the index
+ * (0..k-1, in the previous step's order; -1 at the first step) of the draft it extends,
+ * and its log-score.  If all three are NULL the call does not synchronise. */
+int spd_step(spd_ctx *ctx, const spd_decode_cfg *dc, int32_t *out_last_tokens,
+             int32_t *out_parents, float *out_logscores);
+
+/* Algorithm 1 end to end: spd_prefill + n_tokens spd_steps, then rebuild the drafts from
+ * the per-step parent indices.  out_drafts is HOST int32 [k, n_tokens] row-major, best
+ * draft first; out_logscores HOST float [k].  Synchronises. */
+int spd_generate(spd_ctx *ctx, const int32_t *prefix, int32_t m, const spd_decode_cfg *dc,
+                 int32_t n_tokens, int32_t *out_drafts, float *out_logscores);
+
+/* ---- state access: resets (Section 5.3) and step-by-step comparison with a reference ---- */
+
+/* Read the k drafts' bookkeeping (HOST outputs, any may be NULL): tails int32 [k, SPD_TAIL]
+ * = the last 5 tokens of (prefix, draft), oldest first, -1 where the history is shorter;
+ * logscores float [k]; gamma float [k] = the superposition weights (Eq. 2) of the current
+ * scores.  Synchronises. */
+int spd_get_state(spd_ctx *ctx, int32_t *out_k, int32_t *out_tails, float *out_logscores,
+                  float *out_gamma);
+/* Overwrite the drafts' bookkeeping (HOST inputs) between steps; the KV cache is untouched.
+ * Legal once the first step after a prefill has run.  Synchronises. */
+int spd_set_state(spd_ctx *ctx, int32_t k, const int32_t *tails, const float *logscores);
+/* Copy the logits [vocab] of the most recent forward pass to HOST memory.  Synchronises. */
+int spd_read_logits(spd_ctx *ctx, float *out_logits);
+
+/* What the most recent step decided (HOST outputs, any may be NULL): the kept token ids
+ * int32 [k] and their log p_theta float [k] (Algorithm 1, KeepTopK); for each option
+ * (i, j) = draft i + kept token j, row-major [k, k]: its score log p_i + log p_f (float),
+ * whether it was an option at all (int32 0/1; options outside the overlap set are not,
+ * Section 3.2) and the n-gram mixture value p_ngram (float, Eq. 3).  Synchronises. */
+int spd_get_step_info(spd_ctx *ctx, int32_t *out_top_ids, float *out_top_logp,
+                      float *out_cand_scores, int32_t *out_cand_valid, float *out_cand_pngram);
+
+/* Run only the post-forward part of a timestep (KeepTopK, expansion, n-gram probes,
+ * interpolation, prune, state update) on caller-supplied DEVICE logits float [vocab], as
+ * if the forward pass had produced them.  `first` != 0 performs the first-timestep
+ * initialisation instead.  Requires a prior spd_prefill (it provides the history).  Does
+ * not touch the KV cache or the position.  Does not synchronise. */
+int spd_expand_prune(spd_ctx *ctx, const spd_decode_cfg *dc, const float *dev_logits, int32_t first);
+
+/* Current position (= number of cached positions) as tracked by the host. */
+int spd_position(const spd_ctx *ctx, int32_t *out_pos);
+
+/* Turn the captured-graph replay of spd_step on (default) or off (plain launches). */
+int spd_set_graph(spd_ctx *ctx, int32_t enable);
+
+/* Per-kernel timing for profiling runs: when enabled, spd_step launches kernels one by one
+ * with a HIP event pair around each and accumulates the elapsed time per kernel class.
+ * spd_get_kernel_timing fills HOST arrays of up to `cap` entries (class name pointers valid
+ * for the ctx lifetime, total milliseconds, launch counts), sets *out_n, and synchronises. */
+int spd_set_kernel_timing(spd_ctx *ctx, int32_t enable);
+int spd_get_kernel_timing(spd_ctx *ctx, int32_t cap, const char **out_names, float *out_ms,
+                          int64_t *out_launches, int32_t *out_n);
+
+/* ---- stand-alone operators (the kernels of one timestep, callable one at a time) ---- */
+
+/* y = W x (+ residual), optionally with x first RMS-normalised (x * rsqrt(mean x^2 + eps) *
+ * gain).  W is DEVICE [rows, cols] in `dtype`; x, residual, y are DEVICE float; gain is
+ * DEVICE [cols] in `dtype` or NULL (no normalisation); residual may be NULL or equal y. */
+int spd_op_gemv(int32_t dtype, const void *W, const void *gain, float eps, const float *x,
+                const float *residual, float *y, int32_t rows, int32_t cols, void *hip_stream);
+/* u = silu(Wg xn) * (Wu xn) with xn = RMS-normalised x (gain may be NULL: xn = x). */
+int spd_op_swiglu(int32_t dtype, const void *Wg, const void *Wu, const void *gain, float eps,
+                  const float *x, float *u, int32_t rows, int32_t cols, void *hip_stream);
+/* Single-query attention over n_ctx cached positions: out[h] = softmax(q[h] . K / sqrt(d_head)) V
+ * with K, V DEVICE [n_kv_heads, cap_ctx, d_head] in `dtype` (head-major, as the library's
+ * cache), q and out DEVICE float [n_heads, d_head]; `partials` is DEVICE scratch of
+ * spd_op_attention_scratch_bytes() bytes. */
+size_t spd_op_attention_scratch_bytes(int32_t n_heads, int32_t d_head, int32_t cap_ctx);
+int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V, float *out,
+                     void *partials, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,
+                     int32_t n_ctx, int32_t cap_ctx, void *hip_stream);
+
+const char *spd_last_error(const spd_ctx *ctx);
+const char *spd_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_H */

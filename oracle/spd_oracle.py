@@ -237,6 +237,7 @@ class StepRecord:
     gap_vocab: float               # min gap between adjacent logits among ranks 1..k+1
     gap_prune: float               # min gap between adjacent candidate scores, ranks 1..k+1
     pngram: np.ndarray | None = None   # [k, k] mixture values p_ngram(i, j)
+    state_in: "SpdState | None" = None  # the drafts and scores this step started from
 
 
 @dataclass
@@ -305,7 +306,7 @@ def expand_and_prune(state: SpdState, logits, tables: NgramTables | None, cfg: D
     srt = np.sort(np.asarray(logits, dtype=np.float64))[::-1]
     rec = StepRecord(np.array(logits) if keep_logits else None, ids, logp[ids], cands, kept, gamma_in,
                      _adjacent_gap(srt, cfg.k),
-                     _adjacent_gap([cands[c].logscore for c in order], k), png)
+                     _adjacent_gap([cands[c].logscore for c in order], k), png, state)
     return new, rec
 
 

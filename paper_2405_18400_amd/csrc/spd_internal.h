@@ -1,0 +1,164 @@
+// Internal declarations shared by the host library and the HIP kernels of libspd.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spd.h"
+
+// ---------------------------------------------------------------- n-gram store (device)
+// One open-addressing table (linear probing) for every order.  A slot holds up to six token
+// ids, oldest first, and a 64-bit count:
+//   count entry of order n : tok[0..n-1] >= 0, the rest NG_PAD
+//   total entry of order n : tok[0..n-2] = context, tok[n-1] = NG_TOTAL, the rest NG_PAD;
+//                            count = sum of the counts of all order-n entries with that context
+//   empty slot             : tok[0] = NG_EMPTY
+struct NgramSlot {
+    int32_t tok[6];
+    uint32_t cnt_lo, cnt_hi;
+};
+static_assert(sizeof(NgramSlot) == 32, "slot must be 32 bytes");
+constexpr int32_t NG_PAD = -1;
+constexpr int32_t NG_TOTAL = -2;
+constexpr int32_t NG_EMPTY = -3;
+
+struct NgramDev {
+    const NgramSlot *slots;  // device
+    uint64_t capacity;       // number of slots; home slot = mulhi64(hash, capacity)
+    int32_t max_probe;       // longest displacement of any stored key
+    int32_t present[SPD_N_ORDERS];
+    float lambda[SPD_N_ORDERS];
+};
+
+// Home slot of a hash value: floor(h * capacity / 2^64).
+__host__ __device__ inline uint64_t ngram_home(uint64_t h, uint64_t capacity) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umul64hi(h, capacity);
+#else
+    return (uint64_t)(((unsigned __int128)h * capacity) >> 64);
+#endif
+}
+
+__host__ __device__ inline uint64_t ngram_hash(const int32_t *tok6) {
+    uint64_t h = 0x9E3779B97F4A7C15ull;
+    for (int i = 0; i < 6; ++i) {
+        h ^= (uint64_t)(uint32_t)tok6[i];
+        h *= 0xFF51AFD7ED558CCDull;
+        h ^= h >> 29;
+    }
+    h *= 0xC4CEB9FE1A85EC53ull;
+    h ^= h >> 32;
+    return h;
+}
+
+// ---------------------------------------------------------------- draft state (device)
+constexpr int SPD_KK = SPD_K_MAX * SPD_K_MAX;
+
+struct DevState {
+    int32_t pos;    // number of cached positions = position the next forward pass writes
+    int32_t n_gen;  // tokens generated so far per draft
+    int32_t k;
+    int32_t err;
+    int32_t prefix_tail[SPD_TAIL];        // last 5 prefix tokens, oldest first, NG_PAD-padded
+    int32_t tails[SPD_K_MAX][SPD_TAIL];   // last 5 tokens of (prefix, draft i)
+    float logscore[SPD_K_MAX];            // log p_i
+    float gamma[SPD_K_MAX];               // Eq. 2 on the current scores
+    float gamma_in[SPD_K_MAX];            // the weights the last superposed input used
+    int32_t top_ids[SPD_K_MAX];           // KeepTopK of the last step
+    float top_logp[SPD_K_MAX];
+    int32_t new_tok[SPD_K_MAX];           // newest token / parent of each surviving draft
+    int32_t new_parent[SPD_K_MAX];
+    float cand_score[SPD_KK];             // option (i, j) at [i * k + j]
+    int32_t cand_valid[SPD_KK];
+    float cand_png[SPD_KK];
+};
+
+// ---------------------------------------------------------------- kernel launch arguments
+enum GemvEpilogue { EPI_PLAIN = 0, EPI_RESID = 1, EPI_QKV = 2, EPI_SWIGLU = 3 };
+
+struct GemvArgs {
+    const void *W;       // [rows, cols]
+    const void *W2;      // EPI_SWIGLU: the "up" matrix
+    const void *gain;    // [cols] in weight dtype, or null: no RMS normalisation of x
+    float eps;
+    const float *x;      // [cols]
+    const float *resid;  // EPI_RESID: may alias y
+    float *y;            // EPI_PLAIN/RESID/SWIGLU: [rows]; EPI_QKV: q buffer [n_q_rows]
+    int32_t rows, cols;
+    // EPI_QKV
+    void *kcache, *vcache;      // [n_kv_heads, cap_ctx, d_head] in weight dtype
+    const DevState *st;         // position
+    const double *inv_freq;     // [d_head / 2]
+    int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
+};
+
+struct AttnArgs {
+    const float *q;   // [n_heads, d_head]
+    const void *K, *V;
+    float *out;       // [n_heads, d_head]
+    float *part;      // [n_heads, max_splits, d_head + 2]
+    int32_t *counters;  // [n_heads], zero between launches
+    const DevState *st;  // n_ctx = st->pos + 1 when non-null
+    int32_t n_ctx;       // used when st is null
+    int32_t n_heads, n_kv_heads, d_head, cap_ctx, chunk, max_splits;
+};
+
+struct SuperposeArgs {
+    const void *embed;
+    DevState *st;
+    const int32_t *prefix;  // mode 0: token = prefix[st->pos]
+    float *h;
+    int32_t d_model, mode, k;
+};
+
+struct TopkArgs {
+    const float *logits;
+    int32_t vocab, k, n_part, per_part;
+    float tau;
+    float *pv;    // [n_part, SPD_K_MAX]
+    int32_t *pi;  // [n_part, SPD_K_MAX]
+    float *pm, *ps;  // [n_part]
+};
+
+struct ExpandArgs {
+    DevState *st;
+    const float *pv;
+    const int32_t *pi;
+    const float *pm, *ps;
+    int32_t n_part;
+    NgramDev ng;
+    int32_t k;
+    float alpha, tau, delta;
+    int32_t first, advance;
+    int32_t *hist_tok, *hist_par;  // [max_gen, SPD_K_MAX]
+    int32_t max_gen;
+};
+
+constexpr int TOPK_PART_MAX = 128;
+constexpr int ATTN_CHUNK = 256;
+
+namespace spdk {
+hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu);
+size_t gemv_lds_bytes(int dtype, int cols);
+hipError_t attention(hipStream_t s, int dtype, const AttnArgs &a);
+hipError_t superpose(hipStream_t s, int dtype, const SuperposeArgs &a);
+hipError_t topk_partial(hipStream_t s, const TopkArgs &a);
+hipError_t expand_prune(hipStream_t s, const ExpandArgs &a);
+hipError_t advance(hipStream_t s, DevState *st);
+hipError_t renorm(hipStream_t s, DevState *st, int k);
+hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);
+hipError_t init();  // raise the dynamic-LDS limit of the kernels that need it
+}  // namespace spdk
+
+// ---------------------------------------------------------------- host-side table builder
+#include <string>
+#include <vector>
+struct NgramHostTable {
+    std::vector<NgramSlot> slots;
+    int32_t max_probe = 0;
+    int32_t present[SPD_N_ORDERS] = {0, 0, 0, 0, 0};
+};
+// Upper bound on the slots ngram_build will use for these entry counts.
+uint64_t ngram_capacity_for(const spd_ngram_host_tables *t);
+// Returns SPD_OK or SPD_ETABLE / SPD_EINVAL with a reason in `err`.
+int ngram_build(const spd_ngram_host_tables *t, int32_t vocab, uint64_t capacity, NgramHostTable &out,
+                std::string &err);

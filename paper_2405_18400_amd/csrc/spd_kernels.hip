@@ -1,0 +1,720 @@
+// HIP kernels for one Superposed Decoding timestep on gfx950 (wave64).
+//
+// Batch-1 decode is a chain of matrix-vector products, so every kernel here is built
+// around streaming weights from HBM exactly once with 128-bit loads; the only arithmetic
+// that matters for time is keeping enough bytes in flight.  Reductions use a fixed order
+// (no float atomics), so results are bit-reproducible run to run.
+#include "spd_internal.h"
+
+#include <climits>
+#include <cmath>
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr int BLOCK = 256;
+constexpr int NWAVE = BLOCK / WAVE;
+
+// ------------------------------------------------------------------ storage types
+struct bf16_t { uint16_t b; };
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+    static constexpr int VEC = 4;  // elements per 16-byte load
+    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ float load1(const void *p, size_t i) { return ((const float *)p)[i]; }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) { ((float *)p)[i] = v; }
+};
+template <> struct Store<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ float load1(const void *p, size_t i) {
+        return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
+    }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) {
+        uint32_t u = __float_as_uint(v);               // round to nearest even
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        ((uint16_t *)p)[i] = (uint16_t)(u >> 16);
+    }
+};
+
+__device__ __forceinline__ u32x4 stream_load16(const void *p) {
+    return __builtin_nontemporal_load((const u32x4 *)p);   // weights are read once per step
+}
+
+// Read data another workgroup (possibly on another XCD, behind another L2) wrote and
+// published with a device-scope fence.
+__device__ __forceinline__ float coherent_load(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+// Sum over the block in a fixed order; every thread gets the result. `red` has NWAVE floats.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVE; ++w) t += red[w];
+    return t;
+}
+__device__ __forceinline__ float block_max(float v, float *red) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) t = fmaxf(t, red[w]);
+    return t;
+}
+
+// ------------------------------------------------------------------ matrix-vector product
+// One wave owns two output rows at a time (EPI_SWIGLU: row r of the gate and of the up
+// matrix) and walks the columns 64 lanes x 16 bytes at a time; x lives in LDS as fp32.
+// Loads of the next 4-iteration chunk are issued before the current chunk is consumed, and
+// the very first chunk is issued before x is staged, so HBM latency overlaps the prologue.
+constexpr int GEMV_U = 4;
+
+template <typename WT>
+__device__ __forceinline__ void gemv_issue(const char *w0, const char *w1, int chunk, int lane, int cols,
+                                           u32x4 *a, u32x4 *b) {
+    constexpr int VEC = Store<WT>::VEC;
+#pragma unroll
+    for (int u = 0; u < GEMV_U; ++u) {
+        const int c = ((chunk * GEMV_U + u) * WAVE + lane) * VEC;
+        if (c < cols) {
+            a[u] = stream_load16(w0 + (size_t)c * sizeof(WT));
+            b[u] = stream_load16(w1 + (size_t)c * sizeof(WT));
+        } else {
+            a[u] = (u32x4)(0u);
+            b[u] = (u32x4)(0u);
+        }
+    }
+}
+
+template <typename WT>
+__device__ __forceinline__ void gemv_consume(const u32x4 *a, const u32x4 *b, int chunk, int lane,
+                                             const float *xs, float &acc0, float &acc1) {
+    constexpr int VEC = Store<WT>::VEC;
+#pragma unroll
+    for (int u = 0; u < GEMV_U; ++u) {
+        const int c = ((chunk * GEMV_U + u) * WAVE + lane) * VEC;
+        float xv[VEC], fa[VEC], fb[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; v += 4) {
+            const float4 t = *(const float4 *)(xs + c + v);
+            xv[v] = t.x; xv[v + 1] = t.y; xv[v + 2] = t.z; xv[v + 3] = t.w;
+        }
+        Store<WT>::unpack(a[u], fa);
+        Store<WT>::unpack(b[u], fb);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            acc0 = fmaf(fa[v], xv[v], acc0);
+            acc1 = fmaf(fb[v], xv[v], acc1);
+        }
+    }
+}
+
+template <typename WT, int EPI>
+__global__ __launch_bounds__(BLOCK) void gemv_kernel(const GemvArgs a) {
+    constexpr int VEC = Store<WT>::VEC;
+    extern __shared__ float xs[];           // x, zero-padded to whole chunks
+    __shared__ float red[NWAVE];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
+    const int cols = a.cols;
+    const int chunk_cols = GEMV_U * WAVE * VEC;
+    const int n_chunks = (cols + chunk_cols - 1) / chunk_cols;
+    const int n_units = (EPI == EPI_SWIGLU) ? a.rows : a.rows / 2;
+    const int wave_stride = gridDim.x * NWAVE;
+    int unit = blockIdx.x * NWAVE + wid;
+    const size_t row_bytes = (size_t)cols * sizeof(WT);
+
+    auto rows_of = [&](int un, const char *&w0, const char *&w1) {
+        if (EPI == EPI_SWIGLU) {
+            w0 = (const char *)a.W + (size_t)un * row_bytes;
+            w1 = (const char *)a.W2 + (size_t)un * row_bytes;
+        } else {
+            w0 = (const char *)a.W + (size_t)(2 * un) * row_bytes;
+            w1 = w0 + row_bytes;
+        }
+    };
+
+    u32x4 A[GEMV_U], B[GEMV_U], A2[GEMV_U], B2[GEMV_U];
+    const char *w0 = nullptr, *w1 = nullptr;
+    if (unit < n_units) {
+        rows_of(unit, w0, w1);
+        gemv_issue<WT>(w0, w1, 0, lane, cols, A, B);
+    }
+
+    // stage x (RMS-normalised when a gain is given)
+    const int padded = n_chunks * chunk_cols;
+    float ss = 0.f;
+    for (int c = tid; c < padded; c += BLOCK) {
+        const float v = (c < cols) ? a.x[c] : 0.f;
+        xs[c] = v;
+        ss += v * v;
+    }
+    if (a.gain != nullptr) {
+        const float tot = block_sum(ss, red);
+        const float rs = 1.0f / sqrtf(tot / (float)cols + a.eps);
+        for (int c = tid; c < cols; c += BLOCK) xs[c] = xs[c] * rs * Store<WT>::load1(a.gain, c);
+    }
+    __syncthreads();
+
+    while (unit < n_units) {
+        float acc0 = 0.f, acc1 = 0.f;
+        const int next_unit = unit + wave_stride;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const bool last = (ch + 1 == n_chunks);
+            bool have_next = true;
+            if (!last) {
+                gemv_issue<WT>(w0, w1, ch + 1, lane, cols, A2, B2);
+            } else if (next_unit < n_units) {
+                rows_of(next_unit, w0, w1);
+                gemv_issue<WT>(w0, w1, 0, lane, cols, A2, B2);
+            } else {
+                have_next = false;
+            }
+            gemv_consume<WT>(A, B, ch, lane, xs, acc0, acc1);
+            if (have_next) {
+#pragma unroll
+                for (int u = 0; u < GEMV_U; ++u) { A[u] = A2[u]; B[u] = B2[u]; }
+            }
+        }
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        if (lane == 0) {
+            if (EPI == EPI_PLAIN) {
+                a.y[2 * unit] = acc0;
+                a.y[2 * unit + 1] = acc1;
+            } else if (EPI == EPI_RESID) {
+                a.y[2 * unit] = a.resid[2 * unit] + acc0;
+                a.y[2 * unit + 1] = a.resid[2 * unit + 1] + acc1;
+            } else if (EPI == EPI_SWIGLU) {
+                a.y[unit] = acc0 / (1.0f + expf(-acc0)) * acc1;
+            } else {  // EPI_QKV: rotary on q and k pairs, append k and v to the cache
+                const int r0 = 2 * unit;
+                const int pos = a.st->pos;
+                if (r0 < a.n_q_rows + a.n_kv_rows) {
+                    const int i = (r0 % a.d_head) / 2;
+                    const double ang = (double)pos * a.inv_freq[i];
+                    const float c = (float)cos(ang), s = (float)sin(ang);
+                    const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
+                    const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));
+                    if (r0 < a.n_q_rows) {
+                        a.y[r0] = e;
+                        a.y[r0 + 1] = o;
+                    } else {
+                        const int rr = r0 - a.n_q_rows;
+                        const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+                        Store<WT>::store1(a.kcache, at, e);
+                        Store<WT>::store1(a.kcache, at + 1, o);
+                    }
+                } else {
+                    const int rr = r0 - a.n_q_rows - a.n_kv_rows;
+                    const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+                    Store<WT>::store1(a.vcache, at, acc0);
+                    Store<WT>::store1(a.vcache, at + 1, acc1);
+                }
+            }
+        }
+        unit = next_unit;
+    }
+}
+
+// ------------------------------------------------------------------ single-query attention
+// Block (g, s): key/value head g, context chunk s.  All query heads sharing head g are
+// served from one pass over the chunk.  Chunks are merged by whichever block finishes last
+// for a head, walking the partial results in chunk order (deterministic).
+template <typename KT>
+__global__ __launch_bounds__(BLOCK) void attn_kernel(const AttnArgs a) {
+    constexpr int VEC = Store<KT>::VEC;
+    __shared__ float sc[ATTN_CHUNK];
+    __shared__ float red[NWAVE];
+    extern __shared__ float dyn[];        // [BLOCK / LPP][dh] partial outputs
+    __shared__ int s_last;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
+    const int dh = a.d_head;
+    const int LPP = dh / VEC;             // lanes per cached position
+    const int PPW = WAVE / LPP;           // positions per wave per iteration
+    const int PPB = PPW * NWAVE;
+    const int sub = lane / LPP, li = lane % LPP;
+    const int n_ctx = a.st ? a.st->pos + 1 : a.n_ctx;
+    const int g = blockIdx.x, s = blockIdx.y;
+    const int t0 = s * a.chunk;
+    if (t0 >= n_ctx) return;
+    const int t1 = min(n_ctx, t0 + a.chunk);
+    const int n_splits = (n_ctx + a.chunk - 1) / a.chunk;
+    const int group = a.n_heads / a.n_kv_heads;
+    const float scale = 1.0f / sqrtf((float)dh);
+    const char *Kg = (const char *)a.K + (size_t)g * a.cap_ctx * dh * sizeof(KT);
+    const char *Vg = (const char *)a.V + (size_t)g * a.cap_ctx * dh * sizeof(KT);
+
+    for (int hq = 0; hq < group; ++hq) {
+        const int h = g * group + hq;
+        float qv[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qv[v] = a.q[(size_t)h * dh + li * VEC + v];
+        // scores
+        float lmax = -INFINITY;
+        for (int t = t0 + wid * PPW + sub; t - sub < t1; t += PPB) {   // t - sub is wave-uniform
+            float d = 0.f;
+            if (t < t1) {
+                float kf[VEC];
+                Store<KT>::unpack(*(const u32x4 *)(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT)), kf);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
+            }
+            for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
+            d *= scale;
+            if (t < t1) {
+                if (li == 0) sc[t - t0] = d;
+                lmax = fmaxf(lmax, d);
+            }
+        }
+        const float m = block_max(lmax, red);   // includes a barrier after the sc writes
+        float lsum = 0.f;
+        for (int t = tid; t < t1 - t0; t += BLOCK) {
+            const float p = expf(sc[t] - m);
+            sc[t] = p;
+            lsum += p;
+        }
+        const float l = block_sum(lsum, red);
+        // weighted values
+        float acc[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+        for (int t = t0 + wid * PPW + sub; t < t1; t += PPB) {
+            float vf[VEC];
+            Store<KT>::unpack(*(const u32x4 *)(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT)), vf);
+            const float p = sc[t - t0];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
+        __syncthreads();
+        float o = 0.f;
+        if (tid < dh) {
+            for (int r = 0; r < PPB; ++r) o += dyn[(size_t)r * dh + tid];
+        }
+        if (n_splits == 1) {
+            if (tid < dh) a.out[(size_t)h * dh + tid] = o / l;
+        } else {
+            float *pp = a.part + ((size_t)h * a.max_splits + s) * (dh + 2);
+            if (tid < dh) pp[2 + tid] = o;
+            if (tid == 0) { pp[0] = m; pp[1] = l; }
+            __threadfence();
+            __syncthreads();
+            if (tid == 0) {
+                const int old = atomicAdd(&a.counters[h], 1);
+                s_last = (old == n_splits - 1);
+            }
+            __syncthreads();
+            if (s_last) {
+                __threadfence();
+                const float *ph = a.part + (size_t)h * a.max_splits * (dh + 2);
+                float M = -INFINITY;
+                for (int q = 0; q < n_splits; ++q) M = fmaxf(M, coherent_load(ph + (size_t)q * (dh + 2)));
+                float L = 0.f, O = 0.f;
+                for (int q = 0; q < n_splits; ++q) {
+                    const float *pq = ph + (size_t)q * (dh + 2);
+                    const float w = expf(coherent_load(pq) - M);
+                    L += w * coherent_load(pq + 1);
+                    if (tid < dh) O += w * coherent_load(pq + 2 + tid);
+                }
+                if (tid < dh) a.out[(size_t)h * dh + tid] = O / L;
+                if (tid == 0) a.counters[h] = 0;
+            }
+        }
+        __syncthreads();   // sc / dyn / s_last are reused by the next query head
+    }
+}
+
+// ------------------------------------------------------------------ superposed embedding
+// Section 3.1: gamma_i = p_i / sum_j p_j (from log p_i), x~ = sum_i gamma_i z_i.
+// mode 0 feeds a prefix token's own embedding (gamma = 1) during the prefix pass.
+template <typename WT>
+__global__ __launch_bounds__(BLOCK) void superpose_kernel(const SuperposeArgs a) {
+    const int c = blockIdx.x * BLOCK + threadIdx.x;
+    if (a.mode == 0) {
+        const int tok = a.prefix[a.st->pos];
+        if (c < a.d_model) a.h[c] = Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c);
+        return;
+    }
+    const int k = a.k;
+    float g[SPD_K_MAX];
+    float mx = -INFINITY;
+    for (int i = 0; i < k; ++i) mx = fmaxf(mx, a.st->logscore[i]);
+    float sum = 0.f;
+    for (int i = 0; i < k; ++i) { g[i] = expf(a.st->logscore[i] - mx); sum += g[i]; }
+    float acc = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const float gi = g[i] / sum;
+        if (c < a.d_model) {
+            const int tok = a.st->tails[i][SPD_TAIL - 1];
+            acc = __fadd_rn(acc, __fmul_rn(gi, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c)));
+        }
+        if (c == 0) a.st->gamma_in[i] = gi;
+    }
+    if (c < a.d_model) a.h[c] = acc;
+}
+
+// ------------------------------------------------------------------ vocabulary top-k
+// Total order used everywhere: larger value first, then smaller index.
+__device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
+    return va > vb || (va == vb && ia < ib);
+}
+// Block-wide arg-best; every thread gets the winner.  sv / si have NWAVE entries.
+__device__ __forceinline__ void block_best(float &v, int &i, float *sv, int *si) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, WAVE);
+        const int oi = __shfl_xor(i, o, WAVE);
+        if (better(ov, oi, v, i)) { v = ov; i = oi; }
+    }
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) { sv[threadIdx.x / WAVE] = v; si[threadIdx.x / WAVE] = i; }
+    __syncthreads();
+    v = sv[0]; i = si[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w)
+        if (better(sv[w], si[w], v, i)) { v = sv[w]; i = si[w]; }
+}
+
+// Each block scans a contiguous slice of the logits: its k best entries, its max and its
+// sum of exp((z - max)) with z = logit / tau.
+__global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
+    __shared__ float sv[NWAVE];
+    __shared__ int si[NWAVE];
+    __shared__ float red[NWAVE];
+    const int tid = threadIdx.x, b = blockIdx.x;
+    const int lo = b * a.per_part, hi = min(a.vocab, lo + a.per_part);
+    float mx = -INFINITY;
+    for (int i = lo + tid; i < hi; i += BLOCK) mx = fmaxf(mx, __fdiv_rn(a.logits[i], a.tau));
+    mx = block_max(mx, red);
+    float sm = 0.f;
+    for (int i = lo + tid; i < hi; i += BLOCK) sm += expf(__fdiv_rn(a.logits[i], a.tau) - mx);
+    sm = block_sum(sm, red);
+    if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; }
+    float pv = INFINITY;   // previous winner: everything "after" it in the total order is eligible
+    int pi = -1;
+    for (int r = 0; r < a.k; ++r) {
+        float bv = -INFINITY;
+        int bi = INT_MAX;
+        for (int i = lo + tid; i < hi; i += BLOCK) {
+            const float v = a.logits[i];
+            if (better(pv, pi, v, i) && better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        block_best(bv, bi, sv, si);
+        if (tid == 0) { a.pv[b * SPD_K_MAX + r] = bv; a.pi[b * SPD_K_MAX + r] = bi; }
+        pv = bv; pi = bi;
+    }
+}
+
+// ------------------------------------------------------------------ expand, interpolate, prune
+__device__ __forceinline__ unsigned long long ngram_probe(const NgramDev &ng, const int32_t *key) {
+    uint64_t at = ngram_home(ngram_hash(key), ng.capacity);
+    for (int p = 0; p <= ng.max_probe; ++p, at = (at + 1 == ng.capacity) ? 0 : at + 1) {
+        const NgramSlot *sl = ng.slots + at;
+        const u32x4 lo = *(const u32x4 *)sl;
+        const u32x4 hi = *((const u32x4 *)sl + 1);
+        if ((int32_t)lo.x == NG_EMPTY) return 0ull;
+        if ((int32_t)lo.x == key[0] && (int32_t)lo.y == key[1] && (int32_t)lo.z == key[2] &&
+            (int32_t)lo.w == key[3] && (int32_t)hi.x == key[4] && (int32_t)hi.y == key[5])
+            return ((unsigned long long)hi.w << 32) | hi.z;
+    }
+    return 0ull;
+}
+
+// One block.  Merges the per-slice top-k into the global KeepTopK and log-softmax, builds the
+// k x k options, probes the n-gram store for every (draft, kept token, order), applies the
+// mixture (Eq. 3), the interpolation (Eq. 4) or the penalty form (Eq. 5), keeps the k best
+// options and rewrites the draft state.
+__global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a) {
+    __shared__ float sv[NWAVE];
+    __shared__ int si[NWAVE];
+    __shared__ int s_top[SPD_K_MAX];
+    __shared__ float s_logp[SPD_K_MAX];
+    __shared__ float s_lse;
+    __shared__ int s_tails[SPD_K_MAX][SPD_TAIL];
+    __shared__ float s_old[SPD_K_MAX];
+    __shared__ unsigned long long s_cnt[SPD_KK * SPD_N_ORDERS];
+    __shared__ unsigned long long s_tot[SPD_K_MAX * SPD_N_ORDERS];
+    __shared__ float s_png[SPD_KK];
+    __shared__ int s_any[SPD_K_MAX];
+    __shared__ float s_score[SPD_KK];
+    __shared__ int s_valid[SPD_KK];
+    const int tid = threadIdx.x, k = a.k;
+    DevState *st = a.st;
+
+    // global top-k of the slices' candidates
+    const int n_cand = a.n_part * k;
+    float pv = INFINITY;
+    int pi = -1;
+    for (int r = 0; r < k; ++r) {
+        float bv = -INFINITY;
+        int bi = INT_MAX;
+        for (int c = tid; c < n_cand; c += BLOCK) {
+            const int at = (c / k) * SPD_K_MAX + (c % k);
+            const float v = a.pv[at];
+            const int i = a.pi[at];
+            if (better(pv, pi, v, i) && better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        block_best(bv, bi, sv, si);
+        if (tid == 0) { s_top[r] = bi; s_logp[r] = bv; }
+        pv = bv; pi = bi;
+    }
+    if (tid == 0) {
+        float M = -INFINITY;
+        for (int b = 0; b < a.n_part; ++b) M = fmaxf(M, a.pm[b]);
+        float S = 0.f;
+        for (int b = 0; b < a.n_part; ++b) S += a.ps[b] * expf(a.pm[b] - M);
+        s_lse = M + logf(S);
+    }
+    if (tid < SPD_K_MAX) {
+        s_old[tid] = st->logscore[tid];
+        s_any[tid] = 0;
+        for (int q = 0; q < SPD_TAIL; ++q)
+            s_tails[tid][q] = a.first ? st->prefix_tail[q] : st->tails[tid][q];
+    }
+    __syncthreads();
+    if (tid < k) {
+        s_logp[tid] = __fdiv_rn(s_logp[tid], a.tau) - s_lse;
+        st->top_ids[tid] = s_top[tid];
+        st->top_logp[tid] = s_logp[tid];
+    }
+    __syncthreads();
+
+    if (a.first) {  // Section 3, "First Timestep"
+        if (tid < k) {
+            for (int q = 0; q < SPD_TAIL - 1; ++q) st->tails[tid][q] = s_tails[tid][q + 1];
+            st->tails[tid][SPD_TAIL - 1] = s_top[tid];
+            st->logscore[tid] = s_logp[tid];
+            st->new_tok[tid] = s_top[tid];
+            st->new_parent[tid] = -1;
+            a.hist_tok[tid] = s_top[tid];
+            a.hist_par[tid] = -1;
+        }
+        for (int c = tid; c < k * k; c += BLOCK) {
+            st->cand_score[c] = (c < k) ? s_logp[c] : -INFINITY;
+            st->cand_valid[c] = (c < k);
+            st->cand_png[c] = 0.f;
+        }
+    } else {
+        const bool use_ng = a.alpha != 0.0f;
+        if (use_ng) {
+            const int n_probe = k * SPD_N_ORDERS + k * k * SPD_N_ORDERS;
+            for (int e = tid; e < n_probe; e += BLOCK) {
+                int i, j, n;
+                const bool total = e < k * SPD_N_ORDERS;
+                if (total) { i = e / SPD_N_ORDERS; j = 0; n = SPD_MIN_ORDER + e % SPD_N_ORDERS; }
+                else {
+                    const int f = e - k * SPD_N_ORDERS;
+                    i = f / (k * SPD_N_ORDERS); j = (f / SPD_N_ORDERS) % k; n = SPD_MIN_ORDER + f % SPD_N_ORDERS;
+                }
+                unsigned long long res = 0ull;
+                // the last n-1 tokens of the history must all exist
+                if (a.ng.slots != nullptr && a.ng.present[n - SPD_MIN_ORDER] && s_tails[i][SPD_TAIL - (n - 1)] >= 0) {
+                    int32_t key[6];
+#pragma unroll
+                    for (int q = 0; q < 6; ++q) key[q] = NG_PAD;
+                    for (int q = 0; q < n - 1; ++q) key[q] = s_tails[i][SPD_TAIL - (n - 1) + q];
+                    key[n - 1] = total ? NG_TOTAL : s_top[j];
+                    res = ngram_probe(a.ng, key);
+                }
+                if (total) s_tot[i * SPD_N_ORDERS + (n - SPD_MIN_ORDER)] = res;
+                else s_cnt[(i * k + j) * SPD_N_ORDERS + (n - SPD_MIN_ORDER)] = res;
+            }
+            __syncthreads();
+            if (tid < k * k) {  // Eq. 3
+                const int i = tid / k;
+                float acc = 0.f;
+                for (int o = 0; o < SPD_N_ORDERS; ++o) {
+                    const unsigned long long C = s_tot[i * SPD_N_ORDERS + o];
+                    const float p = C ? __fdiv_rn(__ull2float_rn(s_cnt[tid * SPD_N_ORDERS + o]), __ull2float_rn(C)) : 0.f;
+                    acc = __fadd_rn(acc, __fmul_rn(a.ng.lambda[o], p));
+                }
+                s_png[tid] = acc;
+                if (acc > 0.f) atomicOr(&s_any[i], 1);
+            }
+            __syncthreads();
+        }
+        if (tid < k * k) {
+            const int i = tid / k, j = tid % k;
+            float score;
+            int valid = 1;
+            if (!use_ng) {
+                score = __fadd_rn(s_old[i], s_logp[j]);
+            } else {
+                const float lm = __fmul_rn(__fsub_rn(1.0f, a.alpha), s_logp[j]);
+                float lpf;
+                if (s_png[tid] > 0.f) lpf = __fadd_rn(lm, __fmul_rn(a.alpha, logf(s_png[tid])));   // Eq. 4
+                else if (s_any[i]) { lpf = 0.f; valid = 0; }   // token outside the overlap set
+                else lpf = __fadd_rn(logf(a.delta), lm);       // Eq. 5
+                score = __fadd_rn(s_old[i], lpf);
+            }
+            s_score[tid] = valid ? score : -INFINITY;
+            s_valid[tid] = valid;
+            st->cand_score[tid] = s_score[tid];
+            st->cand_valid[tid] = valid;
+            st->cand_png[tid] = use_ng ? s_png[tid] : 0.f;
+        }
+        __syncthreads();
+        if (tid < k * k && s_valid[tid]) {
+            // rank among valid options: score desc, then parent asc, then token rank asc
+            int rank = 0;
+            for (int c = 0; c < k * k; ++c)
+                if (s_valid[c] && better(s_score[c], c, s_score[tid], tid)) ++rank;
+            if (rank < k) {
+                const int i = tid / k, j = tid % k, gen = st->n_gen;
+                for (int q = 0; q < SPD_TAIL - 1; ++q) st->tails[rank][q] = s_tails[i][q + 1];
+                st->tails[rank][SPD_TAIL - 1] = s_top[j];
+                st->logscore[rank] = s_score[tid];
+                st->new_tok[rank] = s_top[j];
+                st->new_parent[rank] = i;
+                if (gen < a.max_gen) {
+                    a.hist_tok[(size_t)gen * SPD_K_MAX + rank] = s_top[j];
+                    a.hist_par[(size_t)gen * SPD_K_MAX + rank] = i;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    __threadfence_block();
+    if (tid == 0) {  // Eq. 2 on the new scores
+        float mx = -INFINITY, sum = 0.f, g[SPD_K_MAX];
+        for (int i = 0; i < k; ++i) mx = fmaxf(mx, st->logscore[i]);
+        for (int i = 0; i < k; ++i) { g[i] = expf(st->logscore[i] - mx); sum += g[i]; }
+        for (int i = 0; i < k; ++i) st->gamma[i] = g[i] / sum;
+        st->k = k;
+        st->n_gen = a.first ? 1 : st->n_gen + 1;
+        if (a.advance) st->pos += 1;
+    }
+}
+
+__global__ void advance_kernel(DevState *st) { st->pos += 1; }
+
+__global__ void renorm_kernel(DevState *st, int k) {
+    float mx = -INFINITY, sum = 0.f, g[SPD_K_MAX];
+    for (int i = 0; i < k; ++i) mx = fmaxf(mx, st->logscore[i]);
+    for (int i = 0; i < k; ++i) { g[i] = expf(st->logscore[i] - mx); sum += g[i]; }
+    for (int i = 0; i < k; ++i) st->gamma[i] = g[i] / sum;
+    st->k = k;
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int32_t v, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+template <typename WT>
+hipError_t gemv_dispatch(hipStream_t s, int epi, const GemvArgs &a, int blocks, size_t lds) {
+    switch (epi) {
+        case EPI_PLAIN: hipLaunchKernelGGL((gemv_kernel<WT, EPI_PLAIN>), dim3(blocks), dim3(BLOCK), lds, s, a); break;
+        case EPI_RESID: hipLaunchKernelGGL((gemv_kernel<WT, EPI_RESID>), dim3(blocks), dim3(BLOCK), lds, s, a); break;
+        case EPI_QKV: hipLaunchKernelGGL((gemv_kernel<WT, EPI_QKV>), dim3(blocks), dim3(BLOCK), lds, s, a); break;
+        case EPI_SWIGLU: hipLaunchKernelGGL((gemv_kernel<WT, EPI_SWIGLU>), dim3(blocks), dim3(BLOCK), lds, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+namespace spdk {
+
+size_t gemv_lds_bytes(int dtype, int cols) {
+    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    const int chunk_cols = GEMV_U * WAVE * vec;
+    return (size_t)((cols + chunk_cols - 1) / chunk_cols) * chunk_cols * sizeof(float);
+}
+
+hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu) {
+    const int units = epi == EPI_SWIGLU ? a.rows : a.rows / 2;
+    int blocks = (units + NWAVE - 1) / NWAVE;
+    const int cap = num_cu * 8;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    const size_t lds = gemv_lds_bytes(dtype, a.cols);
+    if (dtype == SPD_DTYPE_BF16) return gemv_dispatch<bf16_t>(s, epi, a, blocks, lds);
+    return gemv_dispatch<float>(s, epi, a, blocks, lds);
+}
+
+hipError_t attention(hipStream_t s, int dtype, const AttnArgs &a) {
+    const dim3 grid(a.n_kv_heads, a.max_splits);
+    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    const int lpp = a.d_head / vec;
+    const size_t lds = (size_t)(BLOCK / lpp) * a.d_head * sizeof(float);
+    if (dtype == SPD_DTYPE_BF16) hipLaunchKernelGGL(attn_kernel<bf16_t>, grid, dim3(BLOCK), lds, s, a);
+    else hipLaunchKernelGGL(attn_kernel<float>, grid, dim3(BLOCK), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t superpose(hipStream_t s, int dtype, const SuperposeArgs &a) {
+    const int blocks = (a.d_model + BLOCK - 1) / BLOCK;
+    if (dtype == SPD_DTYPE_BF16) hipLaunchKernelGGL(superpose_kernel<bf16_t>, dim3(blocks), dim3(BLOCK), 0, s, a);
+    else hipLaunchKernelGGL(superpose_kernel<float>, dim3(blocks), dim3(BLOCK), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t topk_partial(hipStream_t s, const TopkArgs &a) {
+    hipLaunchKernelGGL(topk_partial_kernel, dim3(a.n_part), dim3(BLOCK), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t expand_prune(hipStream_t s, const ExpandArgs &a) {
+    hipLaunchKernelGGL(expand_prune_kernel, dim3(1), dim3(BLOCK), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t advance(hipStream_t s, DevState *st) {
+    hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, st);
+    return hipGetLastError();
+}
+
+hipError_t renorm(hipStream_t s, DevState *st, int k) {
+    hipLaunchKernelGGL(renorm_kernel, dim3(1), dim3(1), 0, s, st, k);
+    return hipGetLastError();
+}
+
+hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n) {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+hipError_t init() {
+    const int big = 160 * 1024 - 256;
+    hipError_t e = hipSuccess;
+#define SPD_SET(K) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, big)
+    SPD_SET((gemv_kernel<bf16_t, EPI_PLAIN>)); SPD_SET((gemv_kernel<bf16_t, EPI_RESID>));
+    SPD_SET((gemv_kernel<bf16_t, EPI_QKV>)); SPD_SET((gemv_kernel<bf16_t, EPI_SWIGLU>));
+    SPD_SET((gemv_kernel<float, EPI_PLAIN>)); SPD_SET((gemv_kernel<float, EPI_RESID>));
+    SPD_SET((gemv_kernel<float, EPI_QKV>)); SPD_SET((gemv_kernel<float, EPI_SWIGLU>));
+#undef SPD_SET
+    return e;
+}
+
+}  // namespace spdk

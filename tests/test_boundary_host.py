@@ -1,0 +1,80 @@
+"""Host-only checks of the C-ABI boundary: the library loads, exports what the header
+declares, and rejects bad arguments without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2405_18400_amd as P
+    if not os.path.exists(P.library_path()):
+        from paper_2405_18400_amd.build import build_library
+        build_library()
+    return P
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "spd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(pkg):
+    L = pkg.lib()
+    names = declared_functions()
+    assert len(names) >= 20 and "spd_create" in names and "spd_step" in names and "spd_generate" in names
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in spd.h but not exported by libspd.so"
+
+
+def test_workspace_bytes_and_config_validation(pkg):
+    cfg = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)
+    need = pkg.spd_workspace_bytes(cfg)
+    kv = 2 * 32 * 32 * 128 * 128 * 2                      # K and V, 32 layers, 32 heads, 128 positions, d_head 128, bf16
+    assert kv <= need < kv + 4 * 2 ** 20
+    for field, bad in [("dtype", 7), ("n_heads", 3), ("n_kv_heads", 5), ("k_max", 17), ("k_max", 0), ("max_ctx", 1),
+                       ("vocab", 31999), ("d_ffn", 11004), ("d_model", 0)]:
+        c = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)
+        setattr(c, field, bad)
+        with pytest.raises(pkg.SpdError) as e:
+            pkg.spd_workspace_bytes(c)
+        assert e.value.code == -1
+    for shape in (synth.TINY, synth.LLAMA13B, synth.LLAMA70B):
+        assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(shape, 1100, 8)) > 0
+
+
+def test_create_rejects_null_arguments_before_any_gpu_work(pkg):
+    L = pkg.lib()
+    cfg = pkg.binding.model_cfg(synth.TINY, 64, 8)
+    out = C.c_void_p()
+    assert L.spd_create(C.byref(cfg), None, None, 0, None, C.byref(out)) == -1 and not out.value
+    assert L.spd_create(None, None, None, 0, None, C.byref(out)) == -1
+    assert L.spd_create(C.byref(cfg), None, None, 0, None, None) == -1
+    for fn in ("spd_prefill",):
+        assert getattr(L, fn)(None, None, 0) == -1
+    assert L.spd_step(None, None, None, None, None) == -1
+    assert L.spd_position(None, None) == -1
+    assert pkg.spd_strerror(0) == "ok" and "max_ctx" in pkg.spd_strerror(-3)
+
+
+def test_ngram_table_bytes(pkg):
+    t = synth.make_ngram_tables_uniform(100, {2: 300, 3: 200}, seed=0)
+    need = pkg.spd_ngram_table_bytes(t)
+    assert need >= 2 * 500 * 32 and need % 256 == 0     # an entry plus a context total each, 32-byte slots
+    assert pkg.spd_ngram_table_bytes({}) > 0
+
+
+def test_missing_library_fails_loudly(pkg, monkeypatch):
+    import paper_2405_18400_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "library_path", lambda: "/nonexistent/libspd.so")
+    with pytest.raises(ImportError):
+        b.lib()

@@ -1,0 +1,239 @@
+"""End-to-end parity of the HIP path with the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_common import RTOL, compare_step, make_oracle, tails_of, teacher_forced
+from oracle import spd_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def P():
+    import paper_2405_18400_amd as pkg
+    return pkg
+
+
+def session(shape, weights, max_ctx=64, k_max=8):
+    return P().Session(shape, weights, max_ctx=max_ctx, k_max=k_max)
+
+
+def planted_tables(shape, weights, base, prefix, k, n_tokens, seed=0):
+    """Insert n-grams along the paths an alpha = 0 oracle run visits, so lookups hit."""
+    lm = make_oracle(shape, weights)
+    _, recs = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0), n_tokens)
+    visits = []
+    for rec in recs[1:]:
+        for i in range(k):
+            for tok in rec.top_ids:
+                visits.append((tuple(rec.state_in.history(i)), int(tok)))
+    return synth.plant_ngrams(base, visits, shape.vocab, seed=seed, frac=0.5)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    shape = synth.TINY
+    w = synth.make_weights(shape, seed=0)
+    tabs = synth.make_ngram_tables_uniform(shape.vocab, {2: 50_000, 3: 50_000}, seed=0)
+    prefix = synth.make_prefix_uniform(shape.vocab, 16, seed=0)
+    return shape, w, tabs, prefix
+
+
+def run_teacher_forced(shape, w, tabs, lambdas, prefix, k, alpha, n_tokens, tau=1.0, delta=0.1, max_ctx=64):
+    pkg = P()
+    sess = session(shape, w, max_ctx=max_ctx)
+    try:
+        if tabs is not None:
+            sess.spd_load_ngrams(tabs, lambdas)
+        dc = pkg.SpdDecodeCfg(k, alpha, tau, delta)
+        cfg = O.DecodeCfg(k, alpha, tau, delta, tuple(lambdas))
+        lm = make_oracle(shape, w)
+        state, recs, stats = teacher_forced(sess, lm, tabs, lambdas, prefix, cfg, n_tokens, RTOL[shape.dtype], dc)
+        assert sess.spd_position() == len(prefix) + n_tokens - 1
+        return state, recs, stats
+    finally:
+        sess.close()
+
+
+def test_tiny_config_as_specified(tiny):
+    """BASELINE config 1: 2-layer fp32 model, bigram+trigram tables, k = 3, 10 tokens, alpha 0.5."""
+    shape, w, tabs, prefix = tiny
+    lam = (0.01, 0.04, 0.0, 0.0, 0.0)
+    _, recs, stats = run_teacher_forced(shape, w, tabs, lam, prefix, 3, 0.5, 10)
+    assert sum(s.get("vocab_decisive", False) for s in stats) >= 8
+
+
+def test_tiny_config_with_planted_hits(tiny):
+    shape, w, tabs, prefix = tiny
+    lam = (0.01, 0.04, 0.0, 0.0, 0.0)
+    planted = planted_tables(shape, w, tabs, prefix, 3, 10)
+    _, recs, stats = run_teacher_forced(shape, w, planted, lam, prefix, 3, 0.5, 10)
+    assert any(c.overlap for r in recs[1:] for c in r.candidates), "planting produced no n-gram hit"
+    assert any(not c.overlap for r in recs[1:] for c in r.candidates)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 8])
+@pytest.mark.parametrize("alpha", [0.0, 0.54])
+def test_tiny_k_sweep_all_orders(tiny, k, alpha):
+    shape, w, _, prefix = tiny
+    base = synth.make_ngram_tables_zipf(shape.vocab, 40_000, seed=3)
+    planted = planted_tables(shape, w, base, prefix, k, 6, seed=k)
+    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, k, alpha, 6, tau=0.7)
+
+
+def test_bf16_small_model_gqa():
+    shape = synth.ModelShape("small-bf16", 3, 512, 8, 2, 1408, 2048, "bf16")
+    w = synth.make_weights(shape, seed=5)
+    prefix = synth.make_prefix_zipf(shape.vocab, 37, seed=5)
+    base = synth.make_ngram_tables_zipf(shape.vocab, 30_000, seed=5)
+    planted = planted_tables(shape, w, base, prefix, 3, 8)
+    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8)
+
+
+def test_long_prefix_crosses_attention_chunks():
+    shape = synth.ModelShape("small-fp32", 2, 256, 4, 2, 512, 1024, "fp32")
+    w = synth.make_weights(shape, seed=6)
+    prefix = synth.make_prefix_uniform(shape.vocab, 300, seed=6)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=600)
+
+
+def test_generate_free_running_matches_until_first_undecided_step(tiny):
+    shape, w, tabs, prefix = tiny
+    pkg = P()
+    lam = (0.01, 0.04, 0.0, 0.0, 0.0)
+    planted = planted_tables(shape, w, tabs, prefix, 3, 10)
+    sess = session(shape, w)
+    try:
+        sess.spd_load_ngrams(planted, lam)
+        dc = pkg.SpdDecodeCfg(3, 0.5, 1.0, 0.1)
+        drafts, scores = sess.spd_generate(prefix, dc, 10)
+        lm = make_oracle(shape, w)
+        state, recs = O.generate(lm, O.NgramTables(planted), prefix, O.DecodeCfg(3, 0.5, 1.0, 0.1, lam), 10)
+        tol = RTOL["fp32"] * max(float(np.max(np.abs(r.logits))) for r in recs)
+        decided = 0
+        for r in recs:
+            if r.gap_vocab <= 4 * tol or r.gap_prune <= 4 * tol:
+                break
+            decided += 1
+        assert decided >= 5, "synthetic case too close to ties to say anything"
+        if decided == len(recs):
+            assert drafts.tolist() == state.drafts
+            np.testing.assert_allclose(scores, state.logscores, atol=1e-3)
+        # graph replay and plain launches agree bit for bit
+        sess.spd_set_graph(False)
+        drafts2, scores2 = sess.spd_generate(prefix, dc, 10)
+        assert np.array_equal(drafts, drafts2) and np.array_equal(scores, scores2)
+        # and so does a second replayed generation (determinism, counters reset, state reset)
+        sess.spd_set_graph(True)
+        drafts3, scores3 = sess.spd_generate(prefix, dc, 10)
+        assert np.array_equal(drafts, drafts3) and np.array_equal(scores, scores3)
+    finally:
+        sess.close()
+
+
+def test_k1_is_greedy_on_the_gpu(tiny):
+    shape, w, _, prefix = tiny
+    pkg = P()
+    sess = session(shape, w)
+    try:
+        drafts, _ = sess.spd_generate(prefix, pkg.SpdDecodeCfg(1, 0.0, 1.0, 0.1), 8)
+        lm = make_oracle(shape, w)
+        logits = lm.forward(lm.embedding_rows(prefix))
+        for t in range(8):
+            srt = np.sort(logits)[::-1]
+            if srt[0] - srt[1] < 1e-3:
+                break
+            assert drafts[0, t] == int(np.argmax(logits))
+            logits = lm.forward(lm.embedding_rows([int(np.argmax(logits))]))
+    finally:
+        sess.close()
+
+
+def test_expand_prune_on_scripted_logits_with_ties(tiny):
+    """Decision logic alone: crafted logits (exact ties included) fed straight to the
+    post-forward kernels; everything here is integer- or fp32-exact, so results are compared
+    without a gap allowance."""
+    shape, w, tabs, prefix = tiny
+    pkg = P()
+    lam = synth.PAPER_LAMBDAS
+    rng = np.random.default_rng(0)
+    sess = session(shape, w)
+    try:
+        k = 4
+        corpus = rng.integers(0, 12, size=600)
+        from collections import Counter
+        ctabs = {}
+        for n in range(2, 7):
+            c = Counter(tuple(corpus[i:i + n]) for i in range(len(corpus) - n + 1))
+            ctabs[n] = (np.array(list(c.keys()), np.int32).reshape(-1, n), np.array(list(c.values()), np.uint32))
+        sess.spd_load_ngrams(ctabs, lam)
+        otabs = O.NgramTables(ctabs)
+        pre = corpus[:7].astype(np.int32)
+        sess.spd_prefill(pre)
+        for alpha in (0.54, 0.0):
+            dc = pkg.SpdDecodeCfg(k, alpha, 1.0, 0.1)
+            cfg = O.DecodeCfg(k, alpha, 1.0, 0.1, lam)
+            state = None
+            for step in range(6):
+                z = np.full(shape.vocab, -8.0, np.float32)
+                z[:14] = rng.integers(0, 4, size=14).astype(np.float32)      # many exact ties among 14 tokens
+                if state is None:
+                    state, rec = O.first_step(z, pre, cfg)
+                else:
+                    state, rec = O.expand_and_prune(state, z, otabs, cfg)
+                sess.spd_expand_prune(dc, torch.from_numpy(z).cuda(), first=(step == 0))
+                tails, sc, gamma = sess.spd_get_state()
+                ids, lp, cs, cv, cp = sess.spd_get_step_info(k)
+                assert list(ids) == list(rec.top_ids)
+                np.testing.assert_allclose(lp, rec.top_logp, rtol=2e-6)
+                assert np.array_equal(tails, tails_of(state))
+                np.testing.assert_allclose(sc, state.logscores, rtol=1e-5, atol=1e-5)
+                np.testing.assert_allclose(gamma, O.superposition_weights(state.logscores), rtol=1e-5)
+                assert abs(float(gamma.sum()) - 1.0) < 1e-6
+                if step > 0 and alpha > 0:
+                    np.testing.assert_allclose(cp, rec.pngram, rtol=1e-6)
+                    assert rec.pngram.max() > 0
+                # keep both sides on identical scores so ties stay ties
+                sess.spd_set_state(tails_of(state), state.logscores)
+    finally:
+        sess.close()
+
+
+def test_error_paths(tiny):
+    shape, w, tabs, prefix = tiny
+    pkg = P()
+    sess = session(shape, w, max_ctx=20, k_max=4)
+    try:
+        dc = pkg.SpdDecodeCfg(3, 0.0, 1.0, 0.1)
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_step(dc)
+        assert e.value.code == -2
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_prefill(np.arange(20))
+        assert e.value.code == -3
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_prefill([0, shape.vocab])
+        assert e.value.code == -1
+        sess.spd_prefill(prefix)                      # 16 positions of 20
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_step(pkg.SpdDecodeCfg(5, 0.0, 1.0, 0.1))      # k > k_max
+        assert e.value.code == -1
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_step(pkg.SpdDecodeCfg(3, 0.5, 1.0, 0.1))      # alpha > 0 without tables
+        assert e.value.code == -1
+        for _ in range(5):                            # first step + 4 forwards fill the cache
+            sess.spd_step(dc)
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_step(dc)
+        assert e.value.code == -3
+        bad = {2: (np.array([[1, 2], [1, 2]], np.int32), np.array([1, 1], np.uint32))}
+        with pytest.raises(pkg.SpdError) as e:
+            sess.spd_load_ngrams(bad, synth.PAPER_LAMBDAS)
+        assert e.value.code == -5 and "duplicate" in str(e.value)
+        for keys, counts in (([[1, shape.vocab]], [1]), ([[1, 2]], [0])):
+            with pytest.raises(pkg.SpdError) as e:
+                sess.spd_load_ngrams({2: (np.array(keys, np.int32), np.array(counts, np.uint32))}, synth.PAPER_LAMBDAS)
+            assert e.value.code == -5
+    finally:
+        sess.close()
