@@ -140,7 +140,7 @@ __device__ __forceinline__ void gemv_consume(const u32x4 *a, const u32x4 *b, int
 template <typename WT, int EPI>
 __global__ __launch_bounds__(BLOCK) void gemv_kernel(const GemvArgs a) {
     constexpr int VEC = Store<WT>::VEC;
-    extern __shared__ float xs[];           // x, zero-padded to whole chunks
+    extern __shared__ __align__(16) float xs[];   // x, zero-padded to whole chunks
     __shared__ float red[NWAVE];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
     const int cols = a.cols;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(BLOCK) void attn_kernel(const AttnArgs a) {
     constexpr int VEC = Store<KT>::VEC;
     __shared__ float sc[ATTN_CHUNK];
     __shared__ float red[NWAVE];
-    extern __shared__ float dyn[];        // [BLOCK / LPP][dh] partial outputs
+    extern __shared__ __align__(16) float dyn[];   // [BLOCK / LPP][dh] partial outputs
     __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
     const int dh = a.d_head;
@@ -706,14 +706,17 @@ hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n) {
 }
 
 hipError_t init() {
+    // Needed only for rows wider than 64 KB of fp32 x (e.g. d_ffn = 28672); a refusal here
+    // surfaces later as a launch error for exactly those shapes.
     const int big = 160 * 1024 - 256;
     hipError_t e = hipSuccess;
-#define SPD_SET(K) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, big)
+#define SPD_SET(K) (void)hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, big)
     SPD_SET((gemv_kernel<bf16_t, EPI_PLAIN>)); SPD_SET((gemv_kernel<bf16_t, EPI_RESID>));
     SPD_SET((gemv_kernel<bf16_t, EPI_QKV>)); SPD_SET((gemv_kernel<bf16_t, EPI_SWIGLU>));
     SPD_SET((gemv_kernel<float, EPI_PLAIN>)); SPD_SET((gemv_kernel<float, EPI_RESID>));
     SPD_SET((gemv_kernel<float, EPI_QKV>)); SPD_SET((gemv_kernel<float, EPI_SWIGLU>));
 #undef SPD_SET
+    (void)hipGetLastError();
     return e;
 }
 
