@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the Superposed Decoding timestep on one MI355X.
+
+One "step" is one spd_step: superposition weights, superposed embedding, the batch-1
+transformer forward over the KV cache, LM head, vocabulary top-k, k x k expansion, n-gram
+probes, interpolation, prune and state update -- the whole hot path.  Inputs (weights, KV
+cache, n-gram store) are resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `value` is draft-tokens/s = k * steps / time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(shape, ctx_positions: float) -> dict:
+    """Bytes one timestep must move: every streamed weight once plus the cached keys and
+    values of `ctx_positions` positions (not the embedding table: only k rows are read)."""
+    es = 2 if shape.dtype == "bf16" else 4
+    dh = shape.d_head
+    qkv = (shape.n_heads + 2 * shape.n_kv_heads) * dh * shape.d_model * es
+    o = shape.d_model * shape.n_heads * dh * es
+    gateup = 2 * shape.d_ffn * shape.d_model * es
+    down = shape.d_model * shape.d_ffn * es
+    head = shape.vocab * shape.d_model * es
+    kv_pos = 2 * shape.n_layers * shape.n_kv_heads * dh * es
+    return {"gemv_qkv": qkv, "gemv_o": o, "gemv_gateup": gateup, "gemv_down": down, "gemv_head": head,
+            "kv_per_position": kv_pos,
+            "step": shape.n_layers * (qkv + o + gateup + down) + head + kv_pos * ctx_positions}
+
+
+def cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta):
+    """The CPU oracle, as it stands, timed on this host.  A full 7B-shaped step would take
+    minutes in numpy, so the sample is the same step on depth-truncated copies of the model
+    (1 and 3 layers, same tensors): per-layer cost = (t3 - t1) / 2, the rest (embedding mix,
+    final norm, LM head, decision stage with n-gram scans) = t1 - per-layer; a full step is
+    rest + n_layers * per-layer."""
+    import synth
+    from oracle import spd_oracle as O
+
+    def host(name):
+        return synth.host_view(weights[name]) if not isinstance(weights[name], np.ndarray) else weights[name]
+
+    otabs = O.NgramTables(tables)
+    cfg = O.DecodeCfg(k, alpha, tau, delta, tuple(lambdas))
+    short = list(map(int, prefix[:8]))
+    times = {}
+    depths = (1, 3) if shape.n_layers > 3 else (shape.n_layers,)
+    for nl in depths:
+        names = [n for n, _, _ in synth.weight_names(shape.truncated(nl))]
+        w = {n: host(n) for n in names}
+        lm = O.OracleLM(w, nl, shape.n_heads, shape.n_kv_heads, shape.rms_eps, shape.rope_theta)
+        lm.reset()
+        logits = lm.forward(lm.embedding_rows(short))
+        state, _ = O.first_step(logits, short, cfg, keep_logits=False)
+        t0 = time.perf_counter()
+        n_steps = 2
+        for _ in range(n_steps):
+            gamma = O.superposition_weights(state.logscores)
+            x = O.superposed_embedding(lm.embedding_rows([d[-1] for d in state.drafts]), gamma.astype(np.float32))
+            logits = lm.forward(x[None, :])
+            state, _ = O.expand_and_prune(state, logits, otabs, cfg, keep_logits=False)
+        times[nl] = (time.perf_counter() - t0) / n_steps
+    if len(depths) == 2:
+        per_layer = max((times[3] - times[1]) / 2, 0.0)
+        rest = max(times[1] - per_layer, 0.0)
+        step_s = rest + shape.n_layers * per_layer
+    else:
+        per_layer, rest, step_s = 0.0, times[depths[0]], times[depths[0]]
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": k / step_s, "unit": "draft-tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"2 timed oracle steps each on 1- and 3-layer truncations of the {shape.name} model "
+                      f"(same tensors, same n-gram tables, 8-token prefix); per-layer {per_layer * 1e3:.1f} ms, "
+                      f"rest {rest * 1e3:.1f} ms, extrapolated to {shape.n_layers} layers = {step_s * 1e3:.0f} ms/step",
+            "ms_per_step": step_s * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="7b", choices=["7b", "tiny", "13b", "70b"])
+    ap.add_argument("--prefix", type=int, default=None)
+    ap.add_argument("--k", type=int, default=3)
+    ap.add_argument("--ngram-entries", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the SPD step is a single-GPU, batch-1 path); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2405_18400_amd as pkg
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    shape = {"7b": synth.LLAMA7B, "tiny": synth.TINY, "13b": synth.LLAMA13B, "70b": synth.LLAMA70B}[args.workload]
+    m = args.prefix or {"7b": 64, "tiny": 16, "13b": 256, "70b": 512}[args.workload]
+    entries = args.ngram_entries or {"7b": 10_000_000, "tiny": 100_000, "13b": 50_000_000, "70b": 10_000_000}[args.workload]
+    k, alpha, tau, delta = args.k, 0.54, 1.0, 0.1
+    lambdas = synth.PAPER_LAMBDAS
+    K, W = args.steps, args.warmup
+    max_ctx = m + W + K + 2
+
+    t_setup = time.time()
+    if shape.dtype == "bf16":
+        weights = synth.make_weights_device(shape, seed=0)
+    else:
+        weights = synth.make_weights(shape, seed=0)
+    if args.workload == "tiny":
+        tables = synth.make_ngram_tables_uniform(shape.vocab, {2: entries // 2, 3: entries // 2}, seed=0)
+        prefix = synth.make_prefix_uniform(shape.vocab, m, seed=0)
+    else:
+        tables = synth.make_ngram_tables_zipf(shape.vocab, entries, seed=0)
+        prefix = synth.make_prefix_zipf(shape.vocab, m, seed=0)
+    sess = pkg.Session(shape, weights, max_ctx=max_ctx, k_max=max(k, 8))
+    sess.spd_load_ngrams(tables, lambdas)
+    if args.no_graph:
+        sess.spd_set_graph(False)
+    dc = pkg.SpdDecodeCfg(k, alpha, tau, delta)
+    t_setup = time.time() - t_setup
+
+    def run(n_steps):
+        for _ in range(n_steps):
+            sess.spd_step(dc, fetch=False)
+
+    # prefill + first timestep + warm-up (captures the step graph), untimed
+    sess.spd_prefill(prefix)
+    sess.spd_step(dc, fetch=False)
+    run(W)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(sess.stream):
+        ev0.record(sess.stream)
+        run(K)
+        ev1.record(sess.stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / K
+    tok, par, sc = sess.spd_step(dc)          # one fetched step: the run produced finite drafts
+    assert np.all(np.isfinite(sc)) and len(set(zip(par.tolist(), tok.tolist()))) == k
+
+    ctx_mean = m + W + 1 + (K - 1) / 2.0  # cached positions read by the average timed step
+    ab = algorithmic_bytes(shape, ctx_mean)
+    step_gbs = ab["step"] / (ms_per_step * 1e-3) / 1e9
+
+    # per-kernel durations with HIP events on the library's stream (plain launches, same steps)
+    roofline = {"bound": "hbm", "kernel": "spd_step (all kernels)", "achieved": step_gbs, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS, "traffic": None}
+    kernels = {}
+    if not args.no_kernel_timing:
+        sess.spd_prefill(prefix)
+        sess.spd_step(dc, fetch=False)
+        run(W)
+        sess.spd_set_kernel_timing(True)
+        run(min(K, 32))
+        timing = sess.spd_get_kernel_timing()
+        sess.spd_set_kernel_timing(False)
+        for name, (ms, n) in timing.items():
+            if n:
+                kernels[name] = {"avg_us": ms * 1e3 / n, "launches_per_step": n / min(K, 32)}
+                if name in ab:
+                    kernels[name]["GBps"] = ab[name] / (ms * 1e-3 / n) / 1e9
+        dom = "gemv_gateup"
+        if dom in kernels:
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                        "bytes_per_launch": ab[dom], "avg_launch_us": kernels[dom]["avg_us"],
+                        "step_achieved": step_gbs, "step_frac": step_gbs / HBM_PEAK_GBS,
+                        "step_bytes": ab["step"]}
+
+    # k independent batch-1 passes on the same GPU (k = 1 SPD = greedy): k x the step time of k = 1
+    dc1 = pkg.SpdDecodeCfg(1, 0.0, tau, delta)
+    sess.spd_prefill(prefix)
+    sess.spd_step(dc1, fetch=False)
+    run1 = lambda n: [sess.spd_step(dc1, fetch=False) for _ in range(n)]
+    run1(W)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run1(K)
+    torch.cuda.synchronize()
+    greedy_ms = (time.perf_counter() - t1) * 1e3 / K
+
+    # end-to-end generation as the paper times it: prefix pass + 10 tokens
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    drafts, scores = sess.spd_generate(prefix, dc, 10)
+    e2e_ms = (time.perf_counter() - t2) * 1e3
+
+    out = {
+        "metric": "draft-tokens/sec at k=3 (7B-shape bf16, batch 1); % of peak HBM GB/s",
+        "value": k * K / wall, "unit": "draft-tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}, random-init N(0,0.02), prefix {m} Zipf tokens, k={k}, "
+                               f"alpha={alpha}, tau={tau}, delta={delta}, n-gram tables n=2..6 with "
+                               f"{sum(len(v[1]) for v in tables.values())} entries; {K} consecutive timesteps "
+                               f"(context {m + 1 + W}..{m + W + K})",
+                   "k": k, "prefix": m, "graph": not args.no_graph},
+        "pct_peak_hbm": 100.0 * step_gbs / HBM_PEAK_GBS,
+        "gpu_ms_per_step_events": gpu_ms / K,
+        "roofline": roofline,
+        "kernels": kernels,
+        "k_independent_passes": {"ms_per_pass_step": greedy_ms, "ms_for_k_drafts": k * greedy_ms,
+                                 "speedup_of_spd": k * greedy_ms / ms_per_step, "kind": "k greedy (k=1) passes"},
+        "generate_10_tokens_ms": e2e_ms,
+        "setup_s": t_setup,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta)
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -142,9 +142,13 @@ def _torch():
     return torch
 
 
-def to_device(arr: np.ndarray, dtype: str, device="cuda"):
-    """Host array -> device tensor holding the same bits (uint16 patterns become bfloat16)."""
+def to_device(arr, dtype: str, device="cuda"):
+    """Host array -> device tensor holding the same bits (uint16 patterns become bfloat16).
+    Tensors already on the device pass through."""
     torch = _torch()
+    if isinstance(arr, torch.Tensor):
+        assert arr.dtype == (torch.bfloat16 if dtype == "bf16" else torch.float32)
+        return arr.to(device).contiguous()
     if dtype == "bf16":
         assert arr.dtype == np.uint16
         return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
@@ -167,7 +171,9 @@ class Session:
         self.layers = (SpdLayerWeights * max(shape.n_layers, 1))()
         for l in range(shape.n_layers):
             p = f"layers.{l}."
-            qkv = np.concatenate([weights[p + "wq"], weights[p + "wk"], weights[p + "wv"]], axis=0)
+            qkv = weights.get(p + "wqkv")
+            if qkv is None:
+                qkv = np.concatenate([weights[p + "wq"], weights[p + "wk"], weights[p + "wv"]], axis=0)
             names = {"attn_norm": weights[p + "attn_norm"], "wqkv": qkv, "wo": weights[p + "wo"],
                      "ffn_norm": weights[p + "ffn_norm"], "w_gate": weights[p + "w_gate"],
                      "w_up": weights[p + "w_up"], "w_down": weights[p + "w_down"]}

@@ -18,7 +18,7 @@ import numpy as np
 
 __all__ = [
     "ModelShape", "TINY", "LLAMA7B", "LLAMA13B", "LLAMA70B", "bf16_bits", "bf16_widen",
-    "make_weights", "weight_names", "zipf_token_sampler", "make_ngram_tables_uniform",
+    "make_weights", "make_weights_device", "host_view", "weight_names", "zipf_token_sampler", "make_ngram_tables_uniform",
     "make_ngram_tables_zipf", "plant_ngrams", "make_prefix_uniform", "make_prefix_zipf",
     "PAPER_LAMBDAS", "ORDER_SHARE",
 ]
@@ -142,6 +142,50 @@ def make_weights(shape: ModelShape, seed: int = 0, threads: int = 8,
         return dict(job(s) for s in specs)
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return dict(ex.map(job, specs))
+
+
+def make_weights_device(shape: ModelShape, seed: int = 0, device: str = "cuda") -> dict:
+    """Same tensor set drawn on the GPU with torch's seeded generator (one seed per tensor),
+    for shapes too large to draw on the host in reasonable time.  Returns torch tensors in
+    the storage dtype, with q/k/v of a layer stored as one fused `wqkv` matrix and
+    `wq`/`wk`/`wv` as row-slice views of it.  `host_view` turns any of them into the numpy
+    array format `make_weights` returns (bf16 as uint16 bit patterns)."""
+    import torch
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    out = {}
+    dh = shape.d_head
+    nq, nkv = shape.n_heads * dh, shape.n_kv_heads * dh
+
+    def draw(name, shp, kind):
+        if kind == "ones":
+            return torch.ones(shp, dtype=tdt, device=device)
+        g = torch.Generator(device=device)
+        g.manual_seed((seed << 32) ^ zlib.crc32(name.encode()))
+        x = torch.empty(shp, dtype=torch.float32, device=device)
+        x.normal_(0.0, shape.init_std, generator=g)
+        return x.to(tdt)
+
+    for name, shp, kind in weight_names(shape):
+        base = name.rsplit(".", 1)[-1]
+        if base in ("wk", "wv"):
+            continue
+        if base == "wq":
+            p = name[:-2]
+            fused = draw(p + "wqkv", (nq + 2 * nkv, shape.d_model), kind)
+            out[p + "wqkv"] = fused
+            out[p + "wq"], out[p + "wk"], out[p + "wv"] = fused[:nq], fused[nq:nq + nkv], fused[nq + nkv:]
+        else:
+            out[name] = draw(name, shp, kind)
+    return out
+
+
+def host_view(t) -> np.ndarray:
+    """torch tensor (any device) -> numpy array in make_weights' format."""
+    import torch
+    t = t.detach().contiguous().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
 
 
 # ----------------------------------------------------------------------------- token draws
