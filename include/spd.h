@@ -182,6 +182,14 @@ int spd_position(const spd_ctx *ctx, int32_t *out_pos);
 /* Turn the captured-graph replay of spd_step on (default) or off (plain launches). */
 int spd_set_graph(spd_ctx *ctx, int32_t enable);
 
+/* The transformer forward of a timestep runs either as one persistent kernel ("fused": the
+ * default wherever an instantiation exists for the model shape) or as one kernel per
+ * matrix-vector product.  Both compute the same thing; spd_set_fused switches between them
+ * (SPD_EINVAL when asked for a fused kernel the shape has none for), spd_get_fused tells
+ * which one runs. */
+int spd_set_fused(spd_ctx *ctx, int32_t enable);
+int spd_get_fused(const spd_ctx *ctx, int32_t *out_enabled);
+
 /* Per-kernel timing for profiling runs: when enabled, spd_step launches kernels one by one
  * with a HIP event pair around each and accumulates the elapsed time per kernel class.
  * spd_get_kernel_timing fills HOST arrays of up to `cap` entries (class name pointers valid
@@ -189,6 +197,13 @@ int spd_set_graph(spd_ctx *ctx, int32_t enable);
 int spd_set_kernel_timing(spd_ctx *ctx, int32_t enable);
 int spd_get_kernel_timing(spd_ctx *ctx, int32_t cap, const char **out_names, float *out_ms,
                           int64_t *out_launches, int32_t *out_n);
+
+/* While kernel timing is on, the fused forward kernel records a 100 MHz clock stamp of its
+ * block 0 before and after each of its device-wide barriers (and at its end):
+ * stamp[2i] = arrival at barrier i, stamp[2i+1] = release, i = 0 .. 5 n_layers (barrier 0
+ * follows the input phase; each layer then has QKV, attention, O, gate/up, down).  Copies the
+ * stamps of the most recent fused forward to HOST memory; *out_n = 2 (5 n_layers + 2). */
+int spd_get_phase_clock(spd_ctx *ctx, int32_t cap, int64_t *out_stamps, int32_t *out_n);
 
 /* ---- stand-alone operators (the kernels of one timestep, callable one at a time) ---- */
 

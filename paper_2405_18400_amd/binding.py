@@ -75,6 +75,9 @@ def lib():
             "spd_position": [vp, C.POINTER(i32)],
             "spd_set_graph": [vp, i32],
             "spd_set_kernel_timing": [vp, i32],
+            "spd_get_phase_clock": [vp, i32, C.POINTER(C.c_int64), C.POINTER(i32)],
+            "spd_set_fused": [vp, i32],
+            "spd_get_fused": [vp, C.POINTER(i32)],
             "spd_get_kernel_timing": [vp, i32, C.POINTER(C.c_char_p), C.POINTER(f32), C.POINTER(C.c_int64), C.POINTER(i32)],
             "spd_op_gemv": [i32, vp, vp, f32, vp, vp, vp, i32, i32, vp],
             "spd_op_swiglu": [i32, vp, vp, vp, f32, vp, vp, i32, i32, vp],
@@ -275,6 +278,14 @@ class Session:
     def spd_set_graph(self, enable: bool):
         self._chk(self.L.spd_set_graph(self.ctx, int(enable)), "spd_set_graph")
 
+    def spd_set_fused(self, enable: bool):
+        self._chk(self.L.spd_set_fused(self.ctx, int(enable)), "spd_set_fused")
+
+    def spd_get_fused(self) -> bool:
+        out = C.c_int32(0)
+        self._chk(self.L.spd_get_fused(self.ctx, C.byref(out)), "spd_get_fused")
+        return bool(out.value)
+
     def spd_set_kernel_timing(self, enable: bool):
         self._chk(self.L.spd_set_kernel_timing(self.ctx, int(enable)), "spd_set_kernel_timing")
 
@@ -283,6 +294,12 @@ class Session:
         names, ms, cnt, n = (C.c_char_p * cap)(), (C.c_float * cap)(), (C.c_int64 * cap)(), C.c_int32(0)
         self._chk(self.L.spd_get_kernel_timing(self.ctx, cap, names, ms, cnt, C.byref(n)), "spd_get_kernel_timing")
         return {names[i].decode(): (ms[i], cnt[i]) for i in range(n.value)}
+
+    def spd_get_phase_clock(self):
+        cap = 2 * (5 * self.shape.n_layers + 2)
+        out, n = (C.c_int64 * cap)(), C.c_int32(0)
+        self._chk(self.L.spd_get_phase_clock(self.ctx, cap, out, C.byref(n)), "spd_get_phase_clock")
+        return np.array(out[:n.value], dtype=np.int64)
 
     def synchronize(self):
         self.stream.synchronize()

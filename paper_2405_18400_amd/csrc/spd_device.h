@@ -1,0 +1,315 @@
+// Device-side helpers shared by the HIP kernels of libspd (gfx950, wave64).
+#pragma once
+#include "spd_internal.h"
+
+#include <climits>
+#include <cmath>
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace spdd {
+
+constexpr int WAVE = 64;
+
+// ------------------------------------------------------------------ storage types
+struct bf16_t { uint16_t b; };
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+    static constexpr int VEC = 4;  // elements per 16-byte load
+    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ float load1(const void *p, size_t i) { return ((const float *)p)[i]; }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) { ((float *)p)[i] = v; }
+    static __device__ __forceinline__ void store1_coherent(void *p, size_t i, float v) {
+        __hip_atomic_store((float *)p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
+template <> struct Store<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ float load1(const void *p, size_t i) {
+        return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
+    }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) {
+        uint32_t u = __float_as_uint(v);               // round to nearest even
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        ((uint16_t *)p)[i] = (uint16_t)(u >> 16);
+    }
+    static __device__ __forceinline__ void store1_coherent(void *p, size_t i, float v) {
+        uint32_t u = __float_as_uint(v);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        __hip_atomic_store((uint16_t *)p + i, (uint16_t)(u >> 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
+
+__device__ __forceinline__ u32x4 stream_load16(const void *p) {
+    return __builtin_nontemporal_load((const u32x4 *)p);   // weights are read once per step
+}
+
+// Read data another workgroup (possibly on another XCD, behind another L2) wrote and
+// published with a device-scope fence.
+__device__ __forceinline__ float coherent_load(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Activation traffic between workgroups.  COH = true (the persistent kernel): stores go
+// through to memory and loads come from there (device-scope relaxed atomics, the `sc1`
+// forms), so producers and consumers on different XCDs never need an L2 write-back or
+// invalidate.  COH = false (one kernel per operator): ordinary accesses; the kernel boundary
+// orders them.
+template <bool COH> __device__ __forceinline__ float act_load(const float *p) {
+    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+template <bool COH> __device__ __forceinline__ void act_store(float *p, float v) {
+    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+// Sum over the block in a fixed order; every thread gets the result. `red` has NT/64 floats.
+template <int NT>
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    constexpr int NWAVE = NT / WAVE;
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVE; ++w) t += red[w];
+    return t;
+}
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float *red) {
+    constexpr int NWAVE = NT / WAVE;
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) t = fmaxf(t, red[w]);
+    return t;
+}
+
+
+// ------------------------------------------------------------------ GEMV epilogues
+// What happens to the two finished dot products of one work unit (a row pair, or for
+// EPI_SWIGLU row `unit` of the gate and of the up matrix).
+// cos/sin of pos * theta^(-2i/d_head), computed in double as the reference does.
+__device__ __forceinline__ float2 rope_cos_sin(const double *inv_freq, int i, int pos) {
+    const double ang = (double)pos * inv_freq[i];
+    return make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// ROPE_TABLE: take (cos, sin) from the table `rope` [d_head / 2] for this position instead
+// of evaluating the angle on the spot.
+template <typename WT, int EPI, bool ROPE_TABLE = false, bool COH = false>
+__device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float acc0, float acc1, int pos,
+                                              const float2 *rope = nullptr) {
+    if (EPI == EPI_PLAIN) {
+        act_store<COH>(a.y + 2 * unit, acc0);
+        act_store<COH>(a.y + 2 * unit + 1, acc1);
+    } else if (EPI == EPI_RESID) {
+        act_store<COH>(a.y + 2 * unit, act_load<COH>(a.resid + 2 * unit) + acc0);
+        act_store<COH>(a.y + 2 * unit + 1, act_load<COH>(a.resid + 2 * unit + 1) + acc1);
+    } else if (EPI == EPI_SWIGLU) {
+        act_store<COH>(a.y + unit, acc0 / (1.0f + expf(-acc0)) * acc1);
+    } else {  // EPI_QKV: rotary on q and k pairs, append k and v to the cache
+        const int r0 = 2 * unit;
+        if (r0 < a.n_q_rows + a.n_kv_rows) {
+            const int i = (r0 % a.d_head) / 2;
+            const float2 cs = ROPE_TABLE ? make_float2(act_load<COH>(&rope[i].x), act_load<COH>(&rope[i].y))
+                                         : rope_cos_sin(a.inv_freq, i, pos);
+            const float c = cs.x, s = cs.y;
+            const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
+            const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));
+            if (r0 < a.n_q_rows) {
+                act_store<COH>(a.y + r0, e);
+                act_store<COH>(a.y + r0 + 1, o);
+            } else {
+                const int rr = r0 - a.n_q_rows;
+                const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+                if (COH) { Store<WT>::store1_coherent(a.kcache, at, e); Store<WT>::store1_coherent(a.kcache, at + 1, o); }
+                else { Store<WT>::store1(a.kcache, at, e); Store<WT>::store1(a.kcache, at + 1, o); }
+            }
+        } else {
+            const int rr = r0 - a.n_q_rows - a.n_kv_rows;
+            const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+            if (COH) { Store<WT>::store1_coherent(a.vcache, at, acc0); Store<WT>::store1_coherent(a.vcache, at + 1, acc1); }
+            else { Store<WT>::store1(a.vcache, at, acc0); Store<WT>::store1(a.vcache, at + 1, acc1); }
+        }
+    }
+}
+
+// VEC consecutive cache elements starting at element index `at`; `fresh` marks the row that
+// another workgroup wrote earlier in the same launch.
+template <typename KT, bool COH>
+__device__ __forceinline__ void load_row_piece(const char *base, size_t at, bool fresh, float *f) {
+    constexpr int VEC = Store<KT>::VEC;
+    if (COH && fresh) {
+        const uint32_t *p = (const uint32_t *)(base + at * sizeof(KT));
+        u32x4 v;
+        v.x = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        Store<KT>::unpack(v, f);
+    } else {
+        Store<KT>::unpack(*(const u32x4 *)(base + at * sizeof(KT)), f);
+    }
+    (void)VEC;
+}
+
+// ------------------------------------------------------------------ single-query attention
+// One work item = (key/value head g, context chunk s) handled by a block of NT threads.  All
+// query heads sharing head g are served from the chunk.  Chunks are merged by whichever block
+// finishes last for a head, walking the partial results in chunk order (deterministic).
+// LDS: sc[ATTN_CHUNK], red[NT/64], dyn[NT * VEC] floats, one int.
+// COH: q, the newest cache row (written earlier in the same launch) and the outputs use
+// the coherent access forms.
+template <typename KT, int NT, bool COH = false>
+__device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
+                                          float *dyn, int *s_last) {
+    constexpr int VEC = Store<KT>::VEC;
+    constexpr int NWAVE = NT / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
+    const int dh = a.d_head;
+    const int LPP = dh / VEC;             // lanes per cached position
+    const int PPW = WAVE / LPP;           // positions per wave per iteration
+    const int PPB = PPW * NWAVE;
+    const int sub = lane / LPP, li = lane % LPP;
+    const int t0 = s * a.chunk;
+    const int t1 = min(n_ctx, t0 + a.chunk);
+    const int n_splits = (n_ctx + a.chunk - 1) / a.chunk;
+    const int group = a.n_heads / a.n_kv_heads;
+    const float scale = 1.0f / sqrtf((float)dh);
+    const char *Kg = (const char *)a.K + (size_t)g * a.cap_ctx * dh * sizeof(KT);
+    const char *Vg = (const char *)a.V + (size_t)g * a.cap_ctx * dh * sizeof(KT);
+
+    for (int hq = 0; hq < group; ++hq) {
+        const int h = g * group + hq;
+        float qv[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qv[v] = act_load<COH>(a.q + (size_t)h * dh + li * VEC + v);
+        float lmax = -INFINITY;
+        for (int t = t0 + wid * PPW + sub; t - sub < t1; t += PPB) {   // t - sub is wave-uniform
+            float d = 0.f;
+            if (t < t1) {
+                float kf[VEC];
+                load_row_piece<KT, COH>(Kg, (size_t)t * dh + li * VEC, t == n_ctx - 1, kf);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
+            }
+            for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
+            d *= scale;
+            if (t < t1) {
+                if (li == 0) sc[t - t0] = d;
+                lmax = fmaxf(lmax, d);
+            }
+        }
+        const float m = block_max<NT>(lmax, red);   // includes a barrier after the sc writes
+        float lsum = 0.f;
+        for (int t = tid; t < t1 - t0; t += NT) {
+            const float p = expf(sc[t] - m);
+            sc[t] = p;
+            lsum += p;
+        }
+        const float l = block_sum<NT>(lsum, red);
+        float acc[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+        for (int t = t0 + wid * PPW + sub; t < t1; t += PPB) {
+            float vf[VEC];
+            load_row_piece<KT, COH>(Vg, (size_t)t * dh + li * VEC, t == n_ctx - 1, vf);
+            const float p = sc[t - t0];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
+        __syncthreads();
+        float o = 0.f;
+        if (tid < dh) {
+            for (int r = 0; r < PPB; ++r) o += dyn[(size_t)r * dh + tid];
+        }
+        if (n_splits == 1) {
+            if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, o / l);
+        } else {
+            float *pp = a.part + ((size_t)h * a.max_splits + s) * (dh + 2);
+            if (tid < dh) act_store<COH>(pp + 2 + tid, o);
+            if (tid == 0) { act_store<COH>(pp, m); act_store<COH>(pp + 1, l); }
+            if (COH) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // write-through stores acknowledged
+            else __threadfence();
+            __syncthreads();
+            if (tid == 0) {
+                const int old = atomicAdd(&a.counters[h], 1);
+                *s_last = (old == n_splits - 1);
+            }
+            __syncthreads();
+            if (*s_last) {
+                if (!COH) __threadfence();
+                const float *ph = a.part + (size_t)h * a.max_splits * (dh + 2);
+                float M = -INFINITY;
+                for (int q = 0; q < n_splits; ++q) M = fmaxf(M, coherent_load(ph + (size_t)q * (dh + 2)));
+                float L = 0.f, O = 0.f;
+                for (int q = 0; q < n_splits; ++q) {
+                    const float *pq = ph + (size_t)q * (dh + 2);
+                    const float w = expf(coherent_load(pq) - M);
+                    L += w * coherent_load(pq + 1);
+                    if (tid < dh) O += w * coherent_load(pq + 2 + tid);
+                }
+                if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
+                if (tid == 0) a.counters[h] = 0;
+            }
+        }
+        __syncthreads();   // sc / dyn / s_last are reused by the next query head or item
+    }
+}
+
+// ------------------------------------------------------------------ superposed embedding
+// Section 3.1: gamma_i = p_i / sum_j p_j (from log p_i), x~ = sum_i gamma_i z_i, element c.
+// mode 0 feeds a prefix token's own embedding (gamma = 1) during the prefix pass.
+template <typename WT, bool COH = false>
+__device__ __forceinline__ void superpose_element(const SuperposeArgs &a, int c, int pos) {
+    if (a.mode == 0) {
+        const int tok = a.prefix[pos];
+        if (c < a.d_model) act_store<COH>(a.h + c, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c));
+        return;
+    }
+    const int k = a.k;
+    float mx = -INFINITY;
+    for (int i = 0; i < k; ++i) mx = fmaxf(mx, a.st->logscore[i]);
+    float sum = 0.f;
+    for (int i = 0; i < k; ++i) sum += expf(a.st->logscore[i] - mx);
+    float acc = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const float gi = expf(a.st->logscore[i] - mx) / sum;
+        if (c < a.d_model) {
+            const int tok = a.st->tails[i][SPD_TAIL - 1];
+            acc = __fadd_rn(acc, __fmul_rn(gi, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c)));
+        }
+        if (c == 0) a.st->gamma_in[i] = gi;
+    }
+    if (c < a.d_model) act_store<COH>(a.h + c, acc);
+}
+
+}  // namespace spdd

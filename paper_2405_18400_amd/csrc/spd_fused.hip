@@ -1,0 +1,364 @@
+// The whole transformer forward of one SPD timestep as ONE persistent kernel.
+//
+// Batch-1 decode is a chain of ~160 small matrix-vector products (7B shape: 33-180 MB each,
+// 6-30 us at HBM speed), every one of which needs the complete output of its predecessor.
+// Launching them one by one leaves HBM idle at every boundary, so here a grid that exactly
+// fills the chip walks through all phases itself and meets at a device-wide barrier between
+// phases.  The weights a block needs for its first tile of the NEXT phase do not depend on
+// any activation, so they are requested before the barrier and are in flight while the block
+// waits: the weight stream from HBM does not stop at phase boundaries.
+//
+// Phase GEMV ("row-contiguous"): the NW waves of a block read one matrix row side by side
+// (wave w takes columns [(p*NW + w)*64*VEC, +64*VEC) of pass p), so the slice of x a lane
+// multiplies with is fixed and lives in registers; a tile is U rows, partial sums meet in LDS.
+#include "spd_device.h"
+
+using namespace spdd;
+
+namespace {
+
+constexpr int NT = 512;           // threads per block
+constexpr int NW = NT / WAVE;     // waves per block
+constexpr unsigned SPIN_LIMIT = 1u << 22;
+
+struct FusedShared {
+    float part[2][8][NW];         // [buffer][tile slot][wave]
+    float red[NW];
+    float sc[ATTN_CHUNK];
+    int s_last;
+};
+
+// Device-wide barrier: arrival counter in device memory, monotonically increasing within a
+// launch (the host-side sequence resets it between launches).  Bounded: if the grid is not
+// co-resident the wait gives up, raises st->err and every later wait returns at once, so the
+// kernel always drains.
+__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned target, int *err) {
+    // Everything other blocks will read was stored with write-through (device-scope) stores
+    // and every wave has waited for its own stores (wait_stores) before getting here.
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(1);
+            ++spins;
+            if ((spins & 255u) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+            if (spins > SPIN_LIMIT) {
+                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+        }
+    }
+    __syncthreads();   // readers use device-scope loads, so no cache invalidate is needed
+}
+
+// Wait until this wave's stores have been acknowledged.  Called before the next phase's
+// weights are requested, so it never waits for those.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Units [lo, hi) of n that block b of G owns (contiguous, balanced to within one unit).
+__device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &hi) {
+    // n * (b + 1) stays below 2^32 for every supported shape (n <= 2^21 units, G <= 2^10 blocks)
+    lo = (int)(((unsigned)n * (unsigned)b) / (unsigned)G);
+    hi = (int)(((unsigned)n * (unsigned)(b + 1)) / (unsigned)G);
+}
+
+// A phase keeps ONE tile of U rows x P passes (NS = U * P 16-byte pieces per lane) in
+// registers.  The moment a piece has been multiplied in, its register is re-used for the same
+// piece of the block's next tile, so a wave always has about NS loads in flight; after the
+// last tile the first tile of the NEXT phase is requested, before the device-wide barrier.
+// Loads are never predicated: a row past the block's range re-reads the last valid row and a
+// column past the row end re-reads the row's last 16 bytes (x is zero there), which costs
+// cache hits, not HBM traffic, and keeps the inner loop free of branches.
+template <typename WT, int P, int U, int EPI, int NBUF>
+struct Gemv {
+    static constexpr int VEC = Store<WT>::VEC;
+    static constexpr int UT = U / 2;   // units per tile
+    static constexpr int NS = U * P;
+    static_assert(U % 2 == 0 && NS <= NBUF && U <= 8, "tile does not fit the register window");
+
+    static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
+
+    // Byte offset of this lane's piece of pass p within a row.
+    static __device__ __forceinline__ uint32_t col_offset(const GemvArgs &a, int p) {
+        const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+        const int c = ((p * NW + w) * WAVE + lane) * VEC;
+        return (uint32_t)min(c, a.cols - VEC) * (uint32_t)sizeof(WT);
+    }
+
+    // Piece q = s * P + p of the tile starting at unit u0 of a block whose range ends at u_end.
+    static __device__ __forceinline__ u32x4 piece(const GemvArgs &a, int u0, int u_end, int q, const uint32_t (&coff)[P]) {
+        const int s = q / P, p = q % P;
+        const int unit = min(u0 + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
+        const size_t row_bytes = (size_t)a.cols * sizeof(WT);
+        const char *base;
+        if (EPI == EPI_SWIGLU) base = (const char *)(s < UT ? a.W : a.W2) + (size_t)unit * row_bytes;
+        else base = (const char *)a.W + (size_t)(2 * unit + (s & 1)) * row_bytes;
+        return stream_load16(base + coff[p]);
+    }
+
+    // This block's first tile of the phase (requested by the previous phase).
+    static __device__ __forceinline__ void prefetch(const GemvArgs &a, u32x4 (&buf)[NBUF]) {
+        int lo, hi;
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        if (lo >= hi) return;
+        uint32_t coff[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
+    }
+
+    // Runs the phase.  On entry `buf` holds this block's first tile; on return it holds the
+    // block's first tile of phase Next (arguments `na`).
+    template <typename Next>
+    static __device__ __forceinline__ void run(const GemvArgs &a, const GemvArgs &na, int pos, const float2 *rope,
+                                               FusedShared &sh, u32x4 (&buf)[NBUF]) {
+        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+        int lo, hi;
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        if (lo < hi) {
+            // this lane's slice of x (RMS-normalised when a gain is given)
+            float xr[P][VEC];
+            uint32_t coff[P];
+            float ss = 0.f;
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int c = ((p * NW + w) * WAVE + lane) * VEC;
+                coff[p] = col_offset(a, p);
+#pragma unroll
+                for (int v = 0; v < VEC; v += 4) {
+                    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (c < a.cols) {
+                        t.x = act_load<true>(a.x + c + v); t.y = act_load<true>(a.x + c + v + 1);
+                        t.z = act_load<true>(a.x + c + v + 2); t.w = act_load<true>(a.x + c + v + 3);
+                    }
+                    xr[p][v] = t.x; xr[p][v + 1] = t.y; xr[p][v + 2] = t.z; xr[p][v + 3] = t.w;
+                    ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+                }
+            }
+            if (a.gain != nullptr) {
+                const float tot = block_sum<NT>(ss, sh.red);
+                const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const int c = ((p * NW + w) * WAVE + lane) * VEC;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v)
+                        if (c < a.cols) xr[p][v] = xr[p][v] * rs * Store<WT>::load1(a.gain, c + v);
+                }
+            }
+            int pb = 0;
+            for (int u0 = lo; u0 < hi; u0 += UT) {
+                const bool more = u0 + UT < hi;
+#pragma unroll
+                for (int s = 0; s < U; ++s) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int p = 0; p < P; ++p) {
+                        float f[VEC];
+                        Store<WT>::unpack(buf[s * P + p], f);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
+                        if (more) buf[s * P + p] = piece(a, u0 + UT, hi, s * P + p, coff);
+                    }
+                    acc = wave_sum(acc);
+                    if (lane == 0) sh.part[pb][s][w] = acc;
+                }
+                __syncthreads();
+                if (tid < UT && u0 + tid < hi) {
+                    const int s0 = EPI == EPI_SWIGLU ? tid : 2 * tid;
+                    const int s1 = EPI == EPI_SWIGLU ? tid + UT : 2 * tid + 1;
+                    float r0 = 0.f, r1 = 0.f;
+#pragma unroll
+                    for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][s0][q]; r1 += sh.part[pb][s1][q]; }
+                    gemv_epilogue<WT, EPI, true, true>(a, u0 + tid, r0, r1, pos, rope);
+                }
+                pb ^= 1;
+            }
+        }
+        wait_stores();
+        Next::prefetch(na, buf);
+    }
+};
+
+struct FusedArgs {
+    SuperposeArgs sup;
+    const spd_layer_weights *layers;   // device array [n_layers]
+    const void *final_norm, *lm_head;
+    float *h, *q, *att, *u, *logits;
+    void *kv;                          // layer l: K at kv + 2 l kv_layer_bytes, V one kv_layer_bytes later
+    size_t kv_layer_bytes;
+    float *part;
+    int32_t *counters;
+    const double *inv_freq;
+    float2 *rope;                      // [d_head / 2] (cos, sin) of this step's position
+    long long *prof;                   // optional: block 0 stamps wall_clock64() around every barrier
+    unsigned *barrier;
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
+    float eps;
+};
+
+template <int NBUF>
+struct NoNext {
+    static __device__ __forceinline__ void prefetch(const GemvArgs &, u32x4 (&)[NBUF]) {}
+};
+
+__device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
+    const int dh = a.d_model / a.n_heads;
+    const int nq = a.n_heads * dh, nkv = a.n_kv_heads * dh;
+    GemvArgs g{};
+    const spd_layer_weights &w = a.layers[l];
+    g.W = w.wqkv; g.gain = w.attn_norm; g.eps = a.eps; g.x = a.h; g.y = a.q;
+    g.rows = nq + 2 * nkv; g.cols = a.d_model;
+    g.kcache = (char *)a.kv + (size_t)(2 * l) * a.kv_layer_bytes;
+    g.vcache = (char *)a.kv + (size_t)(2 * l + 1) * a.kv_layer_bytes;
+    g.inv_freq = a.inv_freq;
+    g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = a.cap_ctx;
+    return g;
+}
+
+__device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
+    GemvArgs g{};
+    g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.h; g.y = a.logits;
+    g.rows = a.vocab; g.cols = a.d_model;
+    return g;
+}
+
+// PA / PB: passes a block needs to cover d_model / d_ffn columns; UA / UB: rows per tile.
+template <typename WT, int PA, int UA, int PB, int UB>
+__global__ __launch_bounds__(NT, 4) void fused_forward_kernel(const FusedArgs a) {
+    constexpr int NBUF = (PA * UA > PB * UB) ? PA * UA : PB * UB;
+    using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF>;
+    using Oproj = Gemv<WT, PA, UA, EPI_RESID, NBUF>;
+    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF>;
+    using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF>;
+    using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF>;
+    __shared__ FusedShared sh;
+    __shared__ __align__(16) float dyn[NT * Store<WT>::VEC];
+
+#define SPD_BARRIER()                                                                   \
+    do {                                                                                \
+        if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();      \
+        grid_barrier(a.barrier, ++epoch * gridDim.x, &st->err);                         \
+        if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch - 1] = wall_clock64();  \
+    } while (0)
+    DevState *st = a.sup.st;
+    const int pos = st->pos;
+    const int dh = a.d_model / a.n_heads;
+    const int nq = a.n_heads * dh;
+    unsigned epoch = 0;
+
+    // phase 0: the input vector (Section 3.1, Eq. 1 and 2) and this position's rotary table
+    for (int c = blockIdx.x * NT + threadIdx.x; c < a.d_model; c += gridDim.x * NT)
+        superpose_element<WT, true>(a.sup, c, pos);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < dh / 2)
+    {
+        const float2 cs = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
+        act_store<true>(&a.rope[threadIdx.x].x, cs.x);
+        act_store<true>(&a.rope[threadIdx.x].y, cs.y);
+    }
+    wait_stores();
+    u32x4 buf[NBUF];
+    GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
+    if (a.n_layers > 0) Qkv::prefetch(cur, buf);
+    else if (a.head) Head::prefetch(cur, buf);
+    SPD_BARRIER();
+
+    for (int l = 0; l < a.n_layers; ++l) {
+        const spd_layer_weights &w = a.layers[l];
+        GemvArgs o{};
+        o.W = w.wo; o.x = a.att; o.resid = a.h; o.y = a.h; o.rows = a.d_model; o.cols = nq;
+        Qkv::template run<Oproj>(cur, o, pos, a.rope, sh, buf);
+        SPD_BARRIER();
+
+        {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
+            AttnArgs t{a.q, cur.kcache, cur.vcache, a.att, a.part, a.counters, nullptr, pos + 1,
+                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
+            const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
+            for (int item = blockIdx.x; item < a.n_kv_heads * n_splits; item += gridDim.x)
+                attn_item<WT, NT, true>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn, &sh.s_last);
+            wait_stores();
+        }
+        SPD_BARRIER();
+
+        GemvArgs f{};
+        f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = a.h; f.y = a.u;
+        f.rows = a.d_ffn; f.cols = a.d_model;
+        Oproj::template run<GateUp>(o, f, pos, a.rope, sh, buf);
+        SPD_BARRIER();
+
+        GemvArgs d{};
+        d.W = w.w_down; d.x = a.u; d.resid = a.h; d.y = a.h; d.rows = a.d_model; d.cols = a.d_ffn;
+        GateUp::template run<Down>(f, d, pos, a.rope, sh, buf);
+        SPD_BARRIER();
+
+        if (l + 1 < a.n_layers) {
+            cur = qkv_args(a, l + 1);
+            Down::template run<Qkv>(d, cur, pos, a.rope, sh, buf);
+        } else if (a.head) {
+            cur = head_args(a);
+            Down::template run<Head>(d, cur, pos, a.rope, sh, buf);
+        } else {
+            Down::template run<NoNext<NBUF>>(d, d, pos, a.rope, sh, buf);
+        }
+        if (l + 1 < a.n_layers || a.head) SPD_BARRIER();
+    }
+    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, a.rope, sh, buf);
+    if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();
+#undef SPD_BARRIER
+}
+
+template <typename WT, int PA, int UA, int PB, int UB>
+hipError_t launch_fused(hipStream_t s, const FusedArgs &a, int blocks) {
+    hipLaunchKernelGGL((fused_forward_kernel<WT, PA, UA, PB, UB>), dim3(blocks), dim3(NT), 0, s, a);
+    return hipGetLastError();
+}
+
+template <typename WT, int PA, int UA, int PB, int UB>
+int fused_blocks_per_cu() {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)fused_forward_kernel<WT, PA, UA, PB, UB>, NT, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return n;
+}
+
+}  // namespace
+
+namespace spdk {
+
+// Which instantiation serves a shape: passes needed to cover d_model and d_ffn with NW waves.
+static bool fused_variant(int dtype, int d_model, int d_ffn, int &pa, int &pb) {
+    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    const int span = NW * WAVE * vec;
+    pa = (d_model + span - 1) / span;
+    pb = (d_ffn + span - 1) / span;
+    return (pa == 1 && (pb == 1 || pb == 3));
+}
+
+int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
+    int pa, pb;
+    if (!fused_variant(dtype, d_model, d_ffn, pa, pb)) return 0;
+    if (dtype == SPD_DTYPE_BF16) return pb == 1 ? fused_blocks_per_cu<bf16_t, 1, 8, 1, 8>() : fused_blocks_per_cu<bf16_t, 1, 8, 3, 2>();
+    return pb == 1 ? fused_blocks_per_cu<float, 1, 8, 1, 8>() : fused_blocks_per_cu<float, 1, 8, 3, 2>();
+}
+
+hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int blocks) {
+    FusedArgs a{};
+    a.sup = h.sup; a.layers = h.layers; a.final_norm = h.final_norm; a.lm_head = h.lm_head;
+    a.h = h.h; a.q = h.q; a.att = h.att; a.u = h.u; a.logits = h.logits;
+    a.kv = h.kv; a.kv_layer_bytes = h.kv_layer_bytes; a.part = h.part; a.counters = h.counters;
+    a.inv_freq = h.inv_freq; a.rope = h.rope; a.prof = h.prof; a.barrier = h.barrier;
+    a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
+    a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
+    a.eps = h.eps;
+    int pa, pb;
+    if (!fused_variant(dtype, h.d_model, h.d_ffn, pa, pb)) return hipErrorInvalidValue;
+    if (dtype == SPD_DTYPE_BF16)
+        return pb == 1 ? launch_fused<bf16_t, 1, 8, 1, 8>(s, a, blocks) : launch_fused<bf16_t, 1, 8, 3, 2>(s, a, blocks);
+    return pb == 1 ? launch_fused<float, 1, 8, 1, 8>(s, a, blocks) : launch_fused<float, 1, 8, 3, 2>(s, a, blocks);
+}
+
+}  // namespace spdk

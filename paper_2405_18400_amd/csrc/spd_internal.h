@@ -133,8 +133,26 @@ struct ExpandArgs {
     int32_t max_gen;
 };
 
+// Arguments of the fused forward kernel (one persistent launch for the whole model).
+struct FusedArgsHost {
+    SuperposeArgs sup;
+    const spd_layer_weights *layers;   // DEVICE array [n_layers]
+    const void *final_norm, *lm_head;
+    float *h, *q, *att, *u, *logits;
+    void *kv;
+    size_t kv_layer_bytes;
+    float *part;
+    int32_t *counters;
+    const double *inv_freq;
+    float2 *rope;                      // [d_head / 2] scratch: (cos, sin) at this step's position
+    long long *prof;                   // optional [2 * (5 n_layers + 2)] clock stamps of block 0
+    unsigned *barrier;                 // zero at launch
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
+    float eps;
+};
+
 constexpr int TOPK_PART_MAX = 128;
-constexpr int ATTN_CHUNK = 256;
+constexpr int ATTN_CHUNK = 128;
 
 namespace spdk {
 hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu);
@@ -146,6 +164,9 @@ hipError_t expand_prune(hipStream_t s, const ExpandArgs &a);
 hipError_t advance(hipStream_t s, DevState *st);
 hipError_t renorm(hipStream_t s, DevState *st, int k);
 hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);
+// Fused forward: 0 if no instantiation serves this shape, else resident blocks per CU.
+int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn);
+hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &a, int blocks);
 hipError_t init();  // raise the dynamic-LDS limit of the kernels that need it
 }  // namespace spdk
 

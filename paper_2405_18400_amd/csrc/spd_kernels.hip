@@ -4,91 +4,14 @@
 // around streaming weights from HBM exactly once with 128-bit loads; the only arithmetic
 // that matters for time is keeping enough bytes in flight.  Reductions use a fixed order
 // (no float atomics), so results are bit-reproducible run to run.
-#include "spd_internal.h"
+#include "spd_device.h"
 
-#include <climits>
-#include <cmath>
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using namespace spdd;
 
 namespace {
 
-constexpr int WAVE = 64;
 constexpr int BLOCK = 256;
 constexpr int NWAVE = BLOCK / WAVE;
-
-// ------------------------------------------------------------------ storage types
-struct bf16_t { uint16_t b; };
-
-template <typename T> struct Store;
-template <> struct Store<float> {
-    static constexpr int VEC = 4;  // elements per 16-byte load
-    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
-        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
-        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-    }
-    static __device__ __forceinline__ float load1(const void *p, size_t i) { return ((const float *)p)[i]; }
-    static __device__ __forceinline__ void store1(void *p, size_t i, float v) { ((float *)p)[i] = v; }
-};
-template <> struct Store<bf16_t> {
-    static constexpr int VEC = 8;
-    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
-        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
-        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
-    }
-    static __device__ __forceinline__ float load1(const void *p, size_t i) {
-        return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
-    }
-    static __device__ __forceinline__ void store1(void *p, size_t i, float v) {
-        uint32_t u = __float_as_uint(v);               // round to nearest even
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        ((uint16_t *)p)[i] = (uint16_t)(u >> 16);
-    }
-};
-
-__device__ __forceinline__ u32x4 stream_load16(const void *p) {
-    return __builtin_nontemporal_load((const u32x4 *)p);   // weights are read once per step
-}
-
-// Read data another workgroup (possibly on another XCD, behind another L2) wrote and
-// published with a device-scope fence.
-__device__ __forceinline__ float coherent_load(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-    return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-    return v;
-}
-// Sum over the block in a fixed order; every thread gets the result. `red` has NWAVE floats.
-__device__ __forceinline__ float block_sum(float v, float *red) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
-    __syncthreads();
-    float t = 0.f;
-#pragma unroll
-    for (int w = 0; w < NWAVE; ++w) t += red[w];
-    return t;
-}
-__device__ __forceinline__ float block_max(float v, float *red) {
-    v = wave_max(v);
-    __syncthreads();
-    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
-    __syncthreads();
-    float t = red[0];
-#pragma unroll
-    for (int w = 1; w < NWAVE; ++w) t = fmaxf(t, red[w]);
-    return t;
-}
 
 // ------------------------------------------------------------------ matrix-vector product
 // One wave owns two output rows at a time (EPI_SWIGLU: row r of the gate and of the up
@@ -177,7 +100,7 @@ __global__ __launch_bounds__(BLOCK) void gemv_kernel(const GemvArgs a) {
         ss += v * v;
     }
     if (a.gain != nullptr) {
-        const float tot = block_sum(ss, red);
+        const float tot = block_sum<BLOCK>(ss, red);
         const float rs = 1.0f / sqrtf(tot / (float)cols + a.eps);
         for (int c = tid; c < cols; c += BLOCK) xs[c] = xs[c] * rs * Store<WT>::load1(a.gain, c);
     }
@@ -205,152 +128,21 @@ __global__ __launch_bounds__(BLOCK) void gemv_kernel(const GemvArgs a) {
         }
         acc0 = wave_sum(acc0);
         acc1 = wave_sum(acc1);
-        if (lane == 0) {
-            if (EPI == EPI_PLAIN) {
-                a.y[2 * unit] = acc0;
-                a.y[2 * unit + 1] = acc1;
-            } else if (EPI == EPI_RESID) {
-                a.y[2 * unit] = a.resid[2 * unit] + acc0;
-                a.y[2 * unit + 1] = a.resid[2 * unit + 1] + acc1;
-            } else if (EPI == EPI_SWIGLU) {
-                a.y[unit] = acc0 / (1.0f + expf(-acc0)) * acc1;
-            } else {  // EPI_QKV: rotary on q and k pairs, append k and v to the cache
-                const int r0 = 2 * unit;
-                const int pos = a.st->pos;
-                if (r0 < a.n_q_rows + a.n_kv_rows) {
-                    const int i = (r0 % a.d_head) / 2;
-                    const double ang = (double)pos * a.inv_freq[i];
-                    const float c = (float)cos(ang), s = (float)sin(ang);
-                    const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
-                    const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));
-                    if (r0 < a.n_q_rows) {
-                        a.y[r0] = e;
-                        a.y[r0 + 1] = o;
-                    } else {
-                        const int rr = r0 - a.n_q_rows;
-                        const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-                        Store<WT>::store1(a.kcache, at, e);
-                        Store<WT>::store1(a.kcache, at + 1, o);
-                    }
-                } else {
-                    const int rr = r0 - a.n_q_rows - a.n_kv_rows;
-                    const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-                    Store<WT>::store1(a.vcache, at, acc0);
-                    Store<WT>::store1(a.vcache, at + 1, acc1);
-                }
-            }
-        }
+        if (lane == 0) gemv_epilogue<WT, EPI>(a, unit, acc0, acc1, EPI == EPI_QKV ? a.st->pos : 0);
         unit = next_unit;
     }
 }
 
 // ------------------------------------------------------------------ single-query attention
-// Block (g, s): key/value head g, context chunk s.  All query heads sharing head g are
-// served from one pass over the chunk.  Chunks are merged by whichever block finishes last
-// for a head, walking the partial results in chunk order (deterministic).
 template <typename KT>
 __global__ __launch_bounds__(BLOCK) void attn_kernel(const AttnArgs a) {
-    constexpr int VEC = Store<KT>::VEC;
     __shared__ float sc[ATTN_CHUNK];
     __shared__ float red[NWAVE];
-    extern __shared__ __align__(16) float dyn[];   // [BLOCK / LPP][dh] partial outputs
     __shared__ int s_last;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
-    const int dh = a.d_head;
-    const int LPP = dh / VEC;             // lanes per cached position
-    const int PPW = WAVE / LPP;           // positions per wave per iteration
-    const int PPB = PPW * NWAVE;
-    const int sub = lane / LPP, li = lane % LPP;
+    extern __shared__ __align__(16) float dyn[];   // [BLOCK / LPP][dh] partial outputs
     const int n_ctx = a.st ? a.st->pos + 1 : a.n_ctx;
-    const int g = blockIdx.x, s = blockIdx.y;
-    const int t0 = s * a.chunk;
-    if (t0 >= n_ctx) return;
-    const int t1 = min(n_ctx, t0 + a.chunk);
-    const int n_splits = (n_ctx + a.chunk - 1) / a.chunk;
-    const int group = a.n_heads / a.n_kv_heads;
-    const float scale = 1.0f / sqrtf((float)dh);
-    const char *Kg = (const char *)a.K + (size_t)g * a.cap_ctx * dh * sizeof(KT);
-    const char *Vg = (const char *)a.V + (size_t)g * a.cap_ctx * dh * sizeof(KT);
-
-    for (int hq = 0; hq < group; ++hq) {
-        const int h = g * group + hq;
-        float qv[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) qv[v] = a.q[(size_t)h * dh + li * VEC + v];
-        // scores
-        float lmax = -INFINITY;
-        for (int t = t0 + wid * PPW + sub; t - sub < t1; t += PPB) {   // t - sub is wave-uniform
-            float d = 0.f;
-            if (t < t1) {
-                float kf[VEC];
-                Store<KT>::unpack(*(const u32x4 *)(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT)), kf);
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
-            }
-            for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
-            d *= scale;
-            if (t < t1) {
-                if (li == 0) sc[t - t0] = d;
-                lmax = fmaxf(lmax, d);
-            }
-        }
-        const float m = block_max(lmax, red);   // includes a barrier after the sc writes
-        float lsum = 0.f;
-        for (int t = tid; t < t1 - t0; t += BLOCK) {
-            const float p = expf(sc[t] - m);
-            sc[t] = p;
-            lsum += p;
-        }
-        const float l = block_sum(lsum, red);
-        // weighted values
-        float acc[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-        for (int t = t0 + wid * PPW + sub; t < t1; t += PPB) {
-            float vf[VEC];
-            Store<KT>::unpack(*(const u32x4 *)(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT)), vf);
-            const float p = sc[t - t0];
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
-        }
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
-        __syncthreads();
-        float o = 0.f;
-        if (tid < dh) {
-            for (int r = 0; r < PPB; ++r) o += dyn[(size_t)r * dh + tid];
-        }
-        if (n_splits == 1) {
-            if (tid < dh) a.out[(size_t)h * dh + tid] = o / l;
-        } else {
-            float *pp = a.part + ((size_t)h * a.max_splits + s) * (dh + 2);
-            if (tid < dh) pp[2 + tid] = o;
-            if (tid == 0) { pp[0] = m; pp[1] = l; }
-            __threadfence();
-            __syncthreads();
-            if (tid == 0) {
-                const int old = atomicAdd(&a.counters[h], 1);
-                s_last = (old == n_splits - 1);
-            }
-            __syncthreads();
-            if (s_last) {
-                __threadfence();
-                const float *ph = a.part + (size_t)h * a.max_splits * (dh + 2);
-                float M = -INFINITY;
-                for (int q = 0; q < n_splits; ++q) M = fmaxf(M, coherent_load(ph + (size_t)q * (dh + 2)));
-                float L = 0.f, O = 0.f;
-                for (int q = 0; q < n_splits; ++q) {
-                    const float *pq = ph + (size_t)q * (dh + 2);
-                    const float w = expf(coherent_load(pq) - M);
-                    L += w * coherent_load(pq + 1);
-                    if (tid < dh) O += w * coherent_load(pq + 2 + tid);
-                }
-                if (tid < dh) a.out[(size_t)h * dh + tid] = O / L;
-                if (tid == 0) a.counters[h] = 0;
-            }
-        }
-        __syncthreads();   // sc / dyn / s_last are reused by the next query head
-    }
+    if ((int)blockIdx.y * a.chunk >= n_ctx) return;
+    attn_item<KT, BLOCK>(a, blockIdx.x, blockIdx.y, n_ctx, sc, red, dyn, &s_last);
 }
 
 // ------------------------------------------------------------------ superposed embedding
@@ -358,28 +150,7 @@ __global__ __launch_bounds__(BLOCK) void attn_kernel(const AttnArgs a) {
 // mode 0 feeds a prefix token's own embedding (gamma = 1) during the prefix pass.
 template <typename WT>
 __global__ __launch_bounds__(BLOCK) void superpose_kernel(const SuperposeArgs a) {
-    const int c = blockIdx.x * BLOCK + threadIdx.x;
-    if (a.mode == 0) {
-        const int tok = a.prefix[a.st->pos];
-        if (c < a.d_model) a.h[c] = Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c);
-        return;
-    }
-    const int k = a.k;
-    float g[SPD_K_MAX];
-    float mx = -INFINITY;
-    for (int i = 0; i < k; ++i) mx = fmaxf(mx, a.st->logscore[i]);
-    float sum = 0.f;
-    for (int i = 0; i < k; ++i) { g[i] = expf(a.st->logscore[i] - mx); sum += g[i]; }
-    float acc = 0.f;
-    for (int i = 0; i < k; ++i) {
-        const float gi = g[i] / sum;
-        if (c < a.d_model) {
-            const int tok = a.st->tails[i][SPD_TAIL - 1];
-            acc = __fadd_rn(acc, __fmul_rn(gi, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c)));
-        }
-        if (c == 0) a.st->gamma_in[i] = gi;
-    }
-    if (c < a.d_model) a.h[c] = acc;
+    superpose_element<WT>(a, blockIdx.x * BLOCK + threadIdx.x, a.mode == 0 ? a.st->pos : 0);
 }
 
 // ------------------------------------------------------------------ vocabulary top-k
@@ -414,10 +185,10 @@ __global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
     const int lo = b * a.per_part, hi = min(a.vocab, lo + a.per_part);
     float mx = -INFINITY;
     for (int i = lo + tid; i < hi; i += BLOCK) mx = fmaxf(mx, __fdiv_rn(a.logits[i], a.tau));
-    mx = block_max(mx, red);
+    mx = block_max<BLOCK>(mx, red);
     float sm = 0.f;
     for (int i = lo + tid; i < hi; i += BLOCK) sm += expf(__fdiv_rn(a.logits[i], a.tau) - mx);
-    sm = block_sum(sm, red);
+    sm = block_sum<BLOCK>(sm, red);
     if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; }
     float pv = INFINITY;   // previous winner: everything "after" it in the total order is eligible
     int pi = -1;

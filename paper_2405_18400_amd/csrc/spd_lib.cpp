@@ -14,12 +14,12 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 enum State { ST_CREATED = 0, ST_PREFILLED = 1, ST_STEPPING = 2 };
 
-enum KClass { KC_SUPERPOSE, KC_QKV, KC_ATTN, KC_O, KC_GATEUP, KC_DOWN, KC_HEAD, KC_TOPK, KC_EXPAND, KC_N };
+enum KClass { KC_SUPERPOSE, KC_QKV, KC_ATTN, KC_O, KC_GATEUP, KC_DOWN, KC_HEAD, KC_TOPK, KC_EXPAND, KC_FUSED, KC_N };
 const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_o", "gemv_gateup",
-                                    "gemv_down", "gemv_head", "topk_partial", "expand_prune"};
+                                    "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward"};
 
 struct Layout {
-    size_t state, h, q, att, u, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
+    size_t state, barrier, layers_dev, rope, prof, h, q, att, u, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     int max_splits, n_part, per_part;
 };
@@ -59,6 +59,10 @@ Layout make_layout(const spd_model_cfg &c) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
     L.state = take(sizeof(DevState));
+    L.barrier = take(256);
+    L.layers_dev = take((size_t)(c.n_layers > 0 ? c.n_layers : 1) * sizeof(spd_layer_weights));
+    L.rope = take((size_t)(dh / 2) * 8);
+    L.prof = take((size_t)(2 * (5 * c.n_layers + 2) + 2) * 8);
     L.h = take((size_t)c.d_model * 4);
     L.q = take((size_t)c.n_heads * dh * 4);
     L.att = take((size_t)c.n_heads * dh * 4);
@@ -97,7 +101,8 @@ struct spd_ctx {
     int state, pos, n_gen, k;
     char *pinned;
     size_t pinned_bytes;
-    bool use_graph, timing;
+    bool use_graph, timing, use_fused;
+    int fused_blocks;   // grid of the fused forward kernel; 0 = not available for this shape
     hipGraphExec_t step_exec, prefill_exec;
     spd_decode_cfg step_dc;
     std::vector<Timed> timed;
@@ -163,6 +168,23 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
     const int nq = m.n_heads * dh, nkv = m.n_kv_heads * dh;
     hipError_t e;
     SuperposeArgs sa{c->embed, c->st(), c->at<int32_t>(c->L.prefix), c->at<float>(c->L.h), m.d_model, mode, k};
+    if (c->use_fused && c->fused_blocks > 0) {
+        FusedArgsHost f{};
+        f.sup = sa;
+        f.layers = c->at<spd_layer_weights>(c->L.layers_dev);
+        f.final_norm = c->final_norm; f.lm_head = c->lm_head;
+        f.h = c->at<float>(c->L.h); f.q = c->at<float>(c->L.q); f.att = c->at<float>(c->L.att);
+        f.u = c->at<float>(c->L.u); f.logits = c->at<float>(c->L.logits);
+        f.kv = c->ws + c->L.kv; f.kv_layer_bytes = c->L.kv_layer_bytes;
+        f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
+        f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr; f.barrier = c->at<unsigned>(c->L.barrier);
+        f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
+        f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
+        f.head = head ? 1 : 0; f.eps = m.rms_eps;
+        e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, 1);
+        if (e != hipSuccess) return e;
+        return launch(c, KC_FUSED, [&] { return spdk::fused_forward(c->stream, m.dtype, f, c->fused_blocks); });
+    }
     e = launch(c, KC_SUPERPOSE, [&] { return spdk::superpose(c->stream, m.dtype, sa); });
     if (e != hipSuccess) return e;
     float *h = c->at<float>(c->L.h), *q = c->at<float>(c->L.q), *att = c->at<float>(c->L.att), *u = c->at<float>(c->L.u);
@@ -304,7 +326,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     c->have_ng = false;
     std::memset(&c->ng, 0, sizeof(c->ng));
     c->state = ST_CREATED; c->pos = 0; c->n_gen = 0; c->k = 0;
-    c->use_graph = true; c->timing = false;
+    c->use_graph = true; c->timing = false; c->use_fused = true; c->fused_blocks = 0;
     c->step_exec = nullptr; c->prefill_exec = nullptr;
     std::memset(&c->step_dc, 0, sizeof(c->step_dc));
     std::memset(c->kc_ms, 0, sizeof(c->kc_ms));
@@ -316,16 +338,27 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess) e = spdk::init();
-    c->pinned_bytes = up(sizeof(DevState)) + (size_t)cfg->max_ctx * (4 + 2 * SPD_K_MAX * 4) + (size_t)cfg->vocab * 4;
+    c->pinned_bytes = up(sizeof(DevState)) + (size_t)cfg->max_ctx * (4 + 2 * SPD_K_MAX * 4) + (size_t)cfg->vocab * 4 +
+                      up(2048) + (size_t)cfg->n_layers * sizeof(spd_layer_weights);
     if (e == hipSuccess) e = hipHostMalloc((void **)&c->pinned, c->pinned_bytes, hipHostMallocDefault);
     if (e != hipSuccess) { delete c; return SPD_EHIP; }
     c->num_cu = prop.multiProcessorCount;
+    {   // the fused forward needs its whole grid resident at once: size it from the occupancy
+        int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
+        if (per_cu > 2) per_cu = 2;
+        c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
+    }
 
     // rotary frequencies theta^(-2i/d_head) in double; zeroed state and attention counters
     const int dh = cfg->d_model / cfg->n_heads;
     double *f = (double *)c->pinned;
     for (int i = 0; i < dh / 2; ++i) f[i] = std::pow((double)cfg->rope_theta, -2.0 * i / dh);
+    spd_layer_weights *hl = (spd_layer_weights *)(c->pinned + up((size_t)(dh / 2) * 8));
+    for (int l = 0; l < cfg->n_layers; ++l) hl[l] = c->layers[l];
     e = hipMemcpyAsync(c->ws + L.inv_freq, f, (size_t)(dh / 2) * 8, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess && cfg->n_layers > 0)
+        e = hipMemcpyAsync(c->ws + L.layers_dev, hl, (size_t)cfg->n_layers * sizeof(spd_layer_weights),
+                           hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, (int32_t *)c->st(), 0, sizeof(DevState) / 4);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
@@ -424,6 +457,7 @@ static int copy_step_outputs(spd_ctx *c, int k, int32_t *out_tok, int32_t *out_p
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
     for (int i = 0; i < k; ++i) {
         if (out_tok) out_tok[i] = hs->new_tok[i];
         if (out_par) out_par[i] = hs->new_parent[i];
@@ -602,11 +636,36 @@ int spd_set_graph(spd_ctx *c, int32_t enable) {
     return SPD_OK;
 }
 
+int spd_set_fused(spd_ctx *c, int32_t enable) {
+    if (!c) return SPD_EINVAL;
+    if (enable && c->fused_blocks == 0) return fail(c, SPD_EINVAL, "no fused forward kernel for this model shape");
+    if ((enable != 0) != c->use_fused) { drop_graph(c->step_exec); drop_graph(c->prefill_exec); }
+    c->use_fused = enable != 0;
+    return SPD_OK;
+}
+
+int spd_get_fused(const spd_ctx *c, int32_t *out_enabled) {
+    if (!c || !out_enabled) return SPD_EINVAL;
+    *out_enabled = (c->use_fused && c->fused_blocks > 0) ? 1 : 0;
+    return SPD_OK;
+}
+
 int spd_set_kernel_timing(spd_ctx *c, int32_t enable) {
     if (!c) return SPD_EINVAL;
     if (c->timing && !enable) HIPCHK(c, drain_timing(c));
     c->timing = enable != 0;
     if (enable) { std::memset(c->kc_ms, 0, sizeof(c->kc_ms)); std::memset(c->kc_n, 0, sizeof(c->kc_n)); }
+    return SPD_OK;
+}
+
+int spd_get_phase_clock(spd_ctx *c, int32_t cap, int64_t *out_stamps, int32_t *out_n) {
+    if (!c) return SPD_EINVAL;
+    if (!out_stamps || !out_n) return fail(c, SPD_EINVAL, "null output");
+    const int n = 2 * (5 * c->cfg.n_layers + 2);
+    if (cap < n) return fail(c, SPD_EINVAL, "buffer too small for the phase stamps");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(out_stamps, c->ws + c->L.prof, (size_t)n * 8, hipMemcpyDeviceToHost));
+    *out_n = n;
     return SPD_OK;
 }
 
