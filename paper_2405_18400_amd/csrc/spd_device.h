@@ -50,8 +50,21 @@ template <> struct Store<bf16_t> {
     }
 };
 
+// Pointers that reach a kernel inside structures or through memory are "generic" to the
+// compiler, and generic loads are slower than global ones here in a way that matters: they
+// also count as LDS traffic, so every LDS wait would drain the weight stream.  Everything
+// this library reads in bulk is global memory, and says so.
+typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const f32x4 __attribute__((address_space(1))) *global_f32x4_ptr;
+
 __device__ __forceinline__ u32x4 stream_load16(const void *p) {
-    return __builtin_nontemporal_load((const u32x4 *)p);   // weights are read once per step
+    return __builtin_nontemporal_load((global_u32x4_ptr)p);   // weights are read once per step
+}
+__device__ __forceinline__ u32x4 global_load16(const void *p) { return *(global_u32x4_ptr)p; }
+__device__ __forceinline__ float4 global_load_float4(const float *p) {
+    const f32x4 v = *(global_f32x4_ptr)p;
+    return make_float4(v.x, v.y, v.z, v.w);
 }
 
 // Read data another workgroup (possibly on another XCD, behind another L2) wrote and
@@ -60,11 +73,13 @@ __device__ __forceinline__ float coherent_load(const float *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Activation traffic between workgroups.  COH = true (the persistent kernel): stores go
-// through to memory and loads come from there (device-scope relaxed atomics, the `sc1`
-// forms), so producers and consumers on different XCDs never need an L2 write-back or
-// invalidate.  COH = false (one kernel per operator): ordinary accesses; the kernel boundary
-// orders them.
+// Activation traffic between workgroups.  COH = true (the persistent kernel): stores are
+// written through to memory (device-scope relaxed atomic stores, the `sc1` form) and every
+// produced vector has an address nothing read earlier in the launch, so consumers on other
+// XCDs use ordinary loads: their L2 cannot hold a stale copy, and after the first miss the
+// vector is served from that L2.  No L2 write-back or invalidate is ever needed.  The few
+// places that re-read an address within a launch (attention partials) use act_load<true>.
+// COH = false (one kernel per operator): ordinary accesses; the kernel boundary orders them.
 template <bool COH> __device__ __forceinline__ float act_load(const float *p) {
     if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return *p;
@@ -129,16 +144,15 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
         act_store<COH>(a.y + 2 * unit, acc0);
         act_store<COH>(a.y + 2 * unit + 1, acc1);
     } else if (EPI == EPI_RESID) {
-        act_store<COH>(a.y + 2 * unit, act_load<COH>(a.resid + 2 * unit) + acc0);
-        act_store<COH>(a.y + 2 * unit + 1, act_load<COH>(a.resid + 2 * unit + 1) + acc1);
+        act_store<COH>(a.y + 2 * unit, a.resid[2 * unit] + acc0);
+        act_store<COH>(a.y + 2 * unit + 1, a.resid[2 * unit + 1] + acc1);
     } else if (EPI == EPI_SWIGLU) {
         act_store<COH>(a.y + unit, acc0 / (1.0f + expf(-acc0)) * acc1);
     } else {  // EPI_QKV: rotary on q and k pairs, append k and v to the cache
         const int r0 = 2 * unit;
         if (r0 < a.n_q_rows + a.n_kv_rows) {
             const int i = (r0 % a.d_head) / 2;
-            const float2 cs = ROPE_TABLE ? make_float2(act_load<COH>(&rope[i].x), act_load<COH>(&rope[i].y))
-                                         : rope_cos_sin(a.inv_freq, i, pos);
+            const float2 cs = ROPE_TABLE ? rope[i] : rope_cos_sin(a.inv_freq, i, pos);
             const float c = cs.x, s = cs.y;
             const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
             const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));
@@ -160,32 +174,12 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
     }
 }
 
-// VEC consecutive cache elements starting at element index `at`; `fresh` marks the row that
-// another workgroup wrote earlier in the same launch.
-template <typename KT, bool COH>
-__device__ __forceinline__ void load_row_piece(const char *base, size_t at, bool fresh, float *f) {
-    constexpr int VEC = Store<KT>::VEC;
-    if (COH && fresh) {
-        const uint32_t *p = (const uint32_t *)(base + at * sizeof(KT));
-        u32x4 v;
-        v.x = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        Store<KT>::unpack(v, f);
-    } else {
-        Store<KT>::unpack(*(const u32x4 *)(base + at * sizeof(KT)), f);
-    }
-    (void)VEC;
-}
-
 // ------------------------------------------------------------------ single-query attention
 // One work item = (key/value head g, context chunk s) handled by a block of NT threads.  All
 // query heads sharing head g are served from the chunk.  Chunks are merged by whichever block
 // finishes last for a head, walking the partial results in chunk order (deterministic).
 // LDS: sc[ATTN_CHUNK], red[NT/64], dyn[NT * VEC] floats, one int.
-// COH: q, the newest cache row (written earlier in the same launch) and the outputs use
-// the coherent access forms.
+// COH: outputs are written through; partial results of other chunks are re-read coherently.
 template <typename KT, int NT, bool COH = false>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
                                           float *dyn, int *s_last) {
@@ -209,13 +203,13 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         const int h = g * group + hq;
         float qv[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) qv[v] = act_load<COH>(a.q + (size_t)h * dh + li * VEC + v);
+        for (int v = 0; v < VEC; ++v) qv[v] = a.q[(size_t)h * dh + li * VEC + v];
         float lmax = -INFINITY;
         for (int t = t0 + wid * PPW + sub; t - sub < t1; t += PPB) {   // t - sub is wave-uniform
             float d = 0.f;
             if (t < t1) {
                 float kf[VEC];
-                load_row_piece<KT, COH>(Kg, (size_t)t * dh + li * VEC, t == n_ctx - 1, kf);
+                Store<KT>::unpack(global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT)), kf);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
             }
@@ -239,7 +233,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
         for (int t = t0 + wid * PPW + sub; t < t1; t += PPB) {
             float vf[VEC];
-            load_row_piece<KT, COH>(Vg, (size_t)t * dh + li * VEC, t == n_ctx - 1, vf);
+            Store<KT>::unpack(global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT)), vf);
             const float p = sc[t - t0];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);

@@ -17,29 +17,40 @@ using namespace spdd;
 
 namespace {
 
-constexpr int NT = 512;           // threads per block
-constexpr int NW = NT / WAVE;     // waves per block
+// One block per CU (fewer barrier participants), 16 waves: two groups of NW waves; the waves
+// of a group read one matrix row side by side, the groups work on different rows.
+constexpr int NT = 1024;          // threads per block
+constexpr int NW = 8;             // waves side by side on one row
+constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
 struct FusedShared {
-    float part[2][8][NW];         // [buffer][tile slot][wave]
-    float red[NW];
+    float part[2][NG][8][NW];     // [buffer][row group][tile slot][wave]
+    float red[NT / WAVE];
     float sc[ATTN_CHUNK];
     int s_last;
 };
 
-// Device-wide barrier: arrival counter in device memory, monotonically increasing within a
-// launch (the host-side sequence resets it between launches).  Bounded: if the grid is not
-// co-resident the wait gives up, raises st->err and every later wait returns at once, so the
-// kernel always drains.
-__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned target, int *err) {
+// Device-wide barrier, two levels: blocks arrive on their group's counter (BAR_GROUP
+// consecutive blocks per group, counters 256 bytes apart), the last arriver of a group bumps
+// the top counter, everyone polls the top counter.  Same-address atomics serialise at the
+// memory side (~14 ns each), so this costs about a third of one flat counter.  All counters
+// increase monotonically within a launch; the host-side sequence zeroes them between
+// launches.  Bounded: if the grid is not co-resident the wait gives up, raises *err, and
+// every later wait returns at once, so the kernel always drains.
+__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err) {
     // Everything other blocks will read was stored with write-through (device-scope) stores
     // and every wave has waited for its own stores (wait_stores) before getting here.
     __syncthreads();
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned g = blockIdx.x / BAR_GROUP;
+        const unsigned n_groups = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
+        const unsigned my_size = min((unsigned)BAR_GROUP, gridDim.x - g * BAR_GROUP);
+        unsigned *top = ctr, *grp = ctr + 64 * (1 + g);
+        const unsigned old = __hip_atomic_fetch_add(grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == epoch * my_size) __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
-        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        while (__hip_atomic_load(top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * n_groups) {
             __builtin_amdgcn_s_sleep(1);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
@@ -49,7 +60,23 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned target, int
             }
         }
     }
-    __syncthreads();   // readers use device-scope loads, so no cache invalidate is needed
+    __syncthreads();
+}
+
+// Values that are the same in every lane but were loaded from global memory would occupy
+// vector registers; these move them to scalar registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T> __device__ __forceinline__ T *uniform(T *p) {
+    const uint64_t u = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return (T *)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ spd_layer_weights uniform(const spd_layer_weights &w) {
+    spd_layer_weights r;
+    r.attn_norm = uniform(w.attn_norm); r.wqkv = uniform(w.wqkv); r.wo = uniform(w.wo);
+    r.ffn_norm = uniform(w.ffn_norm); r.w_gate = uniform(w.w_gate); r.w_up = uniform(w.w_up);
+    r.w_down = uniform(w.w_down);
+    return r;
 }
 
 // Wait until this wave's stores have been acknowledged.  Called before the next phase's
@@ -59,8 +86,9 @@ __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)
 // Units [lo, hi) of n that block b of G owns (contiguous, balanced to within one unit).
 __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &hi) {
     // n * (b + 1) stays below 2^32 for every supported shape (n <= 2^21 units, G <= 2^10 blocks)
-    lo = (int)(((unsigned)n * (unsigned)b) / (unsigned)G);
-    hi = (int)(((unsigned)n * (unsigned)(b + 1)) / (unsigned)G);
+    // (integer division runs on the vector unit: bring the uniform results back to scalars)
+    lo = __builtin_amdgcn_readfirstlane((int)(((unsigned)n * (unsigned)b) / (unsigned)G));
+    hi = __builtin_amdgcn_readfirstlane((int)(((unsigned)n * (unsigned)(b + 1)) / (unsigned)G));
 }
 
 // A phase keeps ONE tile of U rows x P passes (NS = U * P 16-byte pieces per lane) in
@@ -81,15 +109,17 @@ struct Gemv {
 
     // Byte offset of this lane's piece of pass p within a row.
     static __device__ __forceinline__ uint32_t col_offset(const GemvArgs &a, int p) {
-        const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+        const int lane = threadIdx.x & (WAVE - 1), w = (threadIdx.x / WAVE) % NW;
         const int c = ((p * NW + w) * WAVE + lane) * VEC;
         return (uint32_t)min(c, a.cols - VEC) * (uint32_t)sizeof(WT);
     }
 
-    // Piece q = s * P + p of the tile starting at unit u0 of a block whose range ends at u_end.
+    // Piece q = s * P + p of this wave's row group within the block tile starting at unit u0
+    // (a block tile is NG * UT units) of a block whose range ends at u_end.
     static __device__ __forceinline__ u32x4 piece(const GemvArgs &a, int u0, int u_end, int q, const uint32_t (&coff)[P]) {
         const int s = q / P, p = q % P;
-        const int unit = min(u0 + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
+        const int g = __builtin_amdgcn_readfirstlane(threadIdx.x / (WAVE * NW));
+        const int unit = min(u0 + g * UT + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
         const size_t row_bytes = (size_t)a.cols * sizeof(WT);
         const char *base;
         if (EPI == EPI_SWIGLU) base = (const char *)(s < UT ? a.W : a.W2) + (size_t)unit * row_bytes;
@@ -114,7 +144,7 @@ struct Gemv {
     template <typename Next>
     static __device__ __forceinline__ void run(const GemvArgs &a, const GemvArgs &na, int pos, const float2 *rope,
                                                FusedShared &sh, u32x4 (&buf)[NBUF]) {
-        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
         block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
         if (lo < hi) {
@@ -129,16 +159,13 @@ struct Gemv {
 #pragma unroll
                 for (int v = 0; v < VEC; v += 4) {
                     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (c < a.cols) {
-                        t.x = act_load<true>(a.x + c + v); t.y = act_load<true>(a.x + c + v + 1);
-                        t.z = act_load<true>(a.x + c + v + 2); t.w = act_load<true>(a.x + c + v + 3);
-                    }
+                    if (c < a.cols) t = global_load_float4(a.x + c + v);   // first read of a fresh address
                     xr[p][v] = t.x; xr[p][v + 1] = t.y; xr[p][v + 2] = t.z; xr[p][v + 3] = t.w;
                     ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
                 }
             }
             if (a.gain != nullptr) {
-                const float tot = block_sum<NT>(ss, sh.red);
+                const float tot = block_sum<NT>(g == 0 ? ss : 0.f, sh.red);   // every group holds all of x
                 const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
@@ -149,8 +176,8 @@ struct Gemv {
                 }
             }
             int pb = 0;
-            for (int u0 = lo; u0 < hi; u0 += UT) {
-                const bool more = u0 + UT < hi;
+            for (int u0 = lo; u0 < hi; u0 += NG * UT) {
+                const bool more = u0 + NG * UT < hi;
 #pragma unroll
                 for (int s = 0; s < U; ++s) {
                     float acc = 0.f;
@@ -160,18 +187,19 @@ struct Gemv {
                         Store<WT>::unpack(buf[s * P + p], f);
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
-                        if (more) buf[s * P + p] = piece(a, u0 + UT, hi, s * P + p, coff);
+                        if (more) buf[s * P + p] = piece(a, u0 + NG * UT, hi, s * P + p, coff);
                     }
                     acc = wave_sum(acc);
-                    if (lane == 0) sh.part[pb][s][w] = acc;
+                    if (lane == 0) sh.part[pb][g][s][w] = acc;
                 }
                 __syncthreads();
-                if (tid < UT && u0 + tid < hi) {
-                    const int s0 = EPI == EPI_SWIGLU ? tid : 2 * tid;
-                    const int s1 = EPI == EPI_SWIGLU ? tid + UT : 2 * tid + 1;
+                if (tid < NG * UT && u0 + tid < hi) {   // unit u0 + tid: row group tid / UT, pair tid % UT
+                    const int eg = tid / UT, t = tid % UT;
+                    const int s0 = EPI == EPI_SWIGLU ? t : 2 * t;
+                    const int s1 = EPI == EPI_SWIGLU ? t + UT : 2 * t + 1;
                     float r0 = 0.f, r1 = 0.f;
 #pragma unroll
-                    for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][s0][q]; r1 += sh.part[pb][s1][q]; }
+                    for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][s0][q]; r1 += sh.part[pb][eg][s1][q]; }
                     gemv_epilogue<WT, EPI, true, true>(a, u0 + tid, r0, r1, pos, rope);
                 }
                 pb ^= 1;
@@ -186,7 +214,9 @@ struct FusedArgs {
     SuperposeArgs sup;
     const spd_layer_weights *layers;   // device array [n_layers]
     const void *final_norm, *lm_head;
-    float *h, *q, *att, *u, *logits;
+    char *act;
+    ActLayout al;
+    float *logits;
     void *kv;                          // layer l: K at kv + 2 l kv_layer_bytes, V one kv_layer_bytes later
     size_t kv_layer_bytes;
     float *part;
@@ -208,8 +238,8 @@ __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh, nkv = a.n_kv_heads * dh;
     GemvArgs g{};
-    const spd_layer_weights &w = a.layers[l];
-    g.W = w.wqkv; g.gain = w.attn_norm; g.eps = a.eps; g.x = a.h; g.y = a.q;
+    const spd_layer_weights w = uniform(a.layers[l]);
+    g.W = w.wqkv; g.gain = w.attn_norm; g.eps = a.eps; g.x = a.al.h_in(a.act, l); g.y = a.al.vec(a.act, l, a.al.q);
     g.rows = nq + 2 * nkv; g.cols = a.d_model;
     g.kcache = (char *)a.kv + (size_t)(2 * l) * a.kv_layer_bytes;
     g.vcache = (char *)a.kv + (size_t)(2 * l + 1) * a.kv_layer_bytes;
@@ -220,14 +250,14 @@ __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
 
 __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
     GemvArgs g{};
-    g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.h; g.y = a.logits;
+    g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.al.h_in(a.act, a.n_layers); g.y = a.logits;
     g.rows = a.vocab; g.cols = a.d_model;
     return g;
 }
 
 // PA / PB: passes a block needs to cover d_model / d_ffn columns; UA / UB: rows per tile.
 template <typename WT, int PA, int UA, int PB, int UB>
-__global__ __launch_bounds__(NT, 4) void fused_forward_kernel(const FusedArgs a) {
+__global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int NBUF = (PA * UA > PB * UB) ? PA * UA : PB * UB;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF>;
     using Oproj = Gemv<WT, PA, UA, EPI_RESID, NBUF>;
@@ -240,11 +270,11 @@ __global__ __launch_bounds__(NT, 4) void fused_forward_kernel(const FusedArgs a)
 #define SPD_BARRIER()                                                                   \
     do {                                                                                \
         if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();      \
-        grid_barrier(a.barrier, ++epoch * gridDim.x, &st->err);                         \
+        grid_barrier(a.barrier, ++epoch, &st->err);                         \
         if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
-    const int pos = st->pos;
+    const int pos = uniform(st->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;
     unsigned epoch = 0;
@@ -266,14 +296,16 @@ __global__ __launch_bounds__(NT, 4) void fused_forward_kernel(const FusedArgs a)
     SPD_BARRIER();
 
     for (int l = 0; l < a.n_layers; ++l) {
-        const spd_layer_weights &w = a.layers[l];
+        const spd_layer_weights w = uniform(a.layers[l]);
         GemvArgs o{};
-        o.W = w.wo; o.x = a.att; o.resid = a.h; o.y = a.h; o.rows = a.d_model; o.cols = nq;
+        float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
+        float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
+        o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
         Qkv::template run<Oproj>(cur, o, pos, a.rope, sh, buf);
         SPD_BARRIER();
 
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
-            AttnArgs t{a.q, cur.kcache, cur.vcache, a.att, a.part, a.counters, nullptr, pos + 1,
+            AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, pos + 1,
                        a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
             const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
             for (int item = blockIdx.x; item < a.n_kv_heads * n_splits; item += gridDim.x)
@@ -283,13 +315,13 @@ __global__ __launch_bounds__(NT, 4) void fused_forward_kernel(const FusedArgs a)
         SPD_BARRIER();
 
         GemvArgs f{};
-        f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = a.h; f.y = a.u;
+        f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
         f.rows = a.d_ffn; f.cols = a.d_model;
         Oproj::template run<GateUp>(o, f, pos, a.rope, sh, buf);
         SPD_BARRIER();
 
         GemvArgs d{};
-        d.W = w.w_down; d.x = a.u; d.resid = a.h; d.y = a.h; d.rows = a.d_model; d.cols = a.d_ffn;
+        d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn;
         GateUp::template run<Down>(f, d, pos, a.rope, sh, buf);
         SPD_BARRIER();
 
@@ -348,7 +380,7 @@ int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int blocks) {
     FusedArgs a{};
     a.sup = h.sup; a.layers = h.layers; a.final_norm = h.final_norm; a.lm_head = h.lm_head;
-    a.h = h.h; a.q = h.q; a.att = h.att; a.u = h.u; a.logits = h.logits;
+    a.act = h.act; a.al = h.al; a.logits = h.logits;
     a.kv = h.kv; a.kv_layer_bytes = h.kv_layer_bytes; a.part = h.part; a.counters = h.counters;
     a.inv_freq = h.inv_freq; a.rope = h.rope; a.prof = h.prof; a.barrier = h.barrier;
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;

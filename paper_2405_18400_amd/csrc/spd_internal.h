@@ -133,12 +133,27 @@ struct ExpandArgs {
     int32_t max_gen;
 };
 
+// Activation vectors of one forward pass.  Every vector a phase produces has an address of
+// its own (no buffer is written twice within a pass), so a consumer on another XCD can read
+// it through its L2 without ever meeting a stale line: byte offsets from `base`.
+struct ActLayout {
+    size_t h0;                 // the input vector x~
+    size_t layer0, stride;     // layer l's block starts at layer0 + l * stride
+    size_t q, att, h1, u, h2;  // within a layer block: query, attention output, residual stream
+                               // after attention, SwiGLU output, residual stream after the FFN
+    __host__ __device__ float *at(char *base, size_t off) const { return (float *)(base + off); }
+    __host__ __device__ float *h_in(char *base, int l) const { return l == 0 ? at(base, h0) : at(base, layer0 + (size_t)(l - 1) * stride + h2); }
+    __host__ __device__ float *vec(char *base, int l, size_t which) const { return at(base, layer0 + (size_t)l * stride + which); }
+};
+
 // Arguments of the fused forward kernel (one persistent launch for the whole model).
 struct FusedArgsHost {
     SuperposeArgs sup;
     const spd_layer_weights *layers;   // DEVICE array [n_layers]
     const void *final_norm, *lm_head;
-    float *h, *q, *att, *u, *logits;
+    char *act;
+    ActLayout al;
+    float *logits;
     void *kv;
     size_t kv_layer_bytes;
     float *part;
@@ -151,6 +166,9 @@ struct FusedArgsHost {
     float eps;
 };
 
+constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
+constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
+constexpr int BAR_WORDS = 64 * (1 + BAR_MAX_GROUPS);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;
 

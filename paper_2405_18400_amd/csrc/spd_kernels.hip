@@ -47,7 +47,7 @@ __device__ __forceinline__ void gemv_consume(const u32x4 *a, const u32x4 *b, int
         float xv[VEC], fa[VEC], fb[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; v += 4) {
-            const float4 t = *(const float4 *)(xs + c + v);
+            const float4 t = *(const float4 *)(xs + c + v);   // LDS
             xv[v] = t.x; xv[v + 1] = t.y; xv[v + 2] = t.z; xv[v + 3] = t.w;
         }
         Store<WT>::unpack(a[u], fa);

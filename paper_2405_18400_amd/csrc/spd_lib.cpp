@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -19,9 +20,10 @@ const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_
                                     "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward"};
 
 struct Layout {
-    size_t state, barrier, layers_dev, rope, prof, h, q, att, u, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
+    size_t state, barrier, layers_dev, rope, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     int max_splits, n_part, per_part;
+    ActLayout al;
 };
 
 size_t elem_size(int dtype) { return dtype == SPD_DTYPE_BF16 ? 2 : 4; }
@@ -59,14 +61,18 @@ Layout make_layout(const spd_model_cfg &c) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
     L.state = take(sizeof(DevState));
-    L.barrier = take(256);
+    L.barrier = take((size_t)BAR_WORDS * 4);
     L.layers_dev = take((size_t)(c.n_layers > 0 ? c.n_layers : 1) * sizeof(spd_layer_weights));
     L.rope = take((size_t)(dh / 2) * 8);
     L.prof = take((size_t)(2 * (5 * c.n_layers + 2) + 2) * 8);
-    L.h = take((size_t)c.d_model * 4);
-    L.q = take((size_t)c.n_heads * dh * 4);
-    L.att = take((size_t)c.n_heads * dh * 4);
-    L.u = take((size_t)c.d_ffn * 4);
+    {   // one address per produced vector (see ActLayout)
+        const size_t vd = up((size_t)c.d_model * 4), vq = up((size_t)c.n_heads * dh * 4), vu = up((size_t)c.d_ffn * 4);
+        L.al.h0 = 0;
+        L.al.layer0 = vd;
+        L.al.q = 0; L.al.att = vq; L.al.h1 = 2 * vq; L.al.u = 2 * vq + vd; L.al.h2 = 2 * vq + vd + vu;
+        L.al.stride = 2 * vq + 2 * vd + vu;
+        L.act = take(vd + (size_t)c.n_layers * L.al.stride);
+    }
     L.logits = take((size_t)c.vocab * 4);
     L.part = take((size_t)c.n_heads * L.max_splits * (dh + 2) * 4);
     L.counters = take((size_t)c.n_heads * 4);
@@ -167,29 +173,31 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
     const int dh = m.d_model / m.n_heads;
     const int nq = m.n_heads * dh, nkv = m.n_kv_heads * dh;
     hipError_t e;
-    SuperposeArgs sa{c->embed, c->st(), c->at<int32_t>(c->L.prefix), c->at<float>(c->L.h), m.d_model, mode, k};
+    char *act = c->ws + c->L.act;
+    const ActLayout &al = c->L.al;
+    SuperposeArgs sa{c->embed, c->st(), c->at<int32_t>(c->L.prefix), al.h_in(act, 0), m.d_model, mode, k};
     if (c->use_fused && c->fused_blocks > 0) {
         FusedArgsHost f{};
         f.sup = sa;
         f.layers = c->at<spd_layer_weights>(c->L.layers_dev);
         f.final_norm = c->final_norm; f.lm_head = c->lm_head;
-        f.h = c->at<float>(c->L.h); f.q = c->at<float>(c->L.q); f.att = c->at<float>(c->L.att);
-        f.u = c->at<float>(c->L.u); f.logits = c->at<float>(c->L.logits);
+        f.act = act; f.al = al; f.logits = c->at<float>(c->L.logits);
         f.kv = c->ws + c->L.kv; f.kv_layer_bytes = c->L.kv_layer_bytes;
         f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
         f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr; f.barrier = c->at<unsigned>(c->L.barrier);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
         f.head = head ? 1 : 0; f.eps = m.rms_eps;
-        e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, 1);
+        e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, BAR_WORDS);
         if (e != hipSuccess) return e;
         return launch(c, KC_FUSED, [&] { return spdk::fused_forward(c->stream, m.dtype, f, c->fused_blocks); });
     }
     e = launch(c, KC_SUPERPOSE, [&] { return spdk::superpose(c->stream, m.dtype, sa); });
     if (e != hipSuccess) return e;
-    float *h = c->at<float>(c->L.h), *q = c->at<float>(c->L.q), *att = c->at<float>(c->L.att), *u = c->at<float>(c->L.u);
     for (int l = 0; l < m.n_layers; ++l) {
         const spd_layer_weights &w = c->layers[l];
+        float *h = al.h_in(act, l), *q = al.vec(act, l, al.q), *att = al.vec(act, l, al.att);
+        float *h1 = al.vec(act, l, al.h1), *u = al.vec(act, l, al.u), *h2 = al.vec(act, l, al.h2);
         GemvArgs g{};
         g.W = w.wqkv; g.gain = w.attn_norm; g.eps = m.rms_eps; g.x = h; g.y = q;
         g.rows = nq + 2 * nkv; g.cols = m.d_model;
@@ -203,22 +211,22 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         e = launch(c, KC_ATTN, [&] { return spdk::attention(c->stream, m.dtype, a); });
         if (e != hipSuccess) return e;
         GemvArgs o{};
-        o.W = w.wo; o.x = att; o.resid = h; o.y = h; o.rows = m.d_model; o.cols = nq;
+        o.W = w.wo; o.x = att; o.resid = h; o.y = h1; o.rows = m.d_model; o.cols = nq;
         e = launch(c, KC_O, [&] { return spdk::gemv(c->stream, m.dtype, EPI_RESID, o, c->num_cu); });
         if (e != hipSuccess) return e;
         GemvArgs f{};
-        f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = m.rms_eps; f.x = h; f.y = u;
+        f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = m.rms_eps; f.x = h1; f.y = u;
         f.rows = m.d_ffn; f.cols = m.d_model;
         e = launch(c, KC_GATEUP, [&] { return spdk::gemv(c->stream, m.dtype, EPI_SWIGLU, f, c->num_cu); });
         if (e != hipSuccess) return e;
         GemvArgs d{};
-        d.W = w.w_down; d.x = u; d.resid = h; d.y = h; d.rows = m.d_model; d.cols = m.d_ffn;
+        d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = m.d_model; d.cols = m.d_ffn;
         e = launch(c, KC_DOWN, [&] { return spdk::gemv(c->stream, m.dtype, EPI_RESID, d, c->num_cu); });
         if (e != hipSuccess) return e;
     }
     if (head) {
         GemvArgs g{};
-        g.W = c->lm_head; g.gain = c->final_norm; g.eps = m.rms_eps; g.x = h; g.y = c->at<float>(c->L.logits);
+        g.W = c->lm_head; g.gain = c->final_norm; g.eps = m.rms_eps; g.x = al.h_in(act, m.n_layers); g.y = c->at<float>(c->L.logits);
         g.rows = m.vocab; g.cols = m.d_model;
         e = launch(c, KC_HEAD, [&] { return spdk::gemv(c->stream, m.dtype, EPI_PLAIN, g, c->num_cu); });
         if (e != hipSuccess) return e;
@@ -345,8 +353,10 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     c->num_cu = prop.multiProcessorCount;
     {   // the fused forward needs its whole grid resident at once: size it from the occupancy
         int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
-        if (per_cu > 2) per_cu = 2;
+        if (per_cu > 1) per_cu = 1;
+        if (const char *e = getenv("SPD_FUSED_BLOCKS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v < per_cu) per_cu = v; }
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
+        if (c->fused_blocks > BAR_GROUP * BAR_MAX_GROUPS) c->fused_blocks = 0;
     }
 
     // rotary frequencies theta^(-2i/d_head) in double; zeroed state and attention counters
