@@ -47,7 +47,7 @@ class SpdDecodeCfg(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(HERE, "libspd.so")
+    return os.environ.get("SPD_LIBRARY", os.path.join(HERE, "libspd.so"))
 
 
 def lib():

@@ -19,15 +19,16 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, out: str = LIB) -> str:
     """Always recompiles.  -ffp-contract=off: the kernels spell out every fused
     multiply-add they want; packed-fp32 instruction selection is disabled."""
     cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
+    cmd += os.environ.get("SPD_EXTRA_DEFS", "").split()      # experiments only, e.g. -DSPD_FUSED_NT=512
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     log = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if noise not in l)
@@ -35,7 +36,7 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -135,11 +135,11 @@ __device__ __forceinline__ float2 rope_cos_sin(const double *inv_freq, int i, in
     return make_float2((float)cos(ang), (float)sin(ang));
 }
 
-// ROPE_TABLE: take (cos, sin) from the table `rope` [d_head / 2] for this position instead
-// of evaluating the angle on the spot.
-template <typename WT, int EPI, bool ROPE_TABLE = false, bool COH = false>
+// ROPE_GIVEN: the caller supplies (cos, sin) of this unit's rotary angle in `given` instead
+// of having the angle evaluated on the spot.
+template <typename WT, int EPI, bool ROPE_GIVEN = false, bool COH = false>
 __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float acc0, float acc1, int pos,
-                                              const float2 *rope = nullptr) {
+                                              float2 given = make_float2(1.f, 0.f)) {
     if (EPI == EPI_PLAIN) {
         act_store<COH>(a.y + 2 * unit, acc0);
         act_store<COH>(a.y + 2 * unit + 1, acc1);
@@ -152,7 +152,7 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
         const int r0 = 2 * unit;
         if (r0 < a.n_q_rows + a.n_kv_rows) {
             const int i = (r0 % a.d_head) / 2;
-            const float2 cs = ROPE_TABLE ? rope[i] : rope_cos_sin(a.inv_freq, i, pos);
+            const float2 cs = ROPE_GIVEN ? given : rope_cos_sin(a.inv_freq, i, pos);
             const float c = cs.x, s = cs.y;
             const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
             const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));

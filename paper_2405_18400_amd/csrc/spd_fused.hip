@@ -19,13 +19,23 @@ namespace {
 
 // One block per CU (fewer barrier participants), 16 waves: two groups of NW waves; the waves
 // of a group read one matrix row side by side, the groups work on different rows.
-constexpr int NT = 1024;          // threads per block
+#ifndef SPD_FUSED_NT
+#define SPD_FUSED_NT 1024
+#endif
+#ifndef SPD_FUSED_UA
+#define SPD_FUSED_UA 8            // rows per tile where one pass covers a row
+#endif
+#ifndef SPD_FUSED_UB
+#define SPD_FUSED_UB 2            // rows per tile where a row takes three passes
+#endif
+constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
+constexpr int MAX_U = 16;
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
 struct FusedShared {
-    float part[2][NG][8][NW];     // [buffer][row group][tile slot][wave]
+    float part[2][NG][MAX_U][NW]; // [buffer][row group][tile slot][wave]
     float red[NT / WAVE];
     float sc[ATTN_CHUNK];
     int s_last;
@@ -103,7 +113,8 @@ struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
     static constexpr int UT = U / 2;   // units per tile
     static constexpr int NS = U * P;
-    static_assert(U % 2 == 0 && NS <= NBUF && U <= 8, "tile does not fit the register window");
+    static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U, "tile does not fit the register window");
+    static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
 
     static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
 
@@ -148,14 +159,20 @@ struct Gemv {
         int lo, hi;
         block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
         if (lo < hi) {
-            // this lane's slice of x (RMS-normalised when a gain is given)
+            // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
+            // depend on any activation, so its load goes out first
             float xr[P][VEC];
             uint32_t coff[P];
+            u32x4 graw[P];
             float ss = 0.f;
 #pragma unroll
             for (int p = 0; p < P; ++p) {
-                const int c = ((p * NW + w) * WAVE + lane) * VEC;
                 coff[p] = col_offset(a, p);
+                if (a.gain != nullptr) graw[p] = global_load16((const char *)a.gain + coff[p]);
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int c = ((p * NW + w) * WAVE + lane) * VEC;
 #pragma unroll
                 for (int v = 0; v < VEC; v += 4) {
                     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -169,15 +186,22 @@ struct Gemv {
                 const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
-                    const int c = ((p * NW + w) * WAVE + lane) * VEC;
+                    float gf[VEC];
+                    Store<WT>::unpack(graw[p], gf);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v)
-                        if (c < a.cols) xr[p][v] = xr[p][v] * rs * Store<WT>::load1(a.gain, c + v);
+                    for (int v = 0; v < VEC; ++v) xr[p][v] = xr[p][v] * rs * gf[v];   // x is 0 past the row end
                 }
             }
             int pb = 0;
             for (int u0 = lo; u0 < hi; u0 += NG * UT) {
                 const bool more = u0 + NG * UT < hi;
+                // what the epilogue thread of unit u0 + tid will need from memory: ask now
+                const int eu = min(u0 + tid, hi - 1);
+                float e0 = 0.f, e1 = 0.f;
+                if (tid < NG * UT) {
+                    if (EPI == EPI_RESID) { e0 = a.resid[2 * eu]; e1 = a.resid[2 * eu + 1]; }
+                    if (EPI == EPI_QKV) { const float2 cs = rope[((2 * eu) % a.d_head) / 2]; e0 = cs.x; e1 = cs.y; }
+                }
 #pragma unroll
                 for (int s = 0; s < U; ++s) {
                     float acc = 0.f;
@@ -200,12 +224,18 @@ struct Gemv {
                     float r0 = 0.f, r1 = 0.f;
 #pragma unroll
                     for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][s0][q]; r1 += sh.part[pb][eg][s1][q]; }
-                    gemv_epilogue<WT, EPI, true, true>(a, u0 + tid, r0, r1, pos, rope);
+                    if (EPI == EPI_RESID) {
+                        act_store<true>(a.y + 2 * eu, e0 + r0);
+                        act_store<true>(a.y + 2 * eu + 1, e1 + r1);
+                    } else {
+                        gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, make_float2(e0, e1));
+                    }
                 }
                 pb ^= 1;
             }
         }
-        wait_stores();
+        // only wave 0 stored anything; the others request the next phase's first tile at once
+        if (tid < WAVE) wait_stores();
         Next::prefetch(na, buf);
     }
 };
@@ -223,7 +253,8 @@ struct FusedArgs {
     int32_t *counters;
     const double *inv_freq;
     float2 *rope;                      // [d_head / 2] (cos, sin) of this step's position
-    long long *prof;                   // optional: block 0 stamps wall_clock64() around every barrier
+    long long *prof;                   // optional: one block stamps wall_clock64() around every barrier
+    int32_t prof_block;
     unsigned *barrier;
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
@@ -269,9 +300,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 
 #define SPD_BARRIER()                                                                   \
     do {                                                                                \
-        if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();      \
+        if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();      \
         grid_barrier(a.barrier, ++epoch, &st->err);                         \
-        if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch - 1] = wall_clock64();  \
+        if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
     const int pos = uniform(st->pos);
@@ -337,7 +368,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         if (l + 1 < a.n_layers || a.head) SPD_BARRIER();
     }
     if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, a.rope, sh, buf);
-    if (a.prof && blockIdx.x == 0 && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();
+    if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();
 #undef SPD_BARRIER
 }
 
@@ -373,8 +404,8 @@ static bool fused_variant(int dtype, int d_model, int d_ffn, int &pa, int &pb) {
 int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
     int pa, pb;
     if (!fused_variant(dtype, d_model, d_ffn, pa, pb)) return 0;
-    if (dtype == SPD_DTYPE_BF16) return pb == 1 ? fused_blocks_per_cu<bf16_t, 1, 8, 1, 8>() : fused_blocks_per_cu<bf16_t, 1, 8, 3, 2>();
-    return pb == 1 ? fused_blocks_per_cu<float, 1, 8, 1, 8>() : fused_blocks_per_cu<float, 1, 8, 3, 2>();
+    if (dtype == SPD_DTYPE_BF16) return pb == 1 ? fused_blocks_per_cu<bf16_t, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>() : fused_blocks_per_cu<bf16_t, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>();
+    return pb == 1 ? fused_blocks_per_cu<float, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>() : fused_blocks_per_cu<float, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>();
 }
 
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int blocks) {
@@ -382,15 +413,15 @@ hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int b
     a.sup = h.sup; a.layers = h.layers; a.final_norm = h.final_norm; a.lm_head = h.lm_head;
     a.act = h.act; a.al = h.al; a.logits = h.logits;
     a.kv = h.kv; a.kv_layer_bytes = h.kv_layer_bytes; a.part = h.part; a.counters = h.counters;
-    a.inv_freq = h.inv_freq; a.rope = h.rope; a.prof = h.prof; a.barrier = h.barrier;
+    a.inv_freq = h.inv_freq; a.rope = h.rope; a.prof = h.prof; a.prof_block = h.prof_block; a.barrier = h.barrier;
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
     a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
     a.eps = h.eps;
     int pa, pb;
     if (!fused_variant(dtype, h.d_model, h.d_ffn, pa, pb)) return hipErrorInvalidValue;
     if (dtype == SPD_DTYPE_BF16)
-        return pb == 1 ? launch_fused<bf16_t, 1, 8, 1, 8>(s, a, blocks) : launch_fused<bf16_t, 1, 8, 3, 2>(s, a, blocks);
-    return pb == 1 ? launch_fused<float, 1, 8, 1, 8>(s, a, blocks) : launch_fused<float, 1, 8, 3, 2>(s, a, blocks);
+        return pb == 1 ? launch_fused<bf16_t, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>(s, a, blocks) : launch_fused<bf16_t, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>(s, a, blocks);
+    return pb == 1 ? launch_fused<float, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>(s, a, blocks) : launch_fused<float, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>(s, a, blocks);
 }
 
 }  // namespace spdk

@@ -160,7 +160,8 @@ struct FusedArgsHost {
     int32_t *counters;
     const double *inv_freq;
     float2 *rope;                      // [d_head / 2] scratch: (cos, sin) at this step's position
-    long long *prof;                   // optional [2 * (5 n_layers + 2)] clock stamps of block 0
+    long long *prof;                   // optional [2 * (5 n_layers + 2)] clock stamps of one block
+    int32_t prof_block;
     unsigned *barrier;                 // zero at launch
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;

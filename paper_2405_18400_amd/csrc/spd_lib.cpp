@@ -184,7 +184,9 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.act = act; f.al = al; f.logits = c->at<float>(c->L.logits);
         f.kv = c->ws + c->L.kv; f.kv_layer_bytes = c->L.kv_layer_bytes;
         f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
-        f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr; f.barrier = c->at<unsigned>(c->L.barrier);
+        f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr;
+        f.prof_block = 0;
+        if (const char *e = getenv("SPD_PROF_BLOCK")) f.prof_block = atoi(e) % c->fused_blocks; f.barrier = c->at<unsigned>(c->L.barrier);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
         f.head = head ? 1 : 0; f.eps = m.rms_eps;
