@@ -58,8 +58,28 @@ typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const f32x4 __attribute__((address_space(1))) *global_f32x4_ptr;
 
+// Weight rows are streamed with raw buffer loads: the matrix is described once by a
+// resource descriptor in scalar registers, a row is a scalar byte offset and only the
+// lane's column offset sits in a vector register -- no 64-bit per-lane address arithmetic.
+// Reads past the end of the matrix return zero instead of touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_resource(const void *base, size_t bytes) {
+    const uint32_t n = bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
+}
+__device__ __forceinline__ u32x4 stream_load16(__amdgpu_buffer_rsrc_t m, uint32_t row_offset, uint32_t lane_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(m, (int)lane_offset, (int)row_offset, 2);   // 2 = non-temporal
+}
+
+typedef const char __attribute__((address_space(1))) *global_char_ptr;
+
 __device__ __forceinline__ u32x4 stream_load16(const void *p) {
     return __builtin_nontemporal_load((global_u32x4_ptr)p);   // weights are read once per step
+}
+// Same, from a wave-uniform base plus a per-lane 32-bit byte offset: written so that the
+// load can take the base from scalar registers and only the offset from a vector register.
+__device__ __forceinline__ u32x4 stream_load16(const void *uniform_base, uint32_t lane_offset) {
+    const global_char_ptr b = (global_char_ptr)uniform_base;
+    return __builtin_nontemporal_load((global_u32x4_ptr)(b + lane_offset));
 }
 __device__ __forceinline__ u32x4 global_load16(const void *p) { return *(global_u32x4_ptr)p; }
 __device__ __forceinline__ float4 global_load_float4(const float *p) {

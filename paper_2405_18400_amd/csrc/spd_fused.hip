@@ -17,16 +17,17 @@ using namespace spdd;
 
 namespace {
 
-// One block per CU (fewer barrier participants), 16 waves: two groups of NW waves; the waves
-// of a group read one matrix row side by side, the groups work on different rows.
+// One block per CU (few barrier participants).  With 512 threads: 8 waves that read one matrix
+// row side by side and have 256 vector registers each, i.e. room for a 16 KB weight tile in
+// flight per wave.  (1024 threads = two such row groups with half the registers.)
 #ifndef SPD_FUSED_NT
-#define SPD_FUSED_NT 1024
+#define SPD_FUSED_NT 512
 #endif
 #ifndef SPD_FUSED_UA
-#define SPD_FUSED_UA 8            // rows per tile where one pass covers a row
+#define SPD_FUSED_UA 16           // rows per tile where one pass covers a row
 #endif
 #ifndef SPD_FUSED_UB
-#define SPD_FUSED_UB 2            // rows per tile where a row takes three passes
+#define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
@@ -89,6 +90,16 @@ __device__ __forceinline__ spd_layer_weights uniform(const spd_layer_weights &w)
     return r;
 }
 
+__device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
+    GemvArgs r = a;
+    r.W = uniform(a.W); r.W2 = uniform(a.W2); r.gain = uniform(a.gain); r.x = uniform(a.x);
+    r.resid = uniform(a.resid); r.y = uniform(a.y); r.rows = uniform(a.rows); r.cols = uniform(a.cols);
+    r.kcache = uniform(a.kcache); r.vcache = uniform(a.vcache);
+    r.n_q_rows = uniform(a.n_q_rows); r.n_kv_rows = uniform(a.n_kv_rows); r.d_head = uniform(a.d_head);
+    r.cap_ctx = uniform(a.cap_ctx);
+    return r;
+}
+
 // Wait until this wave's stores have been acknowledged.  Called before the next phase's
 // weights are requested, so it never waits for those.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -105,9 +116,9 @@ __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &h
 // registers.  The moment a piece has been multiplied in, its register is re-used for the same
 // piece of the block's next tile, so a wave always has about NS loads in flight; after the
 // last tile the first tile of the NEXT phase is requested, before the device-wide barrier.
-// Loads are never predicated: a row past the block's range re-reads the last valid row and a
-// column past the row end re-reads the row's last 16 bytes (x is zero there), which costs
-// cache hits, not HBM traffic, and keeps the inner loop free of branches.
+// Loads are never predicated: a row past the block's range re-reads the last valid row (a
+// cache hit), and a column past the row end reads into the next row, where x is zero (past
+// the end of the matrix the buffer load returns zero); the inner loop has no branches.
 template <typename WT, int P, int U, int EPI, int NBUF>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
@@ -122,7 +133,7 @@ struct Gemv {
     static __device__ __forceinline__ uint32_t col_offset(const GemvArgs &a, int p) {
         const int lane = threadIdx.x & (WAVE - 1), w = (threadIdx.x / WAVE) % NW;
         const int c = ((p * NW + w) * WAVE + lane) * VEC;
-        return (uint32_t)min(c, a.cols - VEC) * (uint32_t)sizeof(WT);
+        return (uint32_t)c * (uint32_t)sizeof(WT);   // past the row end: the next row (x is 0 there) or zero
     }
 
     // Piece q = s * P + p of this wave's row group within the block tile starting at unit u0
@@ -131,15 +142,16 @@ struct Gemv {
         const int s = q / P, p = q % P;
         const int g = __builtin_amdgcn_readfirstlane(threadIdx.x / (WAVE * NW));
         const int unit = min(u0 + g * UT + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
-        const size_t row_bytes = (size_t)a.cols * sizeof(WT);
-        const char *base;
-        if (EPI == EPI_SWIGLU) base = (const char *)(s < UT ? a.W : a.W2) + (size_t)unit * row_bytes;
-        else base = (const char *)a.W + (size_t)(2 * unit + (s & 1)) * row_bytes;
-        return stream_load16(base + coff[p]);
+        const uint32_t row_bytes = (uint32_t)a.cols * (uint32_t)sizeof(WT);
+        const size_t bytes = (size_t)a.rows * row_bytes;
+        if (EPI == EPI_SWIGLU)
+            return stream_load16(matrix_resource(s < UT ? a.W : a.W2, bytes), (uint32_t)unit * row_bytes, coff[p]);
+        return stream_load16(matrix_resource(a.W, bytes), (uint32_t)(2 * unit + (s & 1)) * row_bytes, coff[p]);
     }
 
     // This block's first tile of the phase (requested by the previous phase).
-    static __device__ __forceinline__ void prefetch(const GemvArgs &a, u32x4 (&buf)[NBUF]) {
+    static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
+        const GemvArgs a = uniform(a_in);
         int lo, hi;
         block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
         if (lo >= hi) return;
@@ -153,8 +165,9 @@ struct Gemv {
     // Runs the phase.  On entry `buf` holds this block's first tile; on return it holds the
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
-    static __device__ __forceinline__ void run(const GemvArgs &a, const GemvArgs &na, int pos, const float2 *rope,
+    static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos, const float2 *rope,
                                                FusedShared &sh, u32x4 (&buf)[NBUF]) {
+        const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
         block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
@@ -168,7 +181,8 @@ struct Gemv {
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 coff[p] = col_offset(a, p);
-                if (a.gain != nullptr) graw[p] = global_load16((const char *)a.gain + coff[p]);
+                if (a.gain != nullptr)   // clamped: lanes past the row end must stay inside the gain vector
+                    graw[p] = global_load16((const char *)a.gain + min(coff[p], (uint32_t)((a.cols - VEC) * sizeof(WT))));
             }
 #pragma unroll
             for (int p = 0; p < P; ++p) {
