@@ -31,7 +31,7 @@ namespace {
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
-constexpr int MAX_U = 16;
+constexpr int MAX_U = 32;
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
