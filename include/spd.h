@@ -57,7 +57,7 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
     int32_t max_ctx;   /* key/value cache capacity in positions (prefix + generated)        */
     int32_t k_max;     /* largest k any spd_step will use, 1..SPD_K_MAX                     */
-    int32_t dtype;     /* spd_dtype of weights; the KV cache uses the same type             */
+    int32_t dtype;     /* spd_dtype of the weights; the KV cache is always fp32             */
     float rms_eps, rope_theta;
 } spd_model_cfg;
 

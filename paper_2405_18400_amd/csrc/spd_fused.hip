@@ -310,7 +310,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF>;
     __shared__ FusedShared sh;
-    __shared__ __align__(16) float dyn[NT * Store<WT>::VEC];
+    __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
 
 #define SPD_BARRIER()                                                                   \
     do {                                                                                \
@@ -354,7 +354,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
                        a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
             const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
             for (int item = blockIdx.x; item < a.n_kv_heads * n_splits; item += gridDim.x)
-                attn_item<WT, NT, true>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn, &sh.s_last);
+                attn_item<KvT, NT, true>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn, &sh.s_last);
             wait_stores();
         }
         SPD_BARRIER();

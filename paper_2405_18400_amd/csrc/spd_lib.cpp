@@ -26,7 +26,6 @@ struct Layout {
     ActLayout al;
 };
 
-size_t elem_size(int dtype) { return dtype == SPD_DTYPE_BF16 ? 2 : 4; }
 
 const char *check_cfg(const spd_model_cfg *c) {
     if (!c) return "cfg is null";
@@ -38,8 +37,8 @@ const char *check_cfg(const spd_model_cfg *c) {
     const int vec = c->dtype == SPD_DTYPE_BF16 ? 8 : 4;
     const int dh = c->d_model / c->n_heads;
     if (dh % vec || dh > 256) return "d_head must be a multiple of the 16-byte vector width and <= 256";
-    const int lpp = dh / vec;
-    if (lpp > 64 || (lpp & (lpp - 1))) return "d_head / vector width must be a power of two <= 64";
+    const int lpp = dh / 4;   // lanes per cached position (fp32 cache, 16-byte pieces)
+    if (dh % 4 || lpp > 64 || (lpp & (lpp - 1))) return "d_head / 4 must be a power of two <= 64";
     if (c->d_model % vec || c->d_ffn % vec) return "d_model and d_ffn must be multiples of the 16-byte vector width";
     if (c->vocab % 2) return "vocab must be even";
     if (c->max_ctx < 2) return "max_ctx must be >= 2";
@@ -84,7 +83,7 @@ Layout make_layout(const spd_model_cfg &c) {
     L.pi = take((size_t)L.n_part * SPD_K_MAX * 4);
     L.pm = take((size_t)L.n_part * 4);
     L.ps = take((size_t)L.n_part * 4);
-    L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * elem_size(c.dtype));
+    L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * sizeof(float));   // fp32 cache
     L.kv = take(L.kv_layer_bytes * 2 * (size_t)c.n_layers);
     L.total = o;
     return L;
@@ -210,7 +209,7 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         if (e != hipSuccess) return e;
         AttnArgs a{q, c->kcache(l), c->vcache(l), att, c->at<float>(c->L.part), c->at<int32_t>(c->L.counters),
                    c->st(), 0, m.n_heads, m.n_kv_heads, dh, m.max_ctx, ATTN_CHUNK, c->L.max_splits};
-        e = launch(c, KC_ATTN, [&] { return spdk::attention(c->stream, m.dtype, a); });
+        e = launch(c, KC_ATTN, [&] { return spdk::attention(c->stream, SPD_DTYPE_FP32, a); });   // the cache is fp32
         if (e != hipSuccess) return e;
         GemvArgs o{};
         o.W = w.wo; o.x = att; o.resid = h; o.y = h1; o.rows = m.d_model; o.cols = nq;

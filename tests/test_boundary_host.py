@@ -38,8 +38,8 @@ def test_every_declared_symbol_is_exported(pkg):
 def test_workspace_bytes_and_config_validation(pkg):
     cfg = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)
     need = pkg.spd_workspace_bytes(cfg)
-    kv = 2 * 32 * 32 * 128 * 128 * 2                      # K and V, 32 layers, 32 heads, 128 positions, d_head 128, bf16
-    assert kv <= need < kv + 4 * 2 ** 20
+    kv = 2 * 32 * 32 * 128 * 128 * 4                      # K and V, 32 layers, 32 heads, 128 positions, d_head 128, fp32
+    assert kv <= need < kv + 8 * 2 ** 20
     for field, bad in [("dtype", 7), ("n_heads", 3), ("n_kv_heads", 5), ("k_max", 17), ("k_max", 0), ("max_ctx", 1),
                        ("vocab", 31999), ("d_ffn", 11004), ("d_model", 0)]:
         c = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)

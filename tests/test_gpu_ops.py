@@ -63,7 +63,7 @@ def test_swiglu(dtype, rows, cols):
 
 @pytest.mark.parametrize("dtype,dh", [("bf16", 128), ("fp32", 64), ("bf16", 64), ("fp32", 128)])
 @pytest.mark.parametrize("heads,kv", [(4, 4), (8, 1), (8, 2)])
-@pytest.mark.parametrize("n_ctx,cap", [(1, 8), (7, 300), (256, 256), (257, 600), (1044, 1100)])
+@pytest.mark.parametrize("n_ctx,cap", [(1, 8), (7, 300), (128, 128), (129, 300), (256, 256), (257, 600), (1044, 1100)])
 def test_attention(dtype, dh, heads, kv, n_ctx, cap):
     rng = np.random.default_rng(n_ctx + heads)
     Kst, K = mat(kv * cap, dh, dtype, 11, std=1.0)

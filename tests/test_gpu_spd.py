@@ -40,10 +40,27 @@ def tiny():
     return shape, w, tabs, prefix
 
 
-def run_teacher_forced(shape, w, tabs, lambdas, prefix, k, alpha, n_tokens, tau=1.0, delta=0.1, max_ctx=64):
+@pytest.fixture(params=["fused", "per_operator"])
+def forward_path(request):
+    """Both ways the library can run the transformer forward: one persistent kernel, or one
+    kernel per matrix-vector product."""
+    return request.param
+
+
+def select_path(sess, path):
+    if path == "fused":
+        assert sess.spd_get_fused(), "no fused forward kernel was selected for this shape"
+    else:
+        sess.spd_set_fused(False)
+        assert not sess.spd_get_fused()
+
+
+def run_teacher_forced(shape, w, tabs, lambdas, prefix, k, alpha, n_tokens, tau=1.0, delta=0.1, max_ctx=64,
+                       path="fused"):
     pkg = P()
     sess = session(shape, w, max_ctx=max_ctx)
     try:
+        select_path(sess, path)
         if tabs is not None:
             sess.spd_load_ngrams(tabs, lambdas)
         dc = pkg.SpdDecodeCfg(k, alpha, tau, delta)
@@ -56,19 +73,19 @@ def run_teacher_forced(shape, w, tabs, lambdas, prefix, k, alpha, n_tokens, tau=
         sess.close()
 
 
-def test_tiny_config_as_specified(tiny):
+def test_tiny_config_as_specified(tiny, forward_path):
     """BASELINE config 1: 2-layer fp32 model, bigram+trigram tables, k = 3, 10 tokens, alpha 0.5."""
     shape, w, tabs, prefix = tiny
     lam = (0.01, 0.04, 0.0, 0.0, 0.0)
-    _, recs, stats = run_teacher_forced(shape, w, tabs, lam, prefix, 3, 0.5, 10)
+    _, recs, stats = run_teacher_forced(shape, w, tabs, lam, prefix, 3, 0.5, 10, path=forward_path)
     assert sum(s.get("vocab_decisive", False) for s in stats) >= 8
 
 
-def test_tiny_config_with_planted_hits(tiny):
+def test_tiny_config_with_planted_hits(tiny, forward_path):
     shape, w, tabs, prefix = tiny
     lam = (0.01, 0.04, 0.0, 0.0, 0.0)
     planted = planted_tables(shape, w, tabs, prefix, 3, 10)
-    _, recs, stats = run_teacher_forced(shape, w, planted, lam, prefix, 3, 0.5, 10)
+    _, recs, stats = run_teacher_forced(shape, w, planted, lam, prefix, 3, 0.5, 10, path=forward_path)
     assert any(c.overlap for r in recs[1:] for c in r.candidates), "planting produced no n-gram hit"
     assert any(not c.overlap for r in recs[1:] for c in r.candidates)
 
@@ -82,20 +99,47 @@ def test_tiny_k_sweep_all_orders(tiny, k, alpha):
     run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, k, alpha, 6, tau=0.7)
 
 
-def test_bf16_small_model_gqa():
+def test_bf16_small_model_gqa(forward_path):
     shape = synth.ModelShape("small-bf16", 3, 512, 8, 2, 1408, 2048, "bf16")
     w = synth.make_weights(shape, seed=5)
     prefix = synth.make_prefix_zipf(shape.vocab, 37, seed=5)
     base = synth.make_ngram_tables_zipf(shape.vocab, 30_000, seed=5)
     planted = planted_tables(shape, w, base, prefix, 3, 8)
-    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8)
+    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8, path=forward_path)
 
 
-def test_long_prefix_crosses_attention_chunks():
+def test_long_prefix_crosses_attention_chunks(forward_path):
     shape = synth.ModelShape("small-fp32", 2, 256, 4, 2, 512, 1024, "fp32")
     w = synth.make_weights(shape, seed=6)
     prefix = synth.make_prefix_uniform(shape.vocab, 300, seed=6)
-    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=600)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=600, path=forward_path)
+
+
+def test_wide_ffn_three_pass_rows(forward_path):
+    """d_ffn wider than one block pass (bf16: 4096 columns), ragged against the pass width,
+    like the 7B shape's 11008: exercises the multi-pass rows of the fused kernel."""
+    shape = synth.ModelShape("wide-ffn-bf16", 2, 512, 4, 4, 4096 * 2 + 1416, 1024, "bf16")
+    w = synth.make_weights(shape, seed=7)
+    prefix = synth.make_prefix_uniform(shape.vocab, 21, seed=7)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 2, 0.0, 5, path=forward_path)
+
+
+def test_fused_and_per_operator_forward_agree(tiny):
+    """Same inputs through both forward paths: logits agree to fp32 rounding, drafts are equal."""
+    shape, w, tabs, prefix = tiny
+    pkg = P()
+    out = {}
+    for path in ("fused", "per_operator"):
+        sess = session(shape, w)
+        try:
+            select_path(sess, path)
+            sess.spd_prefill(prefix)
+            logits = sess.spd_read_logits()
+            drafts, scores = sess.spd_generate(prefix, pkg.SpdDecodeCfg(3, 0.0, 1.0, 0.1), 6)
+            out[path] = (logits, drafts, scores)
+        finally:
+            sess.close()
+    np.testing.assert_allclose(out["fused"][0], out["per_operator"][0], rtol=0, atol=2e-5 * np.abs(out["fused"][0]).max())
 
 
 def test_generate_free_running_matches_until_first_undecided_step(tiny):
@@ -235,5 +279,34 @@ def test_error_paths(tiny):
             with pytest.raises(pkg.SpdError) as e:
                 sess.spd_load_ngrams({2: (np.array(keys, np.int32), np.array(counts, np.uint32))}, synth.PAPER_LAMBDAS)
             assert e.value.code == -5
+    finally:
+        sess.close()
+
+
+@pytest.mark.timeout(900)
+def test_full_size_7b_shape_teacher_forced():
+    """BASELINE config 2 at its real size and in the launch configuration the benchmark times
+    (fused forward, graph replay): Llama-2-7B shape, bf16, 64-token Zipf prefix, k = 3,
+    alpha = 0.54, synthetic n = 2..6 tables.  The oracle runs the full model on the host (a few
+    seconds per step), so three timesteps are compared, teacher-forced."""
+    pkg = P()
+    shape = synth.LLAMA7B
+    wdev = synth.make_weights_device(shape, seed=0)
+    host = {k: synth.host_view(v) for k, v in wdev.items() if not k.endswith("wqkv")}
+    prefix = synth.make_prefix_zipf(shape.vocab, 64, seed=0)
+    base = synth.make_ngram_tables_zipf(shape.vocab, 200_000, seed=0)
+    lm = make_oracle(shape, host)
+    _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(3, 0.0), 3)
+    visits = [(tuple(r.state_in.history(i)), int(t)) for r in recs0[1:] for i in range(3) for t in r.top_ids]
+    tabs = synth.plant_ngrams(base, visits, shape.vocab, seed=1, frac=0.5)
+    sess = pkg.Session(shape, wdev, max_ctx=128, k_max=8)
+    try:
+        assert sess.spd_get_fused()
+        sess.spd_load_ngrams(tabs, synth.PAPER_LAMBDAS)
+        dc = pkg.SpdDecodeCfg(3, 0.54, 1.0, 0.1)
+        cfg = O.DecodeCfg(3, 0.54, 1.0, 0.1, synth.PAPER_LAMBDAS)
+        _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, 3, RTOL["bf16"], dc)
+        assert all("logit_err" in s for s in stats)
+        print("7B scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats])
     finally:
         sess.close()
