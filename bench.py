@@ -40,6 +40,20 @@ def algorithmic_bytes(shape, ctx_positions: float) -> dict:
             "step": shape.n_layers * (qkv + o + gateup + down) + head + kv_pos * ctx_positions}
 
 
+def recorded_traffic(workload: str, k: int):
+    """HBM bytes per launch of the fused forward kernel as counted by rocprofv3 (FETCH_SIZE +
+    WRITE_SIZE, scaled by a plain copy): taken from the committed counter summary of this
+    workload, since counters cannot be read from inside the benchmark.  None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"spd_step_{workload}_k{k}_hbm_counters.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta):
     """The CPU oracle, as it stands, timed on this host.  A full 7B-shaped step would take
     minutes in numpy, so the sample is the same step on depth-truncated copies of the model
@@ -102,6 +116,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a known traffic for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the SPD step is a single-GPU, batch-1 path); "
@@ -188,15 +204,17 @@ def main():
         # dominant kernel: the fused forward (the whole model in one launch) where it runs,
         # else the largest matrix-vector product
         fwd_bytes = ab["step"]
+        traffic = None
         if "fused_forward" in kernels:
             dom, dom_bytes = "fused_forward", fwd_bytes
+            traffic = recorded_traffic(args.workload, k)
         else:
             dom, dom_bytes = "gemv_gateup", ab["gemv_gateup"]
         if dom in kernels:
             gbs = dom_bytes / (kernels[dom]["avg_us"] * 1e-6) / 1e9
             kernels[dom]["GBps"] = gbs
             roofline = {"bound": "hbm", "kernel": dom, "achieved": gbs, "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                        "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                         "bytes_per_launch": dom_bytes, "avg_launch_us": kernels[dom]["avg_us"],
                         "step_achieved": step_gbs, "step_frac": step_gbs / HBM_PEAK_GBS,
                         "step_bytes": ab["step"]}
@@ -238,6 +256,13 @@ def main():
         "generate_10_tokens_ms": e2e_ms,
         "setup_s": t_setup,
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes"] = 1 << 30
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta)
     sess.close()
