@@ -185,7 +185,7 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
         f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr;
         f.prof_block = 0;
-        if (const char *e = getenv("SPD_PROF_BLOCK")) f.prof_block = atoi(e) % c->fused_blocks; f.barrier = c->at<unsigned>(c->L.barrier);
+        f.barrier = c->at<unsigned>(c->L.barrier);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
         f.head = head ? 1 : 0; f.eps = m.rms_eps;
@@ -355,7 +355,6 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     {   // the fused forward needs its whole grid resident at once: size it from the occupancy
         int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
         if (per_cu > 1) per_cu = 1;
-        if (const char *e = getenv("SPD_FUSED_BLOCKS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v < per_cu) per_cu = v; }
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
         if (c->fused_blocks > BAR_GROUP * BAR_MAX_GROUPS) c->fused_blocks = 0;
     }
