@@ -75,7 +75,7 @@ def lib():
             "spd_position": [vp, C.POINTER(i32)],
             "spd_set_graph": [vp, i32],
             "spd_set_kernel_timing": [vp, i32],
-            "spd_get_phase_clock": [vp, i32, C.POINTER(C.c_int64), C.POINTER(i32)],
+            "spd_get_phase_clock": [vp, i32, C.POINTER(C.c_int64), C.POINTER(i32), C.POINTER(i32)],
             "spd_set_fused": [vp, i32],
             "spd_get_fused": [vp, C.POINTER(i32)],
             "spd_get_kernel_timing": [vp, i32, C.POINTER(C.c_char_p), C.POINTER(f32), C.POINTER(C.c_int64), C.POINTER(i32)],
@@ -296,10 +296,12 @@ class Session:
         return {names[i].decode(): (ms[i], cnt[i]) for i in range(n.value)}
 
     def spd_get_phase_clock(self):
-        cap = 2 * (5 * self.shape.n_layers + 2)
-        out, n = (C.c_int64 * cap)(), C.c_int32(0)
-        self._chk(self.L.spd_get_phase_clock(self.ctx, cap, out, C.byref(n)), "spd_get_phase_clock")
-        return np.array(out[:n.value], dtype=np.int64)
+        """Clock stamps [blocks, 2 (5 n_layers + 2)] of the most recent fused forward."""
+        cap = 2 * (5 * self.shape.n_layers + 2) * 2048
+        out, n, nb = np.zeros(cap, dtype=np.int64), C.c_int32(0), C.c_int32(0)
+        self._chk(self.L.spd_get_phase_clock(self.ctx, cap, out.ctypes.data_as(C.POINTER(C.c_int64)), C.byref(n),
+                                             C.byref(nb)), "spd_get_phase_clock")
+        return out[:n.value * nb.value].reshape(nb.value, n.value).copy()
 
     def synchronize(self):
         self.stream.synchronize()

@@ -21,10 +21,10 @@ template <> struct Store<float> {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
-    static __device__ __forceinline__ float load1(const void *p, size_t i) { return ((const float *)p)[i]; }
-    static __device__ __forceinline__ void store1(void *p, size_t i, float v) { ((float *)p)[i] = v; }
+    static __device__ __forceinline__ float load1(const void *p, size_t i) { return ((const float __attribute__((address_space(1))) *)p)[i]; }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) { ((float __attribute__((address_space(1))) *)p)[i] = v; }
     static __device__ __forceinline__ void store1_coherent(void *p, size_t i, float v) {
-        __hip_atomic_store((float *)p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store((float __attribute__((address_space(1))) *)p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 };
 template <> struct Store<bf16_t> {
@@ -36,17 +36,17 @@ template <> struct Store<bf16_t> {
         f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
     }
     static __device__ __forceinline__ float load1(const void *p, size_t i) {
-        return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
+        return __uint_as_float((uint32_t)((const uint16_t __attribute__((address_space(1))) *)p)[i] << 16);
     }
     static __device__ __forceinline__ void store1(void *p, size_t i, float v) {
         uint32_t u = __float_as_uint(v);               // round to nearest even
         u += 0x7FFFu + ((u >> 16) & 1u);
-        ((uint16_t *)p)[i] = (uint16_t)(u >> 16);
+        ((uint16_t __attribute__((address_space(1))) *)p)[i] = (uint16_t)(u >> 16);
     }
     static __device__ __forceinline__ void store1_coherent(void *p, size_t i, float v) {
         uint32_t u = __float_as_uint(v);
         u += 0x7FFFu + ((u >> 16) & 1u);
-        __hip_atomic_store((uint16_t *)p + i, (uint16_t)(u >> 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store((uint16_t __attribute__((address_space(1))) *)p + i, (uint16_t)(u >> 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 };
 
@@ -54,6 +54,8 @@ template <> struct Store<bf16_t> {
 // compiler, and generic loads are slower than global ones here in a way that matters: they
 // also count as LDS traffic, so every LDS wait would drain the weight stream.  Everything
 // this library reads in bulk is global memory, and says so.
+template <typename T> using global_ptr = T __attribute__((address_space(1))) *;
+template <typename T> __device__ __forceinline__ global_ptr<T> as_global(T *p) { return (global_ptr<T>)p; }
 typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const f32x4 __attribute__((address_space(1))) *global_f32x4_ptr;
@@ -90,7 +92,7 @@ __device__ __forceinline__ float4 global_load_float4(const float *p) {
 // Read data another workgroup (possibly on another XCD, behind another L2) wrote and
 // published with a device-scope fence.
 __device__ __forceinline__ float coherent_load(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Activation traffic between workgroups.  COH = true (the persistent kernel): stores are
@@ -101,12 +103,12 @@ __device__ __forceinline__ float coherent_load(const float *p) {
 // places that re-read an address within a launch (attention partials) use act_load<true>.
 // COH = false (one kernel per operator): ordinary accesses; the kernel boundary orders them.
 template <bool COH> __device__ __forceinline__ float act_load(const float *p) {
-    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return *p;
+    if (COH) return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *as_global(p);
 }
 template <bool COH> __device__ __forceinline__ void act_store(float *p, float v) {
-    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
+    if (COH) __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *as_global(p) = v;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -156,7 +158,7 @@ typedef float KvT;
 // EPI_SWIGLU row `unit` of the gate and of the up matrix).
 // cos/sin of pos * theta^(-2i/d_head), computed in double as the reference does.
 __device__ __forceinline__ float2 rope_cos_sin(const double *inv_freq, int i, int pos) {
-    const double ang = (double)pos * inv_freq[i];
+    const double ang = (double)pos * as_global(inv_freq)[i];
     return make_float2((float)cos(ang), (float)sin(ang));
 }
 
@@ -169,8 +171,8 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
         act_store<COH>(a.y + 2 * unit, acc0);
         act_store<COH>(a.y + 2 * unit + 1, acc1);
     } else if (EPI == EPI_RESID) {
-        act_store<COH>(a.y + 2 * unit, a.resid[2 * unit] + acc0);
-        act_store<COH>(a.y + 2 * unit + 1, a.resid[2 * unit + 1] + acc1);
+        act_store<COH>(a.y + 2 * unit, as_global(a.resid)[2 * unit] + acc0);
+        act_store<COH>(a.y + 2 * unit + 1, as_global(a.resid)[2 * unit + 1] + acc1);
     } else if (EPI == EPI_SWIGLU) {
         act_store<COH>(a.y + unit, acc0 / (1.0f + expf(-acc0)) * acc1);
     } else {  // EPI_QKV: rotary on q and k pairs, append k and v to the cache
@@ -224,25 +226,47 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     const char *Kg = (const char *)a.K + (size_t)g * a.cap_ctx * dh * sizeof(KT);
     const char *Vg = (const char *)a.V + (size_t)g * a.cap_ctx * dh * sizeof(KT);
 
+    // Cached rows are requested ATTN_BATCH at a time per lane, and the first batch of value
+    // rows together with the keys: this phase is a chain of memory latencies, not bandwidth.
+    constexpr int ATTN_BATCH = 8;
+    const int tbase = t0 + wid * PPW + sub;
     for (int hq = 0; hq < group; ++hq) {
         const int h = g * group + hq;
         float qv[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) qv[v] = a.q[(size_t)h * dh + li * VEC + v];
+        for (int v = 0; v < VEC; ++v) qv[v] = as_global(a.q)[(size_t)h * dh + li * VEC + v];
         float lmax = -INFINITY;
-        for (int t = t0 + wid * PPW + sub; t - sub < t1; t += PPB) {   // t - sub is wave-uniform
-            float d = 0.f;
-            if (t < t1) {
+        u32x4 vb[ATTN_BATCH];
+        for (int b0 = tbase; b0 - sub < t1; b0 += ATTN_BATCH * PPB) {   // b0 - sub is wave-uniform
+            u32x4 kb[ATTN_BATCH];
+#pragma unroll
+            for (int i = 0; i < ATTN_BATCH; ++i) {
+                const int t = b0 + i * PPB;
+                kb[i] = u32x4{0u, 0u, 0u, 0u};
+                if (t < t1) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+            }
+            if (b0 == tbase) {
+#pragma unroll
+                for (int i = 0; i < ATTN_BATCH; ++i) {
+                    const int t = b0 + i * PPB;
+                    vb[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < ATTN_BATCH; ++i) {
+                const int t = b0 + i * PPB;
                 float kf[VEC];
-                Store<KT>::unpack(global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT)), kf);
+                Store<KT>::unpack(kb[i], kf);
+                float d = 0.f;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
-            }
-            for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
-            d *= scale;
-            if (t < t1) {
-                if (li == 0) sc[t - t0] = d;
-                lmax = fmaxf(lmax, d);
+                for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
+                d *= scale;
+                if (t < t1) {
+                    if (li == 0) sc[t - t0] = d;
+                    lmax = fmaxf(lmax, d);
+                }
             }
         }
         const float m = block_max<NT>(lmax, red);   // includes a barrier after the sc writes
@@ -256,12 +280,26 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         float acc[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-        for (int t = t0 + wid * PPW + sub; t < t1; t += PPB) {
-            float vf[VEC];
-            Store<KT>::unpack(global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT)), vf);
-            const float p = sc[t - t0];
+        for (int b0 = tbase; b0 < t1; b0 += ATTN_BATCH * PPB) {
+            if (b0 != tbase) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
+                for (int i = 0; i < ATTN_BATCH; ++i) {
+                    const int t = b0 + i * PPB;
+                    vb[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < ATTN_BATCH; ++i) {
+                const int t = b0 + i * PPB;
+                if (t < t1) {
+                    float vf[VEC];
+                    Store<KT>::unpack(vb[i], vf);
+                    const float p = sc[t - t0];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
+                }
+            }
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
@@ -280,7 +318,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
             else __threadfence();
             __syncthreads();
             if (tid == 0) {
-                const int old = atomicAdd(&a.counters[h], 1);
+                const int old = __hip_atomic_fetch_add(as_global(a.counters) + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 *s_last = (old == n_splits - 1);
             }
             __syncthreads();
@@ -297,7 +335,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     if (tid < dh) O += w * coherent_load(pq + 2 + tid);
                 }
                 if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
-                if (tid == 0) a.counters[h] = 0;
+                if (tid == 0) as_global(a.counters)[h] = 0;
             }
         }
         __syncthreads();   // sc / dyn / s_last are reused by the next query head or item
@@ -310,23 +348,23 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 template <typename WT, bool COH = false>
 __device__ __forceinline__ void superpose_element(const SuperposeArgs &a, int c, int pos) {
     if (a.mode == 0) {
-        const int tok = a.prefix[pos];
+        const int tok = as_global(a.prefix)[pos];
         if (c < a.d_model) act_store<COH>(a.h + c, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c));
         return;
     }
     const int k = a.k;
     float mx = -INFINITY;
-    for (int i = 0; i < k; ++i) mx = fmaxf(mx, a.st->logscore[i]);
+    for (int i = 0; i < k; ++i) mx = fmaxf(mx, as_global(a.st)->logscore[i]);
     float sum = 0.f;
-    for (int i = 0; i < k; ++i) sum += expf(a.st->logscore[i] - mx);
+    for (int i = 0; i < k; ++i) sum += expf(as_global(a.st)->logscore[i] - mx);
     float acc = 0.f;
     for (int i = 0; i < k; ++i) {
-        const float gi = expf(a.st->logscore[i] - mx) / sum;
+        const float gi = expf(as_global(a.st)->logscore[i] - mx) / sum;
         if (c < a.d_model) {
-            const int tok = a.st->tails[i][SPD_TAIL - 1];
+            const int tok = as_global(a.st)->tails[i][SPD_TAIL - 1];
             acc = __fadd_rn(acc, __fmul_rn(gi, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c)));
         }
-        if (c == 0) a.st->gamma_in[i] = gi;
+        if (c == 0) as_global(a.st)->gamma_in[i] = gi;
     }
     if (c < a.d_model) act_store<COH>(a.h + c, acc);
 }

@@ -29,14 +29,24 @@ namespace {
 #ifndef SPD_FUSED_UB
 #define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
 #endif
+#ifndef SPD_FUSED_QD
+#define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested before the barrier
+#endif
+#ifndef SPD_FUSED_WIN
+#define SPD_FUSED_WIN 64          // of which at most this many are outstanding per wave
+#endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
 constexpr int MAX_U = 32;
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
+constexpr int MAX_EPI = FUSED_MAX_EPI;   // residual values a block may need in one phase
+
 struct FusedShared {
     float part[2][NG][MAX_U][NW]; // [buffer][row group][tile slot][wave]
+    float epi[MAX_EPI];           // this block's slice of the residual, staged when the phase starts
+    float2 rope[128];             // (cos, sin) of this step's position, all d_head / 2 <= 128 pairs
     float red[NT / WAVE];
     float sc[ATTN_CHUNK];
     int s_last;
@@ -45,28 +55,35 @@ struct FusedShared {
 // Device-wide barrier, two levels: blocks arrive on their group's counter (BAR_GROUP
 // consecutive blocks per group, counters 256 bytes apart), the last arriver of a group bumps
 // the top counter, everyone polls the top counter.  Same-address atomics serialise at the
-// memory side (~14 ns each), so this costs about a third of one flat counter.  All counters
+// memory side (~14 ns each), so this costs about a third of one flat counter.  (One counter
+// per group polled side by side by every block, without the top level, measured slower: the
+// polls of 256 blocks on each of 8 addresses take longer than the extra hop.)  All counters
 // increase monotonically within a launch; the host-side sequence zeroes them between
 // launches.  Bounded: if the grid is not co-resident the wait gives up, raises *err, and
 // every later wait returns at once, so the kernel always drains.
+//
+// Everything other blocks will read was stored with write-through (device-scope) stores and
+// every storing wave has waited for its own stores (wait_stores) before getting here.
+// ALL_WAVES_STORED: waves other than wave 0 stored too, so the block meets before it arrives.
+// Wave 0 should have no weight loads outstanding when it gets here: memory operations of a
+// wave return in order, so the arrival count and every poll would queue behind them.
+template <bool ALL_WAVES_STORED>
 __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err) {
-    // Everything other blocks will read was stored with write-through (device-scope) stores
-    // and every wave has waited for its own stores (wait_stores) before getting here.
-    __syncthreads();
+    if (ALL_WAVES_STORED) __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned g = blockIdx.x / BAR_GROUP;
         const unsigned n_groups = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
         const unsigned my_size = min((unsigned)BAR_GROUP, gridDim.x - g * BAR_GROUP);
         unsigned *top = ctr, *grp = ctr + 64 * (1 + g);
-        const unsigned old = __hip_atomic_fetch_add(grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1 == epoch * my_size) __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned old = __hip_atomic_fetch_add(as_global(grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == epoch * my_size) __hip_atomic_fetch_add(as_global(top), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
-        while (__hip_atomic_load(top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * n_groups) {
+        while (__hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * n_groups) {
             __builtin_amdgcn_s_sleep(1);
             ++spins;
-            if ((spins & 255u) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+            if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             if (spins > SPIN_LIMIT) {
-                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
         }
@@ -99,6 +116,8 @@ __device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
     r.cap_ctx = uniform(a.cap_ctx);
     return r;
 }
+
+__device__ __forceinline__ bool is_wave0() { return __builtin_amdgcn_readfirstlane((int)threadIdx.x) < WAVE; }
 
 // Wait until this wave's stores have been acknowledged.  Called before the next phase's
 // weights are requested, so it never waits for those.
@@ -149,7 +168,10 @@ struct Gemv {
         return stream_load16(matrix_resource(a.W, bytes), (uint32_t)(2 * unit + (s & 1)) * row_bytes, coff[p]);
     }
 
-    // This block's first tile of the phase (requested by the previous phase).
+    // The head of this block's first tile, pieces [0, QD), is requested by the previous phase
+    // (at most WIN requests per wave outstanding); the rest follows the load of x.
+    static constexpr int QD = NS < SPD_FUSED_QD ? NS : SPD_FUSED_QD;
+    static constexpr int WIN = SPD_FUSED_WIN;
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
@@ -159,13 +181,59 @@ struct Gemv {
 #pragma unroll
         for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
 #pragma unroll
-        for (int q = 0; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
+        for (int q = 0; q < QD; ++q) {
+            if (q >= WIN) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN - 1) : "memory");
+            buf[q] = piece(a, lo, hi, q, coff);
+        }
+    }
+
+    // One tile: U rows of this wave's row group against x, partial sums to LDS, the block
+    // meets, the first NG * UT threads finish their units.  REFILL: every consumed register is
+    // re-requested at once with the same piece of the block's next tile.
+    template <bool REFILL>
+    static __device__ __forceinline__ void tile(const GemvArgs &a, int u0, int lo, int hi, int pos,
+                                                FusedShared &sh, u32x4 (&buf)[NBUF], const float (&xr)[P][VEC],
+                                                const uint32_t (&coff)[P], int pb) {
+        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
+        const int eu = min(u0 + tid, hi - 1);
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            float acc = 0.f;
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                float f[VEC];
+                Store<WT>::unpack(buf[s * P + p], f);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
+                if (REFILL) buf[s * P + p] = piece(a, u0 + NG * UT, hi, s * P + p, coff);
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) sh.part[pb][g][s][w] = acc;
+        }
+        __syncthreads();
+        if (tid < NG * UT && u0 + tid < hi) {   // unit u0 + tid: row group tid / UT, pair tid % UT
+            const int eg = tid / UT, t = tid % UT;
+            const int s0 = EPI == EPI_SWIGLU ? t : 2 * t;
+            const int s1 = EPI == EPI_SWIGLU ? t + UT : 2 * t + 1;
+            float r0 = 0.f, r1 = 0.f;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][s0][q]; r1 += sh.part[pb][eg][s1][q]; }
+            // what the epilogue needs beyond the sums sits in LDS: the tile loop holds no load
+            // from global memory but the weights'
+            if (EPI == EPI_RESID) {
+                act_store<true>(a.y + 2 * eu, sh.epi[2 * (eu - lo)] + r0);
+                act_store<true>(a.y + 2 * eu + 1, sh.epi[2 * (eu - lo) + 1] + r1);
+            } else {
+                const float2 cs = EPI == EPI_QKV ? sh.rope[((2 * eu) % a.d_head) / 2] : make_float2(1.f, 0.f);
+                gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, cs);
+            }
+        }
     }
 
     // Runs the phase.  On entry `buf` holds this block's first tile; on return it holds the
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
-    static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos, const float2 *rope,
+    static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
                                                FusedShared &sh, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
@@ -192,9 +260,20 @@ struct Gemv {
                     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (c < a.cols) t = global_load_float4(a.x + c + v);   // first read of a fresh address
                     xr[p][v] = t.x; xr[p][v + 1] = t.y; xr[p][v + 2] = t.z; xr[p][v + 3] = t.w;
-                    ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
                 }
             }
+            if (EPI == EPI_RESID) {   // this block's slice of the residual: 2 (hi - lo) <= MAX_EPI values
+                for (int i = tid; i < 2 * (hi - lo); i += NT) sh.epi[i] = as_global(a.resid)[2 * lo + i];
+            }
+            if (QD < NS) {   // the rest of the first tile goes out behind x, which everything waits for
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int q = QD; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) ss += xr[p][v] * xr[p][v];
             if (a.gain != nullptr) {
                 const float tot = block_sum<NT>(g == 0 ? ss : 0.f, sh.red);   // every group holds all of x
                 const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
@@ -206,51 +285,19 @@ struct Gemv {
                     for (int v = 0; v < VEC; ++v) xr[p][v] = xr[p][v] * rs * gf[v];   // x is 0 past the row end
                 }
             }
-            int pb = 0;
-            for (int u0 = lo; u0 < hi; u0 += NG * UT) {
-                const bool more = u0 + NG * UT < hi;
-                // what the epilogue thread of unit u0 + tid will need from memory: ask now
-                const int eu = min(u0 + tid, hi - 1);
-                float e0 = 0.f, e1 = 0.f;
-                if (tid < NG * UT) {
-                    if (EPI == EPI_RESID) { e0 = a.resid[2 * eu]; e1 = a.resid[2 * eu + 1]; }
-                    if (EPI == EPI_QKV) { const float2 cs = rope[((2 * eu) % a.d_head) / 2]; e0 = cs.x; e1 = cs.y; }
-                }
-#pragma unroll
-                for (int s = 0; s < U; ++s) {
-                    float acc = 0.f;
-#pragma unroll
-                    for (int p = 0; p < P; ++p) {
-                        float f[VEC];
-                        Store<WT>::unpack(buf[s * P + p], f);
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
-                        if (more) buf[s * P + p] = piece(a, u0 + NG * UT, hi, s * P + p, coff);
-                    }
-                    acc = wave_sum(acc);
-                    if (lane == 0) sh.part[pb][g][s][w] = acc;
-                }
-                __syncthreads();
-                if (tid < NG * UT && u0 + tid < hi) {   // unit u0 + tid: row group tid / UT, pair tid % UT
-                    const int eg = tid / UT, t = tid % UT;
-                    const int s0 = EPI == EPI_SWIGLU ? t : 2 * t;
-                    const int s1 = EPI == EPI_SWIGLU ? t + UT : 2 * t + 1;
-                    float r0 = 0.f, r1 = 0.f;
-#pragma unroll
-                    for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][s0][q]; r1 += sh.part[pb][eg][s1][q]; }
-                    if (EPI == EPI_RESID) {
-                        act_store<true>(a.y + 2 * eu, e0 + r0);
-                        act_store<true>(a.y + 2 * eu + 1, e1 + r1);
-                    } else {
-                        gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, make_float2(e0, e1));
-                    }
-                }
-                pb ^= 1;
-            }
+            // All tiles but the last refill their registers unconditionally; the last one has
+            // its own copy of the loop body.  (A refill under a branch makes the compiler wait
+            // for every outstanding load at the loop's back edge: the stream would stop once
+            // per tile.)
+            int pb = 0, u0 = lo;
+            for (; u0 + NG * UT < hi; u0 += NG * UT, pb ^= 1) tile<true>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
+            tile<false>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
         }
-        // only wave 0 stored anything; the others request the next phase's first tile at once
-        if (tid < WAVE) wait_stores();
-        Next::prefetch(na, buf);
+        // Only wave 0 stored anything; the others request the next phase's first tile at once.
+        // Wave 0 runs the device-wide barrier next and asks for its share after the release
+        // (see grid_barrier).
+        if (is_wave0()) wait_stores();
+        else Next::prefetch(na, buf);
     }
 };
 
@@ -266,9 +313,7 @@ struct FusedArgs {
     float *part;
     int32_t *counters;
     const double *inv_freq;
-    float2 *rope;                      // [d_head / 2] (cos, sin) of this step's position
-    long long *prof;                   // optional: one block stamps wall_clock64() around every barrier
-    int32_t prof_block;
+    long long *prof;                   // optional: every block stamps wall_clock64() around every barrier
     unsigned *barrier;
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
@@ -312,33 +357,36 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     __shared__ FusedShared sh;
     __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
 
-#define SPD_BARRIER()                                                                   \
-    do {                                                                                \
-        if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();      \
-        grid_barrier(a.barrier, ++epoch, &st->err);                         \
-        if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch - 1] = wall_clock64();  \
+#define SPD_BARRIER(ALL_WAVES_STORED)                                        \
+    do {                                                                     \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();      \
+        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err);        \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
-    const int pos = uniform(st->pos);
+    long long *prof = a.prof ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
+    const int pos = uniform(as_global(st)->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;
     unsigned epoch = 0;
 
-    // phase 0: the input vector (Section 3.1, Eq. 1 and 2) and this position's rotary table
+    // phase 0: the input vector (Section 3.1, Eq. 1 and 2); every block keeps this position's
+    // rotary table in LDS
     for (int c = blockIdx.x * NT + threadIdx.x; c < a.d_model; c += gridDim.x * NT)
         superpose_element<WT, true>(a.sup, c, pos);
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x < dh / 2)
-    {
-        const float2 cs = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
-        act_store<true>(&a.rope[threadIdx.x].x, cs.x);
-        act_store<true>(&a.rope[threadIdx.x].y, cs.y);
-    }
+    if (threadIdx.x < dh / 2) sh.rope[threadIdx.x] = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
     wait_stores();
     u32x4 buf[NBUF];
     GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
-    if (a.n_layers > 0) Qkv::prefetch(cur, buf);
-    else if (a.head) Head::prefetch(cur, buf);
-    SPD_BARRIER();
+    if (!is_wave0()) {
+        if (a.n_layers > 0) Qkv::prefetch(cur, buf);
+        else if (a.head) Head::prefetch(cur, buf);
+    }
+    SPD_BARRIER(true);
+    if (is_wave0()) {
+        if (a.n_layers > 0) Qkv::prefetch(cur, buf);
+        else if (a.head) Head::prefetch(cur, buf);
+    }
 
     for (int l = 0; l < a.n_layers; ++l) {
         const spd_layer_weights w = uniform(a.layers[l]);
@@ -346,8 +394,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
-        Qkv::template run<Oproj>(cur, o, pos, a.rope, sh, buf);
-        SPD_BARRIER();
+        Qkv::template run<Oproj>(cur, o, pos, sh, buf);
+        SPD_BARRIER(false);
+        if (is_wave0()) Oproj::prefetch(o, buf);
 
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
             AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, pos + 1,
@@ -357,32 +406,38 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
                 attn_item<KvT, NT, true>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn, &sh.s_last);
             wait_stores();
         }
-        SPD_BARRIER();
+        SPD_BARRIER(true);
 
         GemvArgs f{};
         f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
         f.rows = a.d_ffn; f.cols = a.d_model;
-        Oproj::template run<GateUp>(o, f, pos, a.rope, sh, buf);
-        SPD_BARRIER();
+        Oproj::template run<GateUp>(o, f, pos, sh, buf);
+        SPD_BARRIER(false);
+        if (is_wave0()) GateUp::prefetch(f, buf);
 
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn;
-        GateUp::template run<Down>(f, d, pos, a.rope, sh, buf);
-        SPD_BARRIER();
+        GateUp::template run<Down>(f, d, pos, sh, buf);
+        SPD_BARRIER(false);
+        if (is_wave0()) Down::prefetch(d, buf);
 
         if (l + 1 < a.n_layers) {
             cur = qkv_args(a, l + 1);
-            Down::template run<Qkv>(d, cur, pos, a.rope, sh, buf);
+            Down::template run<Qkv>(d, cur, pos, sh, buf);
         } else if (a.head) {
             cur = head_args(a);
-            Down::template run<Head>(d, cur, pos, a.rope, sh, buf);
+            Down::template run<Head>(d, cur, pos, sh, buf);
         } else {
-            Down::template run<NoNext<NBUF>>(d, d, pos, a.rope, sh, buf);
+            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf);
         }
-        if (l + 1 < a.n_layers || a.head) SPD_BARRIER();
+        if (l + 1 < a.n_layers || a.head) SPD_BARRIER(false);
+        if (is_wave0()) {
+            if (l + 1 < a.n_layers) Qkv::prefetch(cur, buf);
+            else if (a.head) Head::prefetch(cur, buf);
+        }
     }
-    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, a.rope, sh, buf);
-    if (a.prof && blockIdx.x == a.prof_block && threadIdx.x == 0) a.prof[2 * epoch] = wall_clock64();
+    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf);
+    if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();
 #undef SPD_BARRIER
 }
 
@@ -427,7 +482,7 @@ hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int b
     a.sup = h.sup; a.layers = h.layers; a.final_norm = h.final_norm; a.lm_head = h.lm_head;
     a.act = h.act; a.al = h.al; a.logits = h.logits;
     a.kv = h.kv; a.kv_layer_bytes = h.kv_layer_bytes; a.part = h.part; a.counters = h.counters;
-    a.inv_freq = h.inv_freq; a.rope = h.rope; a.prof = h.prof; a.prof_block = h.prof_block; a.barrier = h.barrier;
+    a.inv_freq = h.inv_freq; a.prof = h.prof; a.barrier = h.barrier;
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
     a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
     a.eps = h.eps;

@@ -159,14 +159,13 @@ struct FusedArgsHost {
     float *part;
     int32_t *counters;
     const double *inv_freq;
-    float2 *rope;                      // [d_head / 2] scratch: (cos, sin) at this step's position
-    long long *prof;                   // optional [2 * (5 n_layers + 2)] clock stamps of one block
-    int32_t prof_block;
+    long long *prof;                   // optional [blocks][2 * (5 n_layers + 2)] clock stamps
     unsigned *barrier;                 // zero at launch
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
 };
 
+constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_WORDS = 64 * (1 + BAR_MAX_GROUPS);

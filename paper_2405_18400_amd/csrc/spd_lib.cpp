@@ -20,7 +20,7 @@ const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_
                                     "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward"};
 
 struct Layout {
-    size_t state, barrier, layers_dev, rope, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
+    size_t state, barrier, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     int max_splits, n_part, per_part;
     ActLayout al;
@@ -62,8 +62,7 @@ Layout make_layout(const spd_model_cfg &c) {
     L.state = take(sizeof(DevState));
     L.barrier = take((size_t)BAR_WORDS * 4);
     L.layers_dev = take((size_t)(c.n_layers > 0 ? c.n_layers : 1) * sizeof(spd_layer_weights));
-    L.rope = take((size_t)(dh / 2) * 8);
-    L.prof = take((size_t)(2 * (5 * c.n_layers + 2) + 2) * 8);
+    L.prof = take((size_t)(BAR_GROUP * BAR_MAX_GROUPS) * (size_t)(2 * (5 * c.n_layers + 2)) * 8);   // per block of the largest fused grid
     {   // one address per produced vector (see ActLayout)
         const size_t vd = up((size_t)c.d_model * 4), vq = up((size_t)c.n_heads * dh * 4), vu = up((size_t)c.d_ffn * 4);
         L.al.h0 = 0;
@@ -183,8 +182,7 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.act = act; f.al = al; f.logits = c->at<float>(c->L.logits);
         f.kv = c->ws + c->L.kv; f.kv_layer_bytes = c->L.kv_layer_bytes;
         f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
-        f.inv_freq = c->at<double>(c->L.inv_freq); f.rope = c->at<float2>(c->L.rope); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr;
-        f.prof_block = 0;
+        f.inv_freq = c->at<double>(c->L.inv_freq); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr;
         f.barrier = c->at<unsigned>(c->L.barrier);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
@@ -357,6 +355,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
         if (per_cu > 1) per_cu = 1;
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
         if (c->fused_blocks > BAR_GROUP * BAR_MAX_GROUPS) c->fused_blocks = 0;
+        if (c->fused_blocks > 0 && cfg->d_model / c->fused_blocks + 4 > FUSED_MAX_EPI) c->fused_blocks = 0;   // residual slice per block
     }
 
     // rotary frequencies theta^(-2i/d_head) in double; zeroed state and attention counters
@@ -668,14 +667,16 @@ int spd_set_kernel_timing(spd_ctx *c, int32_t enable) {
     return SPD_OK;
 }
 
-int spd_get_phase_clock(spd_ctx *c, int32_t cap, int64_t *out_stamps, int32_t *out_n) {
+int spd_get_phase_clock(spd_ctx *c, int32_t cap, int64_t *out_stamps, int32_t *out_n, int32_t *out_blocks) {
     if (!c) return SPD_EINVAL;
-    if (!out_stamps || !out_n) return fail(c, SPD_EINVAL, "null output");
+    if (!out_stamps || !out_n || !out_blocks) return fail(c, SPD_EINVAL, "null output");
     const int n = 2 * (5 * c->cfg.n_layers + 2);
-    if (cap < n) return fail(c, SPD_EINVAL, "buffer too small for the phase stamps");
+    if (c->fused_blocks <= 0) return fail(c, SPD_ESTATE, "no fused forward kernel for this model shape");
+    if ((int64_t)cap < (int64_t)n * c->fused_blocks) return fail(c, SPD_EINVAL, "buffer too small for the phase stamps");
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    HIPCHK(c, hipMemcpy(out_stamps, c->ws + c->L.prof, (size_t)n * 8, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(out_stamps, c->ws + c->L.prof, (size_t)n * c->fused_blocks * 8, hipMemcpyDeviceToHost));
     *out_n = n;
+    *out_blocks = c->fused_blocks;
     return SPD_OK;
 }
 
