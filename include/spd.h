@@ -202,7 +202,8 @@ int spd_get_kernel_timing(spd_ctx *ctx, int32_t cap, const char **out_names, flo
  * stamp before and after each of its device-wide barriers (and at its end):
  * stamp[2i] = arrival at barrier i, stamp[2i+1] = release, i = 0 .. 5 n_layers (barrier 0
  * follows the input phase; each layer then has QKV, attention, O, gate/up, down).  Copies the
- * stamps of the most recent fused forward to HOST memory as [*out_blocks][*out_n] with
+ * stamps of the most recent fused forward to HOST memory as [*out_blocks][*out_n] (the first
+ * 512 blocks at most) with
  * *out_n = 2 (5 n_layers + 2); `cap` counts int64 elements of out_stamps.  SPD_ESTATE when
  * the model shape has no fused kernel. */
 int spd_get_phase_clock(spd_ctx *ctx, int32_t cap, int64_t *out_stamps, int32_t *out_n,

@@ -364,7 +364,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
-    long long *prof = a.prof ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
+    long long *prof = (a.prof && blockIdx.x < FUSED_PROF_BLOCKS) ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
     const int pos = uniform(as_global(st)->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;

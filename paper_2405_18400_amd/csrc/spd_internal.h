@@ -166,6 +166,7 @@ struct FusedArgsHost {
 };
 
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
+constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
 constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_WORDS = 64 * (1 + BAR_MAX_GROUPS);

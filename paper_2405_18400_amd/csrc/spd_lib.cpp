@@ -62,7 +62,7 @@ Layout make_layout(const spd_model_cfg &c) {
     L.state = take(sizeof(DevState));
     L.barrier = take((size_t)BAR_WORDS * 4);
     L.layers_dev = take((size_t)(c.n_layers > 0 ? c.n_layers : 1) * sizeof(spd_layer_weights));
-    L.prof = take((size_t)(BAR_GROUP * BAR_MAX_GROUPS) * (size_t)(2 * (5 * c.n_layers + 2)) * 8);   // per block of the largest fused grid
+    L.prof = take((size_t)FUSED_PROF_BLOCKS * (size_t)(2 * (5 * c.n_layers + 2)) * 8);   // phase clocks per block
     {   // one address per produced vector (see ActLayout)
         const size_t vd = up((size_t)c.d_model * 4), vq = up((size_t)c.n_heads * dh * 4), vu = up((size_t)c.d_ffn * 4);
         L.al.h0 = 0;
@@ -672,11 +672,12 @@ int spd_get_phase_clock(spd_ctx *c, int32_t cap, int64_t *out_stamps, int32_t *o
     if (!out_stamps || !out_n || !out_blocks) return fail(c, SPD_EINVAL, "null output");
     const int n = 2 * (5 * c->cfg.n_layers + 2);
     if (c->fused_blocks <= 0) return fail(c, SPD_ESTATE, "no fused forward kernel for this model shape");
-    if ((int64_t)cap < (int64_t)n * c->fused_blocks) return fail(c, SPD_EINVAL, "buffer too small for the phase stamps");
+    const int nb = c->fused_blocks < FUSED_PROF_BLOCKS ? c->fused_blocks : FUSED_PROF_BLOCKS;
+    if ((int64_t)cap < (int64_t)n * nb) return fail(c, SPD_EINVAL, "buffer too small for the phase stamps");
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    HIPCHK(c, hipMemcpy(out_stamps, c->ws + c->L.prof, (size_t)n * c->fused_blocks * 8, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(out_stamps, c->ws + c->L.prof, (size_t)n * nb * 8, hipMemcpyDeviceToHost));
     *out_n = n;
-    *out_blocks = c->fused_blocks;
+    *out_blocks = nb;
     return SPD_OK;
 }
 
