@@ -121,13 +121,38 @@ __device__ __forceinline__ float wave_max(float v) {
     for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
     return v;
 }
+// The same reductions on the vector unit's own lane-crossing paths (quad permutes, mirrors
+// within a row of 16 lanes, row broadcasts) instead of six dependent trips through the LDS
+// crossbar: a fraction of the latency.  The result is complete in lane 63 ONLY.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float v, float identity) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_last(float v) {
+    v += dpp_move<0xB1, 0xF>(v, 0.f);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E, 0xF>(v, 0.f);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xF>(v, 0.f);   // row_half_mirror
+    v += dpp_move<0x140, 0xF>(v, 0.f);   // row_mirror: every lane holds its row's sum
+    v += dpp_move<0x142, 0xA>(v, 0.f);   // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xC>(v, 0.f);   // row_bcast31 into rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ float wave_max_last(float v) {
+    v = fmaxf(v, dpp_move<0xB1, 0xF>(v, -INFINITY));
+    v = fmaxf(v, dpp_move<0x4E, 0xF>(v, -INFINITY));
+    v = fmaxf(v, dpp_move<0x141, 0xF>(v, -INFINITY));
+    v = fmaxf(v, dpp_move<0x140, 0xF>(v, -INFINITY));
+    v = fmaxf(v, dpp_move<0x142, 0xA>(v, -INFINITY));
+    v = fmaxf(v, dpp_move<0x143, 0xC>(v, -INFINITY));
+    return v;
+}
 // Sum over the block in a fixed order; every thread gets the result. `red` has NT/64 floats.
 template <int NT>
 __device__ __forceinline__ float block_sum(float v, float *red) {
     constexpr int NWAVE = NT / WAVE;
-    v = wave_sum(v);
+    v = wave_sum_last(v);
     __syncthreads();
-    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    if ((threadIdx.x & (WAVE - 1)) == WAVE - 1) red[threadIdx.x / WAVE] = v;
     __syncthreads();
     float t = 0.f;
 #pragma unroll
@@ -137,9 +162,9 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
 template <int NT>
 __device__ __forceinline__ float block_max(float v, float *red) {
     constexpr int NWAVE = NT / WAVE;
-    v = wave_max(v);
+    v = wave_max_last(v);
     __syncthreads();
-    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    if ((threadIdx.x & (WAVE - 1)) == WAVE - 1) red[threadIdx.x / WAVE] = v;
     __syncthreads();
     float t = red[0];
 #pragma unroll

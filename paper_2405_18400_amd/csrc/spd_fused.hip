@@ -207,8 +207,8 @@ struct Gemv {
                 for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
                 if (REFILL) buf[s * P + p] = piece(a, u0 + NG * UT, hi, s * P + p, coff);
             }
-            acc = wave_sum(acc);
-            if (lane == 0) sh.part[pb][g][s][w] = acc;
+            acc = wave_sum_last(acc);
+            if (lane == WAVE - 1) sh.part[pb][g][s][w] = acc;
         }
         __syncthreads();
         if (tid < NG * UT && u0 + tid < hi) {   // unit u0 + tid: row group tid / UT, pair tid % UT
