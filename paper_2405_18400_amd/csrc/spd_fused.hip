@@ -30,10 +30,10 @@ namespace {
 #define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
 #endif
 #ifndef SPD_FUSED_QD
-#define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested before the barrier
+#define SPD_FUSED_QD 8            // 16-byte pieces per lane of the next tile requested before the barrier
 #endif
 #ifndef SPD_FUSED_WIN
-#define SPD_FUSED_WIN 64          // of which at most this many are outstanding per wave
+#define SPD_FUSED_WIN 8           // of which at most this many are outstanding per wave
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
