@@ -30,10 +30,10 @@ namespace {
 #define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
 #endif
 #ifndef SPD_FUSED_QD
-#define SPD_FUSED_QD 8            // 16-byte pieces per lane of the next tile requested before the barrier
+#define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested while the block synchronises
 #endif
-#ifndef SPD_FUSED_WIN
-#define SPD_FUSED_WIN 8           // of which at most this many are outstanding per wave
+#ifndef SPD_FUSED_SLICE
+#define SPD_FUSED_SLICE 3         // of which this many go out per synchronisation step of wave 0
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
@@ -50,7 +50,22 @@ struct FusedShared {
     float red[NT / WAVE];
     float sc[ATTN_CHUNK];
     int s_last;
+    unsigned tick;                // bumped by thread 0 whenever it has issued a synchronisation step
+    unsigned released;            // number of device-wide barriers this block has been released from
 };
+
+// (volatile accesses must name the LDS address space, or they become generic-address
+// instructions, which hold up the weight stream: see spd_device.h)
+typedef volatile unsigned __attribute__((address_space(3))) *lds_flag_ptr;
+__device__ __forceinline__ lds_flag_ptr lds_flag(unsigned *p) { return (lds_flag_ptr)p; }
+
+// Thread 0 tells the other waves that one more of its memory operations is on its way.
+__device__ __forceinline__ void tick_bump(FusedShared &sh) {
+    asm volatile("" ::: "memory");
+    lds_flag_ptr t = lds_flag(&sh.tick);
+    *t = *t + 1;
+    asm volatile("" ::: "memory");
+}
 
 // Device-wide barrier, two levels: blocks arrive on their group's counter (BAR_GROUP
 // consecutive blocks per group, counters 256 bytes apart), the last arriver of a group bumps
@@ -67,8 +82,14 @@ struct FusedShared {
 // ALL_WAVES_STORED: waves other than wave 0 stored too, so the block meets before it arrives.
 // Wave 0 should have no weight loads outstanding when it gets here: memory operations of a
 // wave return in order, so the arrival count and every poll would queue behind them.
+//
+// While thread 0 works through the barrier the other waves request the next phase's first
+// tile a slice at a time, one slice behind each memory operation thread 0 issues (tick_bump):
+// a compute unit serves its memory operations in order, so an arrival or a poll issued behind
+// a whole tile of weight requests would wait for all of them, while a slice issued behind the
+// poll delays nothing and keeps the weight stream going through the barrier.
 template <bool ALL_WAVES_STORED>
-__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err) {
+__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err, FusedShared &sh) {
     if (ALL_WAVES_STORED) __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned g = blockIdx.x / BAR_GROUP;
@@ -76,9 +97,13 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
         const unsigned my_size = min((unsigned)BAR_GROUP, gridDim.x - g * BAR_GROUP);
         unsigned *top = ctr, *grp = ctr + 64 * (1 + g);
         const unsigned old = __hip_atomic_fetch_add(as_global(grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        tick_bump(sh);
         if (old + 1 == epoch * my_size) __hip_atomic_fetch_add(as_global(top), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
-        while (__hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * n_groups) {
+        while (true) {
+            const unsigned seen = __hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tick_bump(sh);
+            if (seen >= epoch * n_groups) break;
             __builtin_amdgcn_s_sleep(1);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
@@ -87,6 +112,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
                 break;
             }
         }
+        *lds_flag(&sh.released) = epoch;
     }
     __syncthreads();
 }
@@ -168,10 +194,9 @@ struct Gemv {
         return stream_load16(matrix_resource(a.W, bytes), (uint32_t)(2 * unit + (s & 1)) * row_bytes, coff[p]);
     }
 
-    // The head of this block's first tile, pieces [0, QD), is requested by the previous phase
-    // (at most WIN requests per wave outstanding); the rest follows the load of x.
+    // The head of this block's first tile, pieces [0, QD), is requested before the phase
+    // starts; the rest follows the load of x.
     static constexpr int QD = NS < SPD_FUSED_QD ? NS : SPD_FUSED_QD;
-    static constexpr int WIN = SPD_FUSED_WIN;
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
@@ -181,8 +206,32 @@ struct Gemv {
 #pragma unroll
         for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
 #pragma unroll
+        for (int q = 0; q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
+    }
+    // The same while thread 0 runs barrier number `epoch`: SPD_FUSED_SLICE pieces behind each
+    // of its synchronisation steps, everything that is left once the block has been released.
+    static __device__ __forceinline__ void prefetch_sliced(const GemvArgs &a_in, u32x4 (&buf)[NBUF], FusedShared &sh,
+                                                           unsigned epoch) {
+        const GemvArgs a = uniform(a_in);
+        int lo, hi;
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        if (lo >= hi) return;
+        uint32_t coff[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
+        lds_flag_ptr tick = lds_flag(&sh.tick), released = lds_flag(&sh.released);
+        unsigned seen = uniform((int)*tick);
+#pragma unroll
         for (int q = 0; q < QD; ++q) {
-            if (q >= WIN) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN - 1) : "memory");
+            if (q % SPD_FUSED_SLICE == 0) {
+                unsigned now = seen;
+                for (unsigned spins = 0; spins < SPIN_LIMIT; ++spins) {   // thread 0's own wait is bounded too
+                    now = uniform((int)*tick);
+                    if (now != seen || (unsigned)uniform((int)*released) >= epoch) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                seen = now;
+            }
             buf[q] = piece(a, lo, hi, q, coff);
         }
     }
@@ -228,13 +277,14 @@ struct Gemv {
                 gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, cs);
             }
         }
+        if (!REFILL && tid == 0) tick_bump(sh);   // the phase's last stores are on their way
     }
 
     // Runs the phase.  On entry `buf` holds this block's first tile; on return it holds the
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
-                                               FusedShared &sh, u32x4 (&buf)[NBUF]) {
+                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
@@ -297,7 +347,7 @@ struct Gemv {
         // Wave 0 runs the device-wide barrier next and asks for its share after the release
         // (see grid_barrier).
         if (is_wave0()) wait_stores();
-        else Next::prefetch(na, buf);
+        else Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers have been passed so far
     }
 };
 
@@ -322,6 +372,7 @@ struct FusedArgs {
 template <int NBUF>
 struct NoNext {
     static __device__ __forceinline__ void prefetch(const GemvArgs &, u32x4 (&)[NBUF]) {}
+    static __device__ __forceinline__ void prefetch_sliced(const GemvArgs &, u32x4 (&)[NBUF], FusedShared &, unsigned) {}
 };
 
 __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
@@ -360,7 +411,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 #define SPD_BARRIER(ALL_WAVES_STORED)                                        \
     do {                                                                     \
         if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();      \
-        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err);        \
+        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err, sh);        \
         if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
@@ -378,7 +429,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     wait_stores();
     u32x4 buf[NBUF];
     GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
-    if (!is_wave0()) {
+    if (threadIdx.x == 0) { sh.tick = 0; sh.released = 0; }
+    __syncthreads();
+    if (!is_wave0()) {   // (not sliced: before this barrier the whole block meets first)
         if (a.n_layers > 0) Qkv::prefetch(cur, buf);
         else if (a.head) Head::prefetch(cur, buf);
     }
@@ -394,7 +447,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
-        Qkv::template run<Oproj>(cur, o, pos, sh, buf);
+        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch);
         SPD_BARRIER(false);
         if (is_wave0()) Oproj::prefetch(o, buf);
 
@@ -411,24 +464,24 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         GemvArgs f{};
         f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
         f.rows = a.d_ffn; f.cols = a.d_model;
-        Oproj::template run<GateUp>(o, f, pos, sh, buf);
+        Oproj::template run<GateUp>(o, f, pos, sh, buf, epoch);
         SPD_BARRIER(false);
         if (is_wave0()) GateUp::prefetch(f, buf);
 
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn;
-        GateUp::template run<Down>(f, d, pos, sh, buf);
+        GateUp::template run<Down>(f, d, pos, sh, buf, epoch);
         SPD_BARRIER(false);
         if (is_wave0()) Down::prefetch(d, buf);
 
         if (l + 1 < a.n_layers) {
             cur = qkv_args(a, l + 1);
-            Down::template run<Qkv>(d, cur, pos, sh, buf);
+            Down::template run<Qkv>(d, cur, pos, sh, buf, epoch);
         } else if (a.head) {
             cur = head_args(a);
-            Down::template run<Head>(d, cur, pos, sh, buf);
+            Down::template run<Head>(d, cur, pos, sh, buf, epoch);
         } else {
-            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf);
+            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf, epoch);
         }
         if (l + 1 < a.n_layers || a.head) SPD_BARRIER(false);
         if (is_wave0()) {
@@ -436,7 +489,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             else if (a.head) Head::prefetch(cur, buf);
         }
     }
-    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf);
+    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf, epoch);
     if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();
 #undef SPD_BARRIER
 }

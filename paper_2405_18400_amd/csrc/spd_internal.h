@@ -141,9 +141,9 @@ struct ActLayout {
     size_t layer0, stride;     // layer l's block starts at layer0 + l * stride
     size_t q, att, h1, u, h2;  // within a layer block: query, attention output, residual stream
                                // after attention, SwiGLU output, residual stream after the FFN
-    __host__ __device__ float *at(char *base, size_t off) const { return (float *)(base + off); }
-    __host__ __device__ float *h_in(char *base, int l) const { return l == 0 ? at(base, h0) : at(base, layer0 + (size_t)(l - 1) * stride + h2); }
-    __host__ __device__ float *vec(char *base, int l, size_t which) const { return at(base, layer0 + (size_t)l * stride + which); }
+    __host__ __device__ __forceinline__ float *at(char *base, size_t off) const { return (float *)(base + off); }
+    __host__ __device__ __forceinline__ float *h_in(char *base, int l) const { return l == 0 ? at(base, h0) : at(base, layer0 + (size_t)(l - 1) * stride + h2); }
+    __host__ __device__ __forceinline__ float *vec(char *base, int l, size_t which) const { return at(base, layer0 + (size_t)l * stride + which); }
 };
 
 // Arguments of the fused forward kernel (one persistent launch for the whole model).
