@@ -232,9 +232,28 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
 // finishes last for a head, walking the partial results in chunk order (deterministic).
 // LDS: sc[ATTN_CHUNK], red[NT/64], dyn[NT * VEC] floats, one int.
 // COH: outputs are written through; partial results of other chunks are re-read coherently.
-template <typename KT, int NT, bool COH = false>
+// After / na / nbuf / fire: once the item's own loads are on their way (and only if `fire`),
+// After::prefetch(na, nbuf) may queue further requests behind them (the persistent kernel asks
+// for its next weight tile there; anything requested earlier would hold this item's loads up).
+struct NoAfter {
+    template <int N> static __device__ __forceinline__ void prefetch(const GemvArgs &, u32x4 (&)[N]) {}
+};
+
+// Sum over groups of LPP consecutive lanes (LPP a power of two), complete in the LAST lane of
+// each group: lane-crossing moves of the vector unit instead of LDS permutes.
+__device__ __forceinline__ float group_sum_last(float v, int lpp) {
+    if (lpp >= 2) v += dpp_move<0xB1, 0xF>(v, 0.f);
+    if (lpp >= 4) v += dpp_move<0x4E, 0xF>(v, 0.f);
+    if (lpp >= 8) v += dpp_move<0x141, 0xF>(v, 0.f);
+    if (lpp >= 16) v += dpp_move<0x140, 0xF>(v, 0.f);
+    if (lpp >= 32) v += dpp_move<0x142, 0xA>(v, 0.f);
+    if (lpp >= 64) v += dpp_move<0x143, 0xC>(v, 0.f);
+    return v;
+}
+
+template <typename KT, int NT, bool COH, class After, int NBUF>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
-                                          float *dyn, int *s_last) {
+                                          float *dyn, int *s_last, const GemvArgs &na, u32x4 (&nbuf)[NBUF], bool fire) {
     constexpr int VEC = Store<KT>::VEC;
     constexpr int NWAVE = NT / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
@@ -277,6 +296,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     vb[i] = u32x4{0u, 0u, 0u, 0u};
                     if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
+                if (fire && hq == 0) After::prefetch(na, nbuf);
             }
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
@@ -286,10 +306,9 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                 float d = 0.f;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
-                for (int o = LPP / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
-                d *= scale;
-                if (t < t1) {
-                    if (li == 0) sc[t - t0] = d;
+                d = group_sum_last(d, LPP) * scale;   // complete in the group's last lane
+                if (t < t1 && li == LPP - 1) {
+                    sc[t - t0] = d;
                     lmax = fmaxf(lmax, d);
                 }
             }
@@ -365,6 +384,14 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         }
         __syncthreads();   // sc / dyn / s_last are reused by the next query head or item
     }
+}
+
+template <typename KT, int NT, bool COH = false>
+__device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
+                                          float *dyn, int *s_last) {
+    u32x4 none[1];
+    const GemvArgs na{};
+    attn_item<KT, NT, COH, NoAfter, 1>(a, g, s, n_ctx, sc, red, dyn, s_last, na, none, false);
 }
 
 // ------------------------------------------------------------------ superposed embedding

@@ -29,6 +29,9 @@ namespace {
 #ifndef SPD_FUSED_UB
 #define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
 #endif
+#ifndef SPD_FUSED_UO_EXTRA
+#define SPD_FUSED_UO_EXTRA 4      // extra rows per tile of the O projection
+#endif
 #ifndef SPD_FUSED_QD
 #define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested while the block synchronises
 #endif
@@ -139,7 +142,7 @@ __device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
     r.resid = uniform(a.resid); r.y = uniform(a.y); r.rows = uniform(a.rows); r.cols = uniform(a.cols);
     r.kcache = uniform(a.kcache); r.vcache = uniform(a.vcache);
     r.n_q_rows = uniform(a.n_q_rows); r.n_kv_rows = uniform(a.n_kv_rows); r.d_head = uniform(a.d_head);
-    r.cap_ctx = uniform(a.cap_ctx);
+    r.cap_ctx = uniform(a.cap_ctx); r.first_block = uniform(a.first_block);
     return r;
 }
 
@@ -149,8 +152,11 @@ __device__ __forceinline__ bool is_wave0() { return __builtin_amdgcn_readfirstla
 // weights are requested, so it never waits for those.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// Units [lo, hi) of n that block b of G owns (contiguous, balanced to within one unit).
-__device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &hi) {
+// Units [lo, hi) of n that block b of G owns (contiguous, balanced to within one unit); the
+// first `skip` blocks own nothing.
+__device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &hi, int skip = 0) {
+    if (b < skip) { lo = hi = 0; return; }
+    b -= skip; G -= skip;
     // n * (b + 1) stays below 2^32 for every supported shape (n <= 2^21 units, G <= 2^10 blocks)
     // (integer division runs on the vector unit: bring the uniform results back to scalars)
     lo = __builtin_amdgcn_readfirstlane((int)(((unsigned)n * (unsigned)b) / (unsigned)G));
@@ -200,7 +206,7 @@ struct Gemv {
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
         if (lo >= hi) return;
         uint32_t coff[P];
 #pragma unroll
@@ -214,7 +220,7 @@ struct Gemv {
                                                            unsigned epoch) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
         if (lo >= hi) return;
         uint32_t coff[P];
 #pragma unroll
@@ -284,11 +290,12 @@ struct Gemv {
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
-                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch) {
+                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch,
+                                               bool prefetch_next = true) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi);
+        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
         if (lo < hi) {
             // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
             // depend on any activation, so its load goes out first
@@ -347,7 +354,7 @@ struct Gemv {
         // Wave 0 runs the device-wide barrier next and asks for its share after the release
         // (see grid_barrier).
         if (is_wave0()) wait_stores();
-        else Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers have been passed so far
+        else if (prefetch_next) Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers passed so far
     }
 };
 
@@ -399,9 +406,13 @@ __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
 // PA / PB: passes a block needs to cover d_model / d_ffn columns; UA / UB: rows per tile.
 template <typename WT, int PA, int UA, int PB, int UB>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
-    constexpr int NBUF = (PA * UA > PB * UB) ? PA * UA : PB * UB;
+    // The O projection is one tile per block; its tile is a little taller so that it still is
+    // when the blocks busy with attention items leave their rows to the others.
+    constexpr int UO = UA + SPD_FUSED_UO_EXTRA;
+    constexpr int NA = PA * UO > PA * UA ? PA * UO : PA * UA;
+    constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF>;
-    using Oproj = Gemv<WT, PA, UA, EPI_RESID, NBUF>;
+    using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF>;
     using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF>;
@@ -447,16 +458,24 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
-        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch);
+        // a block with an attention item asks for its O-projection tile behind that item's
+        // loads, the others while they synchronise
+        const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
+        const bool has_item = (int)blockIdx.x < a.n_kv_heads * n_splits;
+        // while few blocks have one, those take no rows of the O projection: they would hold
+        // everybody up fetching their tile after the attention
+        const int n_items = a.n_kv_heads * n_splits;
+        o.first_block = 4 * n_items <= (int)gridDim.x ? n_items : 0;
+        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch, !has_item);
         SPD_BARRIER(false);
-        if (is_wave0()) Oproj::prefetch(o, buf);
+        if (is_wave0() && !has_item) Oproj::prefetch(o, buf);
 
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
             AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, pos + 1,
                        a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
-            const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
             for (int item = blockIdx.x; item < a.n_kv_heads * n_splits; item += gridDim.x)
-                attn_item<KvT, NT, true>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn, &sh.s_last);
+                attn_item<KvT, NT, true, Oproj, NBUF>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn,
+                                                      &sh.s_last, o, buf, item == (int)blockIdx.x);
             wait_stores();
         }
         SPD_BARRIER(true);

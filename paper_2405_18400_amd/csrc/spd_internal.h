@@ -89,6 +89,7 @@ struct GemvArgs {
     const DevState *st;         // position
     const double *inv_freq;     // [d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
+    int32_t first_block;        // fused kernel: blocks below this index take no rows of this phase
 };
 
 struct AttnArgs {
