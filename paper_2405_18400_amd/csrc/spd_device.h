@@ -60,16 +60,16 @@ typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const f32x4 __attribute__((address_space(1))) *global_f32x4_ptr;
 
-// Weight rows are streamed with raw buffer loads: the matrix is described once by a
-// resource descriptor in scalar registers, a row is a scalar byte offset and only the
+// Weight rows are streamed with raw buffer loads: a row is described by a resource descriptor
+// in scalar registers (built with scalar arithmetic from the row's address) and only the
 // lane's column offset sits in a vector register -- no 64-bit per-lane address arithmetic.
-// Reads past the end of the matrix return zero instead of touching memory.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_resource(const void *base, size_t bytes) {
-    const uint32_t n = bytes > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)bytes;
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
+// The descriptor's extent is ONE ROW, so a lane whose columns lie past the row end gets zeros
+// back and causes no memory traffic.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const void *row, uint32_t row_bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(row), 0, (int)row_bytes, 0x00020000);
 }
-__device__ __forceinline__ u32x4 stream_load16(__amdgpu_buffer_rsrc_t m, uint32_t row_offset, uint32_t lane_offset) {
-    return __builtin_amdgcn_raw_buffer_load_b128(m, (int)lane_offset, (int)row_offset, 2);   // 2 = non-temporal
+__device__ __forceinline__ u32x4 stream_load16(__amdgpu_buffer_rsrc_t row, uint32_t lane_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(row, (int)lane_offset, 0, 2);   // 2 = non-temporal
 }
 
 typedef const char __attribute__((address_space(1))) *global_char_ptr;
@@ -227,8 +227,8 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
 }
 
 // ------------------------------------------------------------------ single-query attention
-// One work item = (key/value head g, context chunk s) handled by a block of NT threads.  All
-// query heads sharing head g are served from the chunk.  Chunks are merged by whichever block
+// One work item = (key/value head g, context chunk s) handled by a block of NT threads.  The
+// query heads [hq0, hq1) of those sharing head g are served from the chunk, one after another.  Chunks are merged by whichever block
 // finishes last for a head, walking the partial results in chunk order (deterministic).
 // LDS: sc[ATTN_CHUNK], red[NT/64], dyn[NT * VEC] floats, one int.
 // COH: outputs are written through; partial results of other chunks are re-read coherently.
@@ -253,7 +253,8 @@ __device__ __forceinline__ float group_sum_last(float v, int lpp) {
 
 template <typename KT, int NT, bool COH, class After, int NBUF>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
-                                          float *dyn, int *s_last, const GemvArgs &na, u32x4 (&nbuf)[NBUF], bool fire) {
+                                          float *dyn, int *s_last, const GemvArgs &na, u32x4 (&nbuf)[NBUF], bool fire,
+                                          int hq0 = 0, int hq1 = INT_MAX) {
     constexpr int VEC = Store<KT>::VEC;
     constexpr int NWAVE = NT / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
@@ -274,13 +275,16 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     // rows together with the keys: this phase is a chain of memory latencies, not bandwidth.
     constexpr int ATTN_BATCH = 8;
     const int tbase = t0 + wid * PPW + sub;
-    for (int hq = 0; hq < group; ++hq) {
+    // query heads [hq0, hq1) of the group that shares key/value head g
+    for (int hq = hq0; hq < min(hq1, group); ++hq) {
         const int h = g * group + hq;
         float qv[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) qv[v] = as_global(a.q)[(size_t)h * dh + li * VEC + v];
         float lmax = -INFINITY;
         u32x4 vb[ATTN_BATCH];
+        // (a wave without a position in this chunk has no loads to go first)
+        if (fire && hq == hq0 && tbase - sub >= t1) After::prefetch(na, nbuf);
         for (int b0 = tbase; b0 - sub < t1; b0 += ATTN_BATCH * PPB) {   // b0 - sub is wave-uniform
             u32x4 kb[ATTN_BATCH];
 #pragma unroll
@@ -296,7 +300,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     vb[i] = u32x4{0u, 0u, 0u, 0u};
                     if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
-                if (fire && hq == 0) After::prefetch(na, nbuf);
+                if (fire && hq == hq0) After::prefetch(na, nbuf);
             }
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
@@ -379,7 +383,8 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     if (tid < dh) O += w * coherent_load(pq + 2 + tid);
                 }
                 if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
-                if (tid == 0) as_global(a.counters)[h] = 0;
+                // (written through: the next user of this counter may sit behind another L2)
+                if (tid == 0) __hip_atomic_store(as_global(a.counters) + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();   // sc / dyn / s_last are reused by the next query head or item

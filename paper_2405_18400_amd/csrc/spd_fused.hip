@@ -26,9 +26,6 @@ namespace {
 #ifndef SPD_FUSED_UA
 #define SPD_FUSED_UA 16           // rows per tile where one pass covers a row
 #endif
-#ifndef SPD_FUSED_UB
-#define SPD_FUSED_UB 4            // rows per tile where a row takes three passes
-#endif
 #ifndef SPD_FUSED_UO_EXTRA
 #define SPD_FUSED_UO_EXTRA 4      // extra rows per tile of the O projection
 #endif
@@ -168,8 +165,8 @@ __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &h
 // piece of the block's next tile, so a wave always has about NS loads in flight; after the
 // last tile the first tile of the NEXT phase is requested, before the device-wide barrier.
 // Loads are never predicated: a row past the block's range re-reads the last valid row (a
-// cache hit), and a column past the row end reads into the next row, where x is zero (past
-// the end of the matrix the buffer load returns zero); the inner loop has no branches.
+// cache hit), and a column past the row end lies outside the buffer descriptor, which
+// describes one row (zeros come back, nothing is fetched); the inner loop has no branches.
 template <typename WT, int P, int U, int EPI, int NBUF>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
@@ -184,7 +181,7 @@ struct Gemv {
     static __device__ __forceinline__ uint32_t col_offset(const GemvArgs &a, int p) {
         const int lane = threadIdx.x & (WAVE - 1), w = (threadIdx.x / WAVE) % NW;
         const int c = ((p * NW + w) * WAVE + lane) * VEC;
-        return (uint32_t)c * (uint32_t)sizeof(WT);   // past the row end: the next row (x is 0 there) or zero
+        return (uint32_t)c * (uint32_t)sizeof(WT);   // past the row end: the load returns zero
     }
 
     // Piece q = s * P + p of this wave's row group within the block tile starting at unit u0
@@ -194,10 +191,9 @@ struct Gemv {
         const int g = __builtin_amdgcn_readfirstlane(threadIdx.x / (WAVE * NW));
         const int unit = min(u0 + g * UT + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
         const uint32_t row_bytes = (uint32_t)a.cols * (uint32_t)sizeof(WT);
-        const size_t bytes = (size_t)a.rows * row_bytes;
-        if (EPI == EPI_SWIGLU)
-            return stream_load16(matrix_resource(s < UT ? a.W : a.W2, bytes), (uint32_t)unit * row_bytes, coff[p]);
-        return stream_load16(matrix_resource(a.W, bytes), (uint32_t)(2 * unit + (s & 1)) * row_bytes, coff[p]);
+        const char *W = (const char *)(EPI == EPI_SWIGLU && s >= UT ? a.W2 : a.W);
+        const int row = EPI == EPI_SWIGLU ? unit : 2 * unit + (s & 1);
+        return stream_load16(row_resource(W + (size_t)row * row_bytes, row_bytes), coff[p]);
     }
 
     // The head of this block's first tile, pieces [0, QD), is requested before the phase
@@ -403,13 +399,17 @@ __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
     return g;
 }
 
-// PA / PB: passes a block needs to cover d_model / d_ffn columns; UA / UB: rows per tile.
-template <typename WT, int PA, int UA, int PB, int UB>
+// PA / PB: passes a block needs to cover d_model / d_ffn columns.  Rows per tile follow from
+// them so that a tile stays at about 16 pieces (16 bytes each) per lane.
+constexpr int tile_rows(int passes) { return passes == 1 ? SPD_FUSED_UA : passes == 2 ? SPD_FUSED_UA / 2 : passes <= 4 ? 4 : 2; }
+
+template <typename WT, int PA, int PB>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
+    constexpr int UA = tile_rows(PA), UB = tile_rows(PB);
     // The O projection is one tile per block; its tile is a little taller so that it still is
     // when the blocks busy with attention items leave their rows to the others.
-    constexpr int UO = UA + SPD_FUSED_UO_EXTRA;
-    constexpr int NA = PA * UO > PA * UA ? PA * UO : PA * UA;
+    constexpr int UO = UA + SPD_FUSED_UO_EXTRA / PA;
+    constexpr int NA = PA * UO;
     constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF>;
@@ -461,10 +461,10 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         // a block with an attention item asks for its O-projection tile behind that item's
         // loads, the others while they synchronise
         const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
-        const bool has_item = (int)blockIdx.x < a.n_kv_heads * n_splits;
+        const int n_items = a.n_heads * n_splits;
+        const bool has_item = (int)blockIdx.x < n_items;
         // while few blocks have one, those take no rows of the O projection: they would hold
         // everybody up fetching their tile after the attention
-        const int n_items = a.n_kv_heads * n_splits;
         o.first_block = 4 * n_items <= (int)gridDim.x ? n_items : 0;
         Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch, !has_item);
         SPD_BARRIER(false);
@@ -473,9 +473,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
             AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, pos + 1,
                        a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
-            for (int item = blockIdx.x; item < a.n_kv_heads * n_splits; item += gridDim.x)
-                attn_item<KvT, NT, true, Oproj, NBUF>(t, item / n_splits, item % n_splits, pos + 1, sh.sc, sh.red, dyn,
-                                                      &sh.s_last, o, buf, item == (int)blockIdx.x);
+            const int group = a.n_heads / a.n_kv_heads;
+            for (int item = blockIdx.x; item < n_items; item += gridDim.x) {   // one query head, one chunk
+                const int h = item / n_splits;
+                attn_item<KvT, NT, true, Oproj, NBUF>(t, h / group, item % n_splits, pos + 1, sh.sc, sh.red, dyn,
+                                                      &sh.s_last, o, buf, item == (int)blockIdx.x, h % group, h % group + 1);
+            }
             wait_stores();
         }
         SPD_BARRIER(true);
@@ -513,40 +516,51 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 #undef SPD_BARRIER
 }
 
-template <typename WT, int PA, int UA, int PB, int UB>
-hipError_t launch_fused(hipStream_t s, const FusedArgs &a, int blocks) {
-    hipLaunchKernelGGL((fused_forward_kernel<WT, PA, UA, PB, UB>), dim3(blocks), dim3(NT), 0, s, a);
-    return hipGetLastError();
-}
-
-template <typename WT, int PA, int UA, int PB, int UB>
-int fused_blocks_per_cu() {
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)fused_forward_kernel<WT, PA, UA, PB, UB>, NT, 0) != hipSuccess) {
-        (void)hipGetLastError();
-        return 0;
+template <typename WT, int PA, int PB> struct Variant {
+    static hipError_t launch(hipStream_t s, const FusedArgs &a, int blocks) {
+        hipLaunchKernelGGL((fused_forward_kernel<WT, PA, PB>), dim3(blocks), dim3(NT), 0, s, a);
+        return hipGetLastError();
     }
-    return n;
+    static int blocks_per_cu() {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)fused_forward_kernel<WT, PA, PB>, NT, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        return n;
+    }
+};
+
+// The instantiations that exist: passes needed to cover d_model and d_ffn with NW waves
+// (bf16: 4096 columns per pass).  (1,1) and (1,2): small models; (1,3): the Llama-2-7B shape;
+// (2,4): 13B; (2,7): 70B.  Calls f(Variant<...>{}) for the one that serves the shape.
+template <typename F>
+bool with_variant(int dtype, int d_model, int d_ffn, F &&f) {
+    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    const int span = NW * WAVE * vec;
+    const int pa = (d_model + span - 1) / span, pb = (d_ffn + span - 1) / span;
+    if (dtype == SPD_DTYPE_BF16) {
+        if (pa == 1 && pb == 1) return f(Variant<bf16_t, 1, 1>{}), true;
+        if (pa == 1 && pb == 2) return f(Variant<bf16_t, 1, 2>{}), true;
+        if (pa == 1 && pb == 3) return f(Variant<bf16_t, 1, 3>{}), true;
+        if (pa == 2 && pb == 4) return f(Variant<bf16_t, 2, 4>{}), true;
+        if (pa == 2 && pb == 7) return f(Variant<bf16_t, 2, 7>{}), true;
+    } else {
+        if (pa == 1 && pb == 1) return f(Variant<float, 1, 1>{}), true;
+        if (pa == 1 && pb == 2) return f(Variant<float, 1, 2>{}), true;
+        if (pa == 1 && pb == 3) return f(Variant<float, 1, 3>{}), true;
+    }
+    return false;
 }
 
 }  // namespace
 
 namespace spdk {
 
-// Which instantiation serves a shape: passes needed to cover d_model and d_ffn with NW waves.
-static bool fused_variant(int dtype, int d_model, int d_ffn, int &pa, int &pb) {
-    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
-    const int span = NW * WAVE * vec;
-    pa = (d_model + span - 1) / span;
-    pb = (d_ffn + span - 1) / span;
-    return (pa == 1 && (pb == 1 || pb == 3));
-}
-
 int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
-    int pa, pb;
-    if (!fused_variant(dtype, d_model, d_ffn, pa, pb)) return 0;
-    if (dtype == SPD_DTYPE_BF16) return pb == 1 ? fused_blocks_per_cu<bf16_t, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>() : fused_blocks_per_cu<bf16_t, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>();
-    return pb == 1 ? fused_blocks_per_cu<float, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>() : fused_blocks_per_cu<float, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>();
+    int n = 0;
+    with_variant(dtype, d_model, d_ffn, [&](auto v) { n = decltype(v)::blocks_per_cu(); });
+    return n;
 }
 
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int blocks) {
@@ -558,11 +572,9 @@ hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int b
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
     a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
     a.eps = h.eps;
-    int pa, pb;
-    if (!fused_variant(dtype, h.d_model, h.d_ffn, pa, pb)) return hipErrorInvalidValue;
-    if (dtype == SPD_DTYPE_BF16)
-        return pb == 1 ? launch_fused<bf16_t, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>(s, a, blocks) : launch_fused<bf16_t, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>(s, a, blocks);
-    return pb == 1 ? launch_fused<float, 1, SPD_FUSED_UA, 1, SPD_FUSED_UA>(s, a, blocks) : launch_fused<float, 1, SPD_FUSED_UA, 3, SPD_FUSED_UB>(s, a, blocks);
+    hipError_t e = hipErrorInvalidValue;
+    with_variant(dtype, h.d_model, h.d_ffn, [&](auto v) { e = decltype(v)::launch(s, a, blocks); });
+    return e;
 }
 
 }  // namespace spdk

@@ -115,6 +115,16 @@ def test_long_prefix_crosses_attention_chunks(forward_path):
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=600, path=forward_path)
 
 
+def test_many_attention_items(forward_path):
+    """More (query head, chunk) items than a quarter of the fused kernel's blocks: the blocks
+    that hold an item also take rows of the O projection and ask for them behind the item's
+    own loads; the last chunk is ragged, so some waves of a block have no position in it."""
+    shape = synth.ModelShape("heads32-fp32", 2, 512, 32, 8, 512, 1024, "fp32")
+    w = synth.make_weights(shape, seed=9)
+    prefix = synth.make_prefix_uniform(shape.vocab, 261, seed=9)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=400, path=forward_path)
+
+
 def test_wide_ffn_three_pass_rows(forward_path):
     """d_ffn wider than one block pass (bf16: 4096 columns), ragged against the pass width,
     like the 7B shape's 11008: exercises the multi-pass rows of the fused kernel."""
@@ -122,6 +132,53 @@ def test_wide_ffn_three_pass_rows(forward_path):
     w = synth.make_weights(shape, seed=7)
     prefix = synth.make_prefix_uniform(shape.vocab, 21, seed=7)
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 2, 0.0, 5, path=forward_path)
+
+
+def test_two_pass_ffn_rows(forward_path):
+    """d_ffn between one and two block passes."""
+    shape = synth.ModelShape("ffn2-bf16", 2, 512, 4, 4, 4096 + 2056, 1024, "bf16")
+    w = synth.make_weights(shape, seed=8)
+    prefix = synth.make_prefix_uniform(shape.vocab, 9, seed=8)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 2, 0.0, 4, path=forward_path)
+
+
+def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_path, alpha=0.54):
+    """A published shape with its real widths and head layout but few layers (the oracle runs on
+    the host): weights drawn on the GPU, n-gram tables planted along the oracle's path."""
+    pkg = P()
+    shape = shape.truncated(n_layers)
+    wdev = synth.make_weights_device(shape, seed=seed)
+    host = {k_: synth.host_view(v) for k_, v in wdev.items() if not k_.endswith("wqkv")}
+    prefix = synth.make_prefix_zipf(shape.vocab, prefix_len, seed=seed)
+    base = synth.make_ngram_tables_zipf(shape.vocab, 100_000, seed=seed)
+    lm = make_oracle(shape, host)
+    _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0), n_tokens)
+    visits = [(tuple(r.state_in.history(i)), int(t)) for r in recs0[1:] for i in range(k) for t in r.top_ids]
+    tabs = synth.plant_ngrams(base, visits, shape.vocab, seed=seed + 1, frac=0.5)
+    sess = pkg.Session(shape, wdev, max_ctx=prefix_len + n_tokens + 8, k_max=8)
+    try:
+        select_path(sess, forward_path)
+        sess.spd_load_ngrams(tabs, synth.PAPER_LAMBDAS)
+        dc = pkg.SpdDecodeCfg(k, alpha, 1.0, 0.1)
+        cfg = O.DecodeCfg(k, alpha, 1.0, 0.1, synth.PAPER_LAMBDAS)
+        _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, n_tokens, RTOL["bf16"], dc)
+        print(shape.name, "scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats if "logit_err" in s])
+    finally:
+        sess.close()
+
+
+@pytest.mark.timeout(600)
+def test_13b_shape_two_layers(forward_path):
+    """BASELINE config 4's widths (d_model 5120, 40 heads, FFN 13824: rows of 1.25 and 3.375
+    block passes), k = 5, two of its 40 layers."""
+    _layer_truncated(synth.LLAMA13B, 2, 140, 5, 4, 13, forward_path)
+
+
+@pytest.mark.timeout(600)
+def test_70b_shape_one_layer(forward_path):
+    """BASELINE config 5's widths (d_model 8192, 64 query heads on 8 key/value heads, FFN
+    28672), k = 3, one of its 80 layers; the prefix crosses an attention chunk."""
+    _layer_truncated(synth.LLAMA70B, 1, 131, 3, 3, 70, forward_path)
 
 
 def test_fused_and_per_operator_forward_agree(tiny):
