@@ -230,15 +230,8 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
 // One work item = (key/value head g, context chunk s) handled by a block of NT threads.  The
 // query heads [hq0, hq1) of those sharing head g are served from the chunk, one after another.  Chunks are merged by whichever block
 // finishes last for a head, walking the partial results in chunk order (deterministic).
-// LDS: sc[ATTN_CHUNK], red[NT/64], dyn[NT * VEC] floats, one int.
+// LDS: sc[a.chunk], red[NT/64], dyn[NT * VEC] floats, one int.
 // COH: outputs are written through; partial results of other chunks are re-read coherently.
-// After / na / nbuf / fire: once the item's own loads are on their way (and only if `fire`),
-// After::prefetch(na, nbuf) may queue further requests behind them (the persistent kernel asks
-// for its next weight tile there; anything requested earlier would hold this item's loads up).
-struct NoAfter {
-    template <int N> static __device__ __forceinline__ void prefetch(const GemvArgs &, u32x4 (&)[N]) {}
-};
-
 // Sum over groups of LPP consecutive lanes (LPP a power of two), complete in the LAST lane of
 // each group: lane-crossing moves of the vector unit instead of LDS permutes.
 __device__ __forceinline__ float group_sum_last(float v, int lpp) {
@@ -251,10 +244,9 @@ __device__ __forceinline__ float group_sum_last(float v, int lpp) {
     return v;
 }
 
-template <typename KT, int NT, bool COH, class After, int NBUF>
+template <typename KT, int NT, bool COH = false>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
-                                          float *dyn, int *s_last, const GemvArgs &na, u32x4 (&nbuf)[NBUF], bool fire,
-                                          int hq0 = 0, int hq1 = INT_MAX) {
+                                          float *dyn, int *s_last, int hq0 = 0, int hq1 = INT_MAX) {
     constexpr int VEC = Store<KT>::VEC;
     constexpr int NWAVE = NT / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
@@ -283,8 +275,6 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         for (int v = 0; v < VEC; ++v) qv[v] = as_global(a.q)[(size_t)h * dh + li * VEC + v];
         float lmax = -INFINITY;
         u32x4 vb[ATTN_BATCH];
-        // (a wave without a position in this chunk has no loads to go first)
-        if (fire && hq == hq0 && tbase - sub >= t1) After::prefetch(na, nbuf);
         for (int b0 = tbase; b0 - sub < t1; b0 += ATTN_BATCH * PPB) {   // b0 - sub is wave-uniform
             u32x4 kb[ATTN_BATCH];
 #pragma unroll
@@ -300,7 +290,6 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     vb[i] = u32x4{0u, 0u, 0u, 0u};
                     if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
-                if (fire && hq == hq0) After::prefetch(na, nbuf);
             }
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
@@ -373,14 +362,43 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
             if (*s_last) {
                 if (!COH) __threadfence();
                 const float *ph = a.part + (size_t)h * a.max_splits * (dh + 2);
-                float M = -INFINITY;
-                for (int q = 0; q < n_splits; ++q) M = fmaxf(M, coherent_load(ph + (size_t)q * (dh + 2)));
                 float L = 0.f, O = 0.f;
-                for (int q = 0; q < n_splits; ++q) {
-                    const float *pq = ph + (size_t)q * (dh + 2);
-                    const float w = expf(coherent_load(pq) - M);
-                    L += w * coherent_load(pq + 1);
-                    if (tid < dh) O += w * coherent_load(pq + 2 + tid);
+                if (n_splits <= min(a.chunk, NT)) {
+                    // every chunk's (max, sum) at once, one thread each; weights via LDS; then
+                    // the partial outputs eight chunks at a time.  Sums run in chunk order.
+                    float mq = -INFINITY, lq = 0.f;
+                    if (tid < n_splits) {
+                        mq = coherent_load(ph + (size_t)tid * (dh + 2));
+                        lq = coherent_load(ph + (size_t)tid * (dh + 2) + 1);
+                    }
+                    const float M = block_max<NT>(mq, red);
+                    if (tid < n_splits) {
+                        const float w = expf(mq - M);
+                        sc[tid] = w;
+                        dyn[tid] = w * lq;
+                    }
+                    __syncthreads();
+                    for (int q = 0; q < n_splits; ++q) L += dyn[q];
+                    if (tid < dh) {
+                        for (int q0 = 0; q0 < n_splits; q0 += 8) {
+                            float pv[8];
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                pv[j] = coherent_load(ph + (size_t)min(q0 + j, n_splits - 1) * (dh + 2) + 2 + tid);
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                if (q0 + j < n_splits) O += sc[q0 + j] * pv[j];
+                        }
+                    }
+                } else {
+                    float M = -INFINITY;
+                    for (int q = 0; q < n_splits; ++q) M = fmaxf(M, coherent_load(ph + (size_t)q * (dh + 2)));
+                    for (int q = 0; q < n_splits; ++q) {
+                        const float *pq = ph + (size_t)q * (dh + 2);
+                        const float w = expf(coherent_load(pq) - M);
+                        L += w * coherent_load(pq + 1);
+                        if (tid < dh) O += w * coherent_load(pq + 2 + tid);
+                    }
                 }
                 if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
                 // (written through: the next user of this counter may sit behind another L2)
@@ -389,14 +407,6 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         }
         __syncthreads();   // sc / dyn / s_last are reused by the next query head or item
     }
-}
-
-template <typename KT, int NT, bool COH = false>
-__device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
-                                          float *dyn, int *s_last) {
-    u32x4 none[1];
-    const GemvArgs na{};
-    attn_item<KT, NT, COH, NoAfter, 1>(a, g, s, n_ctx, sc, red, dyn, s_last, na, none, false);
 }
 
 // ------------------------------------------------------------------ superposed embedding

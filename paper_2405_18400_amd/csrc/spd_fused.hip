@@ -48,7 +48,7 @@ struct FusedShared {
     float epi[MAX_EPI];           // this block's slice of the residual, staged when the phase starts
     float2 rope[128];             // (cos, sin) of this step's position, all d_head / 2 <= 128 pairs
     float red[NT / WAVE];
-    float sc[ATTN_CHUNK];
+    float sc[ATTN_CHUNK_MAX];
     int s_last;
     unsigned tick;                // bumped by thread 0 whenever it has issued a synchronisation step
     unsigned released;            // number of device-wide barriers this block has been released from
@@ -286,8 +286,7 @@ struct Gemv {
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
-                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch,
-                                               bool prefetch_next = true) {
+                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
@@ -350,7 +349,7 @@ struct Gemv {
         // Wave 0 runs the device-wide barrier next and asks for its share after the release
         // (see grid_barrier).
         if (is_wave0()) wait_stores();
-        else if (prefetch_next) Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers passed so far
+        else Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers have been passed so far
     }
 };
 
@@ -458,26 +457,32 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
-        // a block with an attention item asks for its O-projection tile behind that item's
-        // loads, the others while they synchronise
-        const int n_splits = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
+        // Attention items: one per (query head, chunk of cached positions).  Short contexts are
+        // one chunk; longer ones are cut so that every block gets an item if the chunk bounds
+        // allow.  While few blocks have an item those take no rows of the O projection: they
+        // would hold everybody up fetching their tile after the attention.
+        const int n_ctx = pos + 1;
+        int chunk = ATTN_CHUNK;
+        if (n_ctx > ATTN_CHUNK) {
+            const int per_head = max(1, (int)gridDim.x / a.n_heads);
+            chunk = ((n_ctx + per_head - 1) / per_head + 15) & ~15;
+            chunk = min(ATTN_CHUNK_MAX, max(ATTN_CHUNK_MIN, chunk));
+        }
+        const int n_splits = (n_ctx + chunk - 1) / chunk;
         const int n_items = a.n_heads * n_splits;
-        const bool has_item = (int)blockIdx.x < n_items;
-        // while few blocks have one, those take no rows of the O projection: they would hold
-        // everybody up fetching their tile after the attention
         o.first_block = 4 * n_items <= (int)gridDim.x ? n_items : 0;
-        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch, !has_item);
+        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch);
         SPD_BARRIER(false);
-        if (is_wave0() && !has_item) Oproj::prefetch(o, buf);
+        if (is_wave0()) Oproj::prefetch(o, buf);
 
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
-            AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, pos + 1,
-                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, ATTN_CHUNK, a.max_splits};
+            AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, n_ctx,
+                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, chunk, a.max_splits};
             const int group = a.n_heads / a.n_kv_heads;
-            for (int item = blockIdx.x; item < n_items; item += gridDim.x) {   // one query head, one chunk
+            for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
-                attn_item<KvT, NT, true, Oproj, NBUF>(t, h / group, item % n_splits, pos + 1, sh.sc, sh.red, dyn,
-                                                      &sh.s_last, o, buf, item == (int)blockIdx.x, h % group, h % group + 1);
+                attn_item<KvT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                         h % group, h % group + 1);
             }
             wait_stores();
         }

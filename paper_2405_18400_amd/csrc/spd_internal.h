@@ -172,7 +172,9 @@ constexpr int BAR_GROUP = 32;          // blocks per group of the two-level devi
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_WORDS = 64 * (1 + BAR_MAX_GROUPS);
 constexpr int TOPK_PART_MAX = 128;
-constexpr int ATTN_CHUNK = 128;
+constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
+constexpr int ATTN_CHUNK_MIN = 64;     // the fused kernel picks the chunk per step within these bounds
+constexpr int ATTN_CHUNK_MAX = 512;
 
 namespace spdk {
 hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu);

@@ -435,7 +435,7 @@ hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu
 }
 
 hipError_t attention(hipStream_t s, int dtype, const AttnArgs &a) {
-    const dim3 grid(a.n_kv_heads, a.max_splits);
+    const dim3 grid(a.n_kv_heads, (a.cap_ctx + a.chunk - 1) / a.chunk);
     const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
     const int lpp = a.d_head / vec;
     const size_t lds = (size_t)(BLOCK / lpp) * a.d_head * sizeof(float);

@@ -53,7 +53,7 @@ const char *check_cfg(const spd_model_cfg *c) {
 Layout make_layout(const spd_model_cfg &c) {
     Layout L{};
     const int dh = c.d_model / c.n_heads;
-    L.max_splits = (c.max_ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    L.max_splits = (c.max_ctx + ATTN_CHUNK_MIN - 1) / ATTN_CHUNK_MIN;   // room for the smallest chunk
     L.n_part = (c.vocab + 1023) / 1024;
     if (L.n_part > TOPK_PART_MAX) L.n_part = TOPK_PART_MAX;
     L.per_part = (c.vocab + L.n_part - 1) / L.n_part;
