@@ -325,3 +325,60 @@ def generate(lm, tables, prefix, cfg: DecodeCfg, n_tokens: int, dtype=np.float32
         state, rec = expand_and_prune(state, logits, tables, cfg, dtype, keep_logits, gamma)
         records.append(rec)
     return state, records
+
+
+# ===================================================================== nucleus sampling
+# The comparison decoder of Section 4.3 (one of k independent passes): Section 2 describes it
+# as truncating the next-token distribution to the smallest set of tokens whose cumulative
+# probability reaches p, then sampling from the renormalised set.  Readings: the cumulative
+# probability has to reach (>=) p; the vocabulary is ordered by probability descending with
+# the lower token id first among equals, the nucleus is the shortest prefix of that order,
+# and the draw u in [0, 1) picks the first token whose cumulative probability within that
+# order exceeds u times the nucleus mass (inverse CDF).  The temperature divides the logits
+# of the full-vocabulary softmax, as for SPD.  The uniform number u is an input.
+@dataclass
+class NucleusRecord:
+    token: int
+    logp: float            # log p_theta(token) under the full-vocabulary softmax
+    nucleus_size: int
+    nucleus_mass: float
+    margin_sample: float   # distance of u * mass to the nearer cumulative boundary of the chosen token
+    margin_nucleus: float  # distance of p to the nearer cumulative boundary at the nucleus edge
+    p_edge: float          # probability of the token just past the nucleus (0 if none)
+    logits: np.ndarray | None = None
+
+
+def nucleus_sample(logits, top_p: float, tau: float, u: float, keep_logits: bool = False) -> NucleusRecord:
+    lp = log_softmax_tau(np.asarray(logits), tau, np.float64)
+    p = np.exp(lp)
+    order = np.lexsort((np.arange(p.size), -p))          # probability descending, then id ascending
+    cs = np.cumsum(p[order])
+    n = int(np.searchsorted(cs, top_p, side="left"))     # first index with cs >= top_p
+    n = min(n, p.size - 1)
+    mass = float(cs[n])
+    target = u * mass
+    j = int(np.searchsorted(cs[: n + 1], target, side="right"))   # first index with cs > target
+    j = min(j, n)
+    lo = float(cs[j - 1]) if j > 0 else 0.0
+    below = float(cs[n - 1]) if n > 0 else 0.0
+    return NucleusRecord(token=int(order[j]), logp=float(lp[order[j]]), nucleus_size=n + 1, nucleus_mass=mass,
+                         margin_sample=min(target - lo, float(cs[j]) - target),
+                         margin_nucleus=min(top_p - below, mass - top_p),
+                         p_edge=float(p[order[n + 1]]) if n + 1 < p.size else 0.0,
+                         logits=np.asarray(logits).copy() if keep_logits else None)
+
+
+def nucleus_generate(lm, prefix, top_p: float, tau: float, us, keep_logits: bool = False):
+    """One pass of nucleus sampling: len(us) tokens after `prefix`, us[t] the draw of token t.
+    Returns (tokens, sum of their log-probabilities, records)."""
+    lm.reset()
+    logits = lm.forward(lm.embedding_rows(np.asarray(prefix, dtype=np.int64)))
+    toks, recs, total = [], [], 0.0
+    for t, u in enumerate(us):
+        if t > 0:
+            logits = lm.forward(lm.embedding_rows(np.asarray([toks[-1]], dtype=np.int64)))
+        rec = nucleus_sample(logits, top_p, tau, float(u), keep_logits)
+        toks.append(rec.token)
+        total += rec.logp
+        recs.append(rec)
+    return toks, total, recs
