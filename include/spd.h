@@ -176,6 +176,40 @@ int spd_get_step_info(spd_ctx *ctx, int32_t *out_top_ids, float *out_top_logp,
  * not touch the KV cache or the position.  Does not synchronise. */
 int spd_expand_prune(spd_ctx *ctx, const spd_decode_cfg *dc, const float *dev_logits, int32_t first);
 
+/* ---- the comparison decoder: one pass of nucleus (top-p) sampling ----
+ * Section 4.3 times Superposed Decoding against k independent passes of nucleus sampling;
+ * Section 2 describes the sampler: the next-token distribution is cut to the smallest set of
+ * most probable tokens whose cumulative probability reaches top_p and renormalised.  Here:
+ * probabilities are the full-vocabulary softmax of logits / tau; tokens are ordered by
+ * probability, the lower id first among equals; the nucleus is the shortest prefix of that
+ * order whose mass reaches top_p; the draw u in [0, 1) (supplied by the caller, who owns the
+ * random number generator) selects the first token whose cumulative probability in that
+ * order exceeds u times the nucleus mass. */
+typedef struct spd_sample_cfg {
+    float top_p; /* in (0, 1] */
+    float tau;   /* > 0 */
+} spd_sample_cfg;
+
+/* One token of one pass.  The first call after spd_prefill samples from the prefix pass's
+ * logits; every later call feeds the previously sampled token's embedding through the
+ * transformer (one more cached position) and samples from the new logits.  out_token /
+ * out_logprob: HOST, may be NULL (then the call does not synchronise); the log-probability
+ * is that of the sampled token under the full-vocabulary softmax.  A pass and an SPD
+ * generation with k > 1 cannot be interleaved on one context (SPD_ESTATE); spd_prefill
+ * starts either. */
+int spd_nucleus_step(spd_ctx *ctx, const spd_sample_cfg *sc, float u, int32_t *out_token, float *out_logprob);
+
+/* Run only the sampler (not the transformer) on caller-supplied DEVICE logits float [vocab],
+ * as if the forward pass had produced them; `first` != 0 starts a pass (as the first
+ * spd_nucleus_step after spd_prefill does).  Does not touch the KV cache or the position.
+ * Does not synchronise; read the result with spd_get_state / spd_get_nucleus_info. */
+int spd_nucleus_sample(spd_ctx *ctx, const spd_sample_cfg *sc, float u, const float *dev_logits, int32_t first);
+
+/* Size and probability mass of the nucleus of the most recent sampling call, and the sum
+ * of the log-probabilities of the tokens sampled so far in this pass.  HOST outputs, any may
+ * be NULL.  Synchronises. */
+int spd_get_nucleus_info(spd_ctx *ctx, int32_t *out_size, float *out_mass, float *out_sum_logprob);
+
 /* Current position (= number of cached positions) as tracked by the host. */
 int spd_position(const spd_ctx *ctx, int32_t *out_pos);
 

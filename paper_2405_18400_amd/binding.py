@@ -46,6 +46,10 @@ class SpdDecodeCfg(C.Structure):
     _fields_ = [("k", C.c_int32), ("alpha", C.c_float), ("tau", C.c_float), ("delta", C.c_float)]
 
 
+class SpdSampleCfg(C.Structure):
+    _fields_ = [("top_p", C.c_float), ("tau", C.c_float)]
+
+
 def library_path() -> str:
     return os.environ.get("SPD_LIBRARY", os.path.join(HERE, "libspd.so"))
 
@@ -66,6 +70,9 @@ def lib():
             "spd_load_ngrams": [vp, C.POINTER(SpdNgramHostTables), vp, sz],
             "spd_prefill": [vp, vp, i32],
             "spd_step": [vp, C.POINTER(SpdDecodeCfg), vp, vp, vp],
+            "spd_nucleus_step": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, vp],
+            "spd_get_nucleus_info": [vp, vp, vp, vp],
+            "spd_nucleus_sample": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, i32],
             "spd_generate": [vp, vp, i32, C.POINTER(SpdDecodeCfg), i32, vp, vp],
             "spd_get_state": [vp, C.POINTER(i32), vp, vp, vp],
             "spd_set_state": [vp, i32, vp, vp],
@@ -235,6 +242,24 @@ class Session:
         tok, par, sc = np.zeros(dc.k, np.int32), np.zeros(dc.k, np.int32), np.zeros(dc.k, np.float32)
         self._chk(self.L.spd_step(self.ctx, C.byref(dc), _np_ptr(tok), _np_ptr(par), _np_ptr(sc)), "spd_step")
         return tok, par, sc
+
+    def spd_nucleus_step(self, sc: SpdSampleCfg, u: float, fetch: bool = True):
+        if not fetch:
+            self._chk(self.L.spd_nucleus_step(self.ctx, C.byref(sc), float(u), None, None), "spd_nucleus_step")
+            return None
+        tok, lp = C.c_int32(0), C.c_float(0)
+        self._chk(self.L.spd_nucleus_step(self.ctx, C.byref(sc), float(u), C.byref(tok), C.byref(lp)), "spd_nucleus_step")
+        return tok.value, lp.value
+
+    def spd_nucleus_sample(self, sc: SpdSampleCfg, u: float, dev_logits, first: bool):
+        assert dev_logits.is_cuda and dev_logits.dtype == _torch().float32 and dev_logits.numel() == self.shape.vocab
+        self._chk(self.L.spd_nucleus_sample(self.ctx, C.byref(sc), float(u), dev_logits.data_ptr(), int(first)),
+                  "spd_nucleus_sample")
+
+    def spd_get_nucleus_info(self):
+        size, mass, total = C.c_int32(0), C.c_float(0), C.c_float(0)
+        self._chk(self.L.spd_get_nucleus_info(self.ctx, C.byref(size), C.byref(mass), C.byref(total)), "spd_get_nucleus_info")
+        return size.value, mass.value, total.value
 
     def spd_generate(self, prefix, dc: SpdDecodeCfg, n_tokens: int):
         p = np.ascontiguousarray(prefix, dtype=np.int32)

@@ -70,6 +70,9 @@ struct DevState {
     float cand_score[SPD_KK];             // option (i, j) at [i * k + j]
     int32_t cand_valid[SPD_KK];
     float cand_png[SPD_KK];
+    float sample_u;                       // nucleus pass: the uniform draw of the next token (host-written)
+    int32_t nucleus_size;                 // nucleus pass: size and mass of the last nucleus
+    float nucleus_mass;
 };
 
 // ---------------------------------------------------------------- kernel launch arguments
@@ -118,6 +121,18 @@ struct TopkArgs {
     float *pv;    // [n_part, SPD_K_MAX]
     int32_t *pi;  // [n_part, SPD_K_MAX]
     float *pm, *ps;  // [n_part]
+};
+
+struct NucleusArgs {
+    const float *logits;
+    int32_t vocab;
+    DevState *st;
+    const float *pm, *ps;   // per-slice max and sum of exp of logit / tau (topk_partial)
+    int32_t n_part;
+    float top_p, tau;
+    int32_t first, advance;
+    int32_t *hist_tok, *hist_par;
+    int32_t max_gen;
 };
 
 struct ExpandArgs {
@@ -183,6 +198,7 @@ hipError_t attention(hipStream_t s, int dtype, const AttnArgs &a);
 hipError_t superpose(hipStream_t s, int dtype, const SuperposeArgs &a);
 hipError_t topk_partial(hipStream_t s, const TopkArgs &a);
 hipError_t expand_prune(hipStream_t s, const ExpandArgs &a);
+hipError_t nucleus(hipStream_t s, const NucleusArgs &a);
 hipError_t advance(hipStream_t s, DevState *st);
 hipError_t renorm(hipStream_t s, DevState *st, int k);
 hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);

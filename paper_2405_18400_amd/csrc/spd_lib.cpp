@@ -15,9 +15,9 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 enum State { ST_CREATED = 0, ST_PREFILLED = 1, ST_STEPPING = 2 };
 
-enum KClass { KC_SUPERPOSE, KC_QKV, KC_ATTN, KC_O, KC_GATEUP, KC_DOWN, KC_HEAD, KC_TOPK, KC_EXPAND, KC_FUSED, KC_N };
+enum KClass { KC_SUPERPOSE, KC_QKV, KC_ATTN, KC_O, KC_GATEUP, KC_DOWN, KC_HEAD, KC_TOPK, KC_EXPAND, KC_FUSED, KC_NUCLEUS, KC_N };
 const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_o", "gemv_gateup",
-                                    "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward"};
+                                    "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward", "nucleus"};
 
 struct Layout {
     size_t state, barrier, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
@@ -107,8 +107,9 @@ struct spd_ctx {
     size_t pinned_bytes;
     bool use_graph, timing, use_fused;
     int fused_blocks;   // grid of the fused forward kernel; 0 = not available for this shape
-    hipGraphExec_t step_exec, prefill_exec;
+    hipGraphExec_t step_exec, prefill_exec, nucleus_exec;
     spd_decode_cfg step_dc;
+    spd_sample_cfg nucleus_sc;
     std::vector<Timed> timed;
     std::vector<hipEvent_t> ev_pool;
     double kc_ms[KC_N];
@@ -249,6 +250,20 @@ hipError_t enqueue_decide(spd_ctx *c, const spd_decode_cfg &dc, const float *log
     return launch(c, KC_EXPAND, [&] { return spdk::expand_prune(c->stream, x); });
 }
 
+// Post-forward part of one nucleus-sampling step: slice statistics, then the sampler.
+hipError_t enqueue_sample(spd_ctx *c, const spd_sample_cfg &sc, const float *logits, int first, int advance) {
+    TopkArgs t{logits, c->cfg.vocab, 1, c->L.n_part, c->L.per_part, sc.tau,
+               c->at<float>(c->L.pv), c->at<int32_t>(c->L.pi), c->at<float>(c->L.pm), c->at<float>(c->L.ps)};
+    hipError_t e = launch(c, KC_TOPK, [&] { return spdk::topk_partial(c->stream, t); });
+    if (e != hipSuccess) return e;
+    NucleusArgs n{};
+    n.logits = logits; n.vocab = c->cfg.vocab; n.st = c->st(); n.pm = t.pm; n.ps = t.ps; n.n_part = c->L.n_part;
+    n.top_p = sc.top_p; n.tau = sc.tau; n.first = first; n.advance = advance;
+    n.hist_tok = c->at<int32_t>(c->L.hist_tok); n.hist_par = c->at<int32_t>(c->L.hist_par);
+    n.max_gen = c->cfg.max_ctx;
+    return launch(c, KC_NUCLEUS, [&] { return spdk::nucleus(c->stream, n); });
+}
+
 void drop_graph(hipGraphExec_t &g) {
     if (g) { (void)hipGraphExecDestroy(g); g = nullptr; }
 }
@@ -334,7 +349,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     std::memset(&c->ng, 0, sizeof(c->ng));
     c->state = ST_CREATED; c->pos = 0; c->n_gen = 0; c->k = 0;
     c->use_graph = true; c->timing = false; c->use_fused = true; c->fused_blocks = 0;
-    c->step_exec = nullptr; c->prefill_exec = nullptr;
+    c->step_exec = nullptr; c->prefill_exec = nullptr; c->nucleus_exec = nullptr;
     std::memset(&c->step_dc, 0, sizeof(c->step_dc));
     std::memset(c->kc_ms, 0, sizeof(c->kc_ms));
     std::memset(c->kc_n, 0, sizeof(c->kc_n));
@@ -381,6 +396,7 @@ void spd_destroy(spd_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     drop_graph(c->step_exec);
     drop_graph(c->prefill_exec);
+    drop_graph(c->nucleus_exec);
     for (auto &t : c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     for (auto &e : c->ev_pool) (void)hipEventDestroy(e);
     if (c->pinned) (void)hipHostFree(c->pinned);
@@ -508,6 +524,90 @@ int spd_step(spd_ctx *c, const spd_decode_cfg *dc, int32_t *out_tok, int32_t *ou
     c->pos += 1;
     c->n_gen += 1;
     return copy_step_outputs(c, dc->k, out_tok, out_par, out_sc);
+}
+
+static const char *check_sample(const spd_sample_cfg *sc, float u);
+
+int spd_nucleus_step(spd_ctx *c, const spd_sample_cfg *sc, float u, int32_t *out_tok, float *out_logprob) {
+    if (!c) return SPD_EINVAL;
+    if (const char *why = check_sample(sc, u)) return fail(c, SPD_EINVAL, why);
+    if (c->state == ST_CREATED) return fail(c, SPD_ESTATE, "spd_nucleus_step before spd_prefill");
+    if (c->state == ST_STEPPING && c->k != 1) return fail(c, SPD_ESTATE, "a generation with k > 1 drafts is in progress");
+    uint32_t bits;
+    std::memcpy(&bits, &u, 4);
+    HIPCHK(c, hipMemsetD32Async((hipDeviceptr_t)&c->st()->sample_u, (int)bits, 1, c->stream));
+    if (c->state == ST_PREFILLED) {
+        HIPCHK(c, enqueue_sample(c, *sc, c->at<float>(c->L.logits), 1, 0));
+        c->state = ST_STEPPING;
+        c->k = 1;
+        c->n_gen = 1;
+    } else {
+        if (c->pos + 1 > c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "KV cache is full");
+        if (c->n_gen >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "token history is full");
+        auto body = [&]() -> hipError_t {
+            hipError_t e = enqueue_forward(c, 1, 1, true);
+            if (e == hipSuccess) e = enqueue_sample(c, *sc, c->at<float>(c->L.logits), 0, 1);
+            return e;
+        };
+        if (graphs_usable(c)) {
+            if (c->nucleus_exec && std::memcmp(&c->nucleus_sc, sc, sizeof(*sc)) != 0) drop_graph(c->nucleus_exec);
+            if (!c->nucleus_exec) {
+                const int rc = capture(c, &c->nucleus_exec, body);
+                if (rc != SPD_OK) return rc;
+                c->nucleus_sc = *sc;
+            }
+            HIPCHK(c, hipGraphLaunch(c->nucleus_exec, c->stream));
+        } else {
+            HIPCHK(c, body());
+        }
+        c->pos += 1;
+        c->n_gen += 1;
+    }
+    if (!out_tok && !out_logprob) return SPD_OK;
+    DevState *hs = (DevState *)c->pinned;
+    HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+    if (c->timing) HIPCHK(c, drain_timing(c));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    if (out_tok) *out_tok = hs->new_tok[0];
+    if (out_logprob) *out_logprob = hs->top_logp[0];
+    return SPD_OK;
+}
+
+static const char *check_sample(const spd_sample_cfg *sc, float u) {
+    if (!sc) return "sample cfg is null";
+    if (!(sc->top_p > 0.f && sc->top_p <= 1.f)) return "top_p outside (0, 1]";
+    if (!(sc->tau > 0.f)) return "tau must be positive";
+    if (!(u >= 0.f && u < 1.f)) return "the draw u must lie in [0, 1)";
+    return nullptr;
+}
+
+int spd_nucleus_sample(spd_ctx *c, const spd_sample_cfg *sc, float u, const float *dev_logits, int32_t first) {
+    if (!c) return SPD_EINVAL;
+    if (const char *why = check_sample(sc, u)) return fail(c, SPD_EINVAL, why);
+    if (!dev_logits) return fail(c, SPD_EINVAL, "logits pointer is null");
+    if (c->state == ST_CREATED) return fail(c, SPD_ESTATE, "spd_nucleus_sample before spd_prefill");
+    if (!first && (c->state != ST_STEPPING || c->k != 1)) return fail(c, SPD_ESTATE, "no nucleus pass is in progress");
+    if (!first && c->n_gen >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "token history is full");
+    uint32_t bits;
+    std::memcpy(&bits, &u, 4);
+    HIPCHK(c, hipMemsetD32Async((hipDeviceptr_t)&c->st()->sample_u, (int)bits, 1, c->stream));
+    HIPCHK(c, enqueue_sample(c, *sc, dev_logits, first ? 1 : 0, 0));
+    if (first) { c->state = ST_STEPPING; c->k = 1; c->n_gen = 1; }
+    else c->n_gen += 1;
+    return SPD_OK;
+}
+
+int spd_get_nucleus_info(spd_ctx *c, int32_t *out_size, float *out_mass, float *out_sum_logprob) {
+    if (!c) return SPD_EINVAL;
+    if (c->state != ST_STEPPING || c->k != 1) return fail(c, SPD_ESTATE, "no nucleus step has run");
+    DevState *hs = (DevState *)c->pinned;
+    HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (out_size) *out_size = hs->nucleus_size;
+    if (out_mass) *out_mass = hs->nucleus_mass;
+    if (out_sum_logprob) *out_sum_logprob = hs->logscore[0];
+    return SPD_OK;
 }
 
 int spd_generate(spd_ctx *c, const int32_t *prefix, int32_t m, const spd_decode_cfg *dc, int32_t n_tokens,
@@ -648,7 +748,7 @@ int spd_set_graph(spd_ctx *c, int32_t enable) {
 int spd_set_fused(spd_ctx *c, int32_t enable) {
     if (!c) return SPD_EINVAL;
     if (enable && c->fused_blocks == 0) return fail(c, SPD_EINVAL, "no fused forward kernel for this model shape");
-    if ((enable != 0) != c->use_fused) { drop_graph(c->step_exec); drop_graph(c->prefill_exec); }
+    if ((enable != 0) != c->use_fused) { drop_graph(c->step_exec); drop_graph(c->prefill_exec); drop_graph(c->nucleus_exec); }
     c->use_fused = enable != 0;
     return SPD_OK;
 }
