@@ -224,6 +224,15 @@ int spd_set_graph(spd_ctx *ctx, int32_t enable);
 int spd_set_fused(spd_ctx *ctx, int32_t enable);
 int spd_get_fused(const spd_ctx *ctx, int32_t *out_enabled);
 
+/* spd_prefill runs the prefix either one token at a time through the timestep's forward, or
+ * ("dense": the default for bf16 models whose widths allow it, for prefixes of 8 tokens or
+ * more) 256 prefix tokens at a time as matrix-matrix products on the matrix cores, reading the
+ * weights once per 256 tokens.  Both fill the same cache and leave the same logits up to fp32
+ * rounding.  spd_set_dense_prefill switches (SPD_EINVAL when asked for a dense pass the model
+ * has none for). */
+int spd_set_dense_prefill(spd_ctx *ctx, int32_t enable);
+int spd_get_dense_prefill(const spd_ctx *ctx, int32_t *out_enabled);
+
 /* Per-kernel timing for profiling runs: when enabled, spd_step launches kernels one by one
  * with a HIP event pair around each and accumulates the elapsed time per kernel class.
  * spd_get_kernel_timing fills HOST arrays of up to `cap` entries (class name pointers valid

@@ -72,6 +72,8 @@ def lib():
             "spd_step": [vp, C.POINTER(SpdDecodeCfg), vp, vp, vp],
             "spd_nucleus_step": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, vp],
             "spd_get_nucleus_info": [vp, vp, vp, vp],
+            "spd_set_dense_prefill": [vp, i32],
+            "spd_get_dense_prefill": [vp, C.POINTER(i32)],
             "spd_nucleus_sample": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, i32],
             "spd_generate": [vp, vp, i32, C.POINTER(SpdDecodeCfg), i32, vp, vp],
             "spd_get_state": [vp, C.POINTER(i32), vp, vp, vp],
@@ -242,6 +244,14 @@ class Session:
         tok, par, sc = np.zeros(dc.k, np.int32), np.zeros(dc.k, np.int32), np.zeros(dc.k, np.float32)
         self._chk(self.L.spd_step(self.ctx, C.byref(dc), _np_ptr(tok), _np_ptr(par), _np_ptr(sc)), "spd_step")
         return tok, par, sc
+
+    def spd_set_dense_prefill(self, enable: bool):
+        self._chk(self.L.spd_set_dense_prefill(self.ctx, int(enable)), "spd_set_dense_prefill")
+
+    def spd_get_dense_prefill(self) -> bool:
+        out = C.c_int32(0)
+        self._chk(self.L.spd_get_dense_prefill(self.ctx, C.byref(out)), "spd_get_dense_prefill")
+        return bool(out.value)
 
     def spd_nucleus_step(self, sc: SpdSampleCfg, u: float, fetch: bool = True):
         if not fetch:

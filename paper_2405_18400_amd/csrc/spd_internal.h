@@ -181,6 +181,25 @@ struct FusedArgsHost {
     float eps;
 };
 
+// One chunk of the dense prefix pass (bf16 weights): T <= PREFILL_CHUNK prefix tokens at
+// positions p0 .. p0 + T - 1.  Arena buffers are DEVICE, sized for PREFILL_CHUNK rows.
+constexpr int PREFILL_CHUNK = 256;
+struct PrefillChunk {
+    const void *embed;
+    const int32_t *prefix;             // DEVICE token ids of the whole prefix
+    const spd_layer_weights *layers;   // HOST array [n_layers]
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, cap_ctx, p0, T;
+    float eps;
+    const double *inv_freq;
+    char *kv;
+    size_t kv_layer_bytes;
+    float *h, *h1;                     // [PREFILL_CHUNK, d_model] residual stream (in / out) and after attention
+    float *q;                          // [PREFILL_CHUNK, n_heads * d_head]
+    uint16_t *xhi, *xlo;               // [PREFILL_CHUNK, max(d_model, n_heads * d_head)] bf16 pair
+    uint16_t *uhi, *ulo;               // [PREFILL_CHUNK, d_ffn] bf16 pair
+    float2 *rope;                      // [PREFILL_CHUNK, d_head / 2]
+};
+
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
 constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
@@ -199,6 +218,8 @@ hipError_t superpose(hipStream_t s, int dtype, const SuperposeArgs &a);
 hipError_t topk_partial(hipStream_t s, const TopkArgs &a);
 hipError_t expand_prune(hipStream_t s, const ExpandArgs &a);
 hipError_t nucleus(hipStream_t s, const NucleusArgs &a);
+hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c);
+hipError_t prefill_init();
 hipError_t advance(hipStream_t s, DevState *st);
 hipError_t renorm(hipStream_t s, DevState *st, int k);
 hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);

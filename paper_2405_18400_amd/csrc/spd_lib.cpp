@@ -20,6 +20,8 @@ const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_
                                     "gemv_down", "gemv_head", "topk_partial", "expand_prune", "fused_forward", "nucleus"};
 
 struct Layout {
+    size_t pf_h, pf_h1, pf_q, pf_xhi, pf_xlo, pf_uhi, pf_ulo, pf_rope;   // dense prefix pass arena (0 = none)
+    bool dense;
     size_t state, barrier, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     int max_splits, n_part, per_part;
@@ -82,6 +84,20 @@ Layout make_layout(const spd_model_cfg &c) {
     L.pi = take((size_t)L.n_part * SPD_K_MAX * 4);
     L.pm = take((size_t)L.n_part * 4);
     L.ps = take((size_t)L.n_part * 4);
+    // dense prefix pass (matrix cores): bf16 weights, d_head <= 128, widths the tiles divide
+    L.dense = c.dtype == SPD_DTYPE_BF16 && dh <= 128 && c.d_model % 64 == 0 && c.d_ffn % 64 == 0 &&
+              (c.n_heads * dh) % 64 == 0 && c.n_layers > 0;
+    if (L.dense) {
+        const size_t nq = (size_t)c.n_heads * dh, wide = nq > (size_t)c.d_model ? nq : (size_t)c.d_model;
+        L.pf_h = take((size_t)PREFILL_CHUNK * c.d_model * 4);
+        L.pf_h1 = take((size_t)PREFILL_CHUNK * c.d_model * 4);
+        L.pf_q = take((size_t)PREFILL_CHUNK * nq * 4);
+        L.pf_xhi = take((size_t)PREFILL_CHUNK * wide * 2);
+        L.pf_xlo = take((size_t)PREFILL_CHUNK * wide * 2);
+        L.pf_uhi = take((size_t)PREFILL_CHUNK * c.d_ffn * 2);
+        L.pf_ulo = take((size_t)PREFILL_CHUNK * c.d_ffn * 2);
+        L.pf_rope = take((size_t)PREFILL_CHUNK * (dh / 2) * 8);
+    }
     L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * sizeof(float));   // fp32 cache
     L.kv = take(L.kv_layer_bytes * 2 * (size_t)c.n_layers);
     L.total = o;
@@ -105,7 +121,7 @@ struct spd_ctx {
     int state, pos, n_gen, k;
     char *pinned;
     size_t pinned_bytes;
-    bool use_graph, timing, use_fused;
+    bool use_graph, timing, use_fused, use_dense;
     int fused_blocks;   // grid of the fused forward kernel; 0 = not available for this shape
     hipGraphExec_t step_exec, prefill_exec, nucleus_exec;
     spd_decode_cfg step_dc;
@@ -292,6 +308,8 @@ const char *check_dc(const spd_ctx *c, const spd_decode_cfg *dc) {
     return nullptr;
 }
 
+constexpr int DENSE_PREFILL_MIN = 8;   // shorter prefixes go token by token
+
 bool graphs_usable(const spd_ctx *c) { return c->use_graph && !c->timing && c->stream != nullptr; }
 
 }  // namespace
@@ -349,6 +367,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     std::memset(&c->ng, 0, sizeof(c->ng));
     c->state = ST_CREATED; c->pos = 0; c->n_gen = 0; c->k = 0;
     c->use_graph = true; c->timing = false; c->use_fused = true; c->fused_blocks = 0;
+    c->use_dense = c->L.dense && spdk::prefill_init() == hipSuccess;
     c->step_exec = nullptr; c->prefill_exec = nullptr; c->nucleus_exec = nullptr;
     std::memset(&c->step_dc, 0, sizeof(c->step_dc));
     std::memset(c->kc_ms, 0, sizeof(c->kc_ms));
@@ -455,6 +474,33 @@ int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
     c->state = ST_CREATED;
     c->pos = 0; c->n_gen = 0; c->k = 0;
 
+    if (c->use_dense && m >= DENSE_PREFILL_MIN) {
+        // whole chunks of prefix tokens on the matrix cores; the last token's final norm and
+        // LM head go through the matrix-vector kernel
+        const spd_model_cfg &mc = c->cfg;
+        PrefillChunk pc{};
+        pc.embed = c->embed; pc.prefix = c->at<int32_t>(c->L.prefix); pc.layers = c->layers.data();
+        pc.n_layers = mc.n_layers; pc.d_model = mc.d_model; pc.n_heads = mc.n_heads; pc.n_kv_heads = mc.n_kv_heads;
+        pc.d_ffn = mc.d_ffn; pc.cap_ctx = mc.max_ctx; pc.eps = mc.rms_eps;
+        pc.inv_freq = c->at<double>(c->L.inv_freq); pc.kv = c->ws + c->L.kv; pc.kv_layer_bytes = c->L.kv_layer_bytes;
+        pc.h = c->at<float>(c->L.pf_h); pc.h1 = c->at<float>(c->L.pf_h1); pc.q = c->at<float>(c->L.pf_q);
+        pc.xhi = c->at<uint16_t>(c->L.pf_xhi); pc.xlo = c->at<uint16_t>(c->L.pf_xlo);
+        pc.uhi = c->at<uint16_t>(c->L.pf_uhi); pc.ulo = c->at<uint16_t>(c->L.pf_ulo);
+        pc.rope = c->at<float2>(c->L.pf_rope);
+        int last_T = 0;
+        for (int p0 = 0; p0 < m; p0 += PREFILL_CHUNK) {
+            pc.p0 = p0; pc.T = last_T = (m - p0 < PREFILL_CHUNK) ? m - p0 : PREFILL_CHUNK;
+            HIPCHK(c, spdk::prefill_chunk(c->stream, pc));
+        }
+        GemvArgs g{};
+        g.W = c->lm_head; g.gain = c->final_norm; g.eps = mc.rms_eps; g.x = pc.h + (size_t)(last_T - 1) * mc.d_model;
+        g.y = c->at<float>(c->L.logits); g.rows = mc.vocab; g.cols = mc.d_model;
+        HIPCHK(c, spdk::gemv(c->stream, mc.dtype, EPI_PLAIN, g, c->num_cu));
+        HIPCHK(c, spdk::fill_i32(c->stream, &c->st()->pos, m, 1));
+        c->pos = m;
+        c->state = ST_PREFILLED;
+        return SPD_OK;
+    }
     auto one_token = [&]() -> hipError_t {
         hipError_t e = enqueue_forward(c, 0, 1, false);
         if (e == hipSuccess) e = spdk::advance(c->stream, c->st());
@@ -750,6 +796,19 @@ int spd_set_fused(spd_ctx *c, int32_t enable) {
     if (enable && c->fused_blocks == 0) return fail(c, SPD_EINVAL, "no fused forward kernel for this model shape");
     if ((enable != 0) != c->use_fused) { drop_graph(c->step_exec); drop_graph(c->prefill_exec); drop_graph(c->nucleus_exec); }
     c->use_fused = enable != 0;
+    return SPD_OK;
+}
+
+int spd_set_dense_prefill(spd_ctx *c, int32_t enable) {
+    if (!c) return SPD_EINVAL;
+    if (enable && !c->L.dense) return fail(c, SPD_EINVAL, "no dense prefix pass for this model (bf16 weights, d_head <= 128, widths divisible by 64)");
+    c->use_dense = enable != 0;
+    return SPD_OK;
+}
+
+int spd_get_dense_prefill(const spd_ctx *c, int32_t *out_enabled) {
+    if (!c || !out_enabled) return SPD_EINVAL;
+    *out_enabled = c->use_dense ? 1 : 0;
     return SPD_OK;
 }
 

@@ -181,6 +181,46 @@ def test_70b_shape_one_layer(forward_path):
     _layer_truncated(synth.LLAMA70B, 1, 131, 3, 3, 70, forward_path)
 
 
+@pytest.mark.parametrize("m", [8, 31, 33, 64, 257, 300])
+def test_dense_prefix_pass_matches_the_oracle_and_the_token_by_token_pass(m):
+    """The prefix pass on the matrix cores (256 tokens per weight pass) against the oracle's
+    full-sequence forward and against the token-by-token pass: logits after the prefix, and
+    three timesteps on top of the cache it filled.  Sizes straddle the 32- and 64-token tiles
+    and the 256-token chunk; grouped key/value heads."""
+    pkg = P()
+    shape = synth.ModelShape("small-bf16-dense", 3, 512, 8, 2, 1408, 2048, "bf16")
+    w = synth.make_weights(shape, seed=21)
+    prefix = synth.make_prefix_zipf(shape.vocab, m, seed=m)
+    lm = make_oracle(shape, w)
+    cfg = O.DecodeCfg(3, 0.0)
+    dc = pkg.SpdDecodeCfg(3, 0.0, 1.0, 0.1)
+    logits = {}
+    for dense in (True, False):
+        sess = session(shape, w, max_ctx=m + 16)
+        try:
+            assert sess.spd_get_dense_prefill()
+            sess.spd_set_dense_prefill(dense)
+            state, recs, stats = teacher_forced(sess, lm, None, synth.PAPER_LAMBDAS, prefix, cfg, 4, RTOL["bf16"], dc)
+            assert max(s["logit_err"] for s in stats if "logit_err" in s) < 1e-4      # far inside the bf16 tolerance
+            sess.spd_prefill(prefix)
+            logits[dense] = sess.spd_read_logits()
+        finally:
+            sess.close()
+    assert np.max(np.abs(logits[True] - logits[False])) <= 1e-4 * np.max(np.abs(logits[False]))
+
+
+def test_dense_prefix_pass_is_refused_where_it_does_not_exist(tiny):
+    shape, w, tabs, prefix = tiny           # fp32 weights
+    sess = session(shape, w)
+    try:
+        assert not sess.spd_get_dense_prefill()
+        with pytest.raises(P().SpdError):
+            sess.spd_set_dense_prefill(True)
+        sess.spd_set_dense_prefill(False)
+    finally:
+        sess.close()
+
+
 def test_fused_and_per_operator_forward_agree(tiny):
     """Same inputs through both forward paths: logits agree to fp32 rounding, drafts are equal."""
     shape, w, tabs, prefix = tiny
