@@ -143,16 +143,24 @@ __global__ __launch_bounds__(GNT, 2) void prefill_gemm_kernel(const PrefillGemmA
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][tt][r] = 0.f;
+    // Two steps in flight.  K is a multiple of two steps (the host checks), so the loop body has
+    // no branch at all: a load or a product under a branch makes the compiler wait for
+    // everything outstanding.  Past the end the last step is simply requested again.
     Frags<NMAT> f0, f1;
+    const int k_last = a.K - KSTEP;
     load_step<TT, NMAT>(a, f0, t0, nl, 0, lane);
-    int k0 = 0;
-    for (; k0 + 2 * KSTEP <= a.K; k0 += 2 * KSTEP) {
+    for (int k0 = 0; k0 < a.K; k0 += 2 * KSTEP) {
+        // (the scheduling barriers keep the compiler from sinking a step's loads down to their
+        // first use, which would put a memory latency in front of every product)
         load_step<TT, NMAT>(a, f1, t0, nl, k0 + KSTEP, lane);
+        __builtin_amdgcn_sched_barrier(0);
         mma_step<TT, NMAT>(f0, acc);
-        if (k0 + 2 * KSTEP < a.K) load_step<TT, NMAT>(a, f0, t0, nl, k0 + 2 * KSTEP, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        load_step<TT, NMAT>(a, f0, t0, nl, min(k0 + 2 * KSTEP, k_last), lane);
+        __builtin_amdgcn_sched_barrier(0);
         mma_step<TT, NMAT>(f1, acc);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    if (k0 < a.K) mma_step<TT, NMAT>(f0, acc);                  // odd number of steps
 
     // C layout: lane -> column nc = tile + lane % 32; register r -> token 8 (r / 4) + 4 (lane / 32) + r % 4
     const int nc = blockIdx.y * G_NB + 32 * w + lane % 32;
