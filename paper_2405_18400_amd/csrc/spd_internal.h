@@ -183,12 +183,12 @@ struct FusedArgsHost {
 
 // One chunk of the dense prefix pass (bf16 weights): T <= PREFILL_CHUNK prefix tokens at
 // positions p0 .. p0 + T - 1.  Arena buffers are DEVICE, sized for PREFILL_CHUNK rows.
-constexpr int PREFILL_CHUNK = 256;
+constexpr int PREFILL_CHUNK = 512;
 struct PrefillChunk {
     const void *embed;
     const int32_t *prefix;             // DEVICE token ids of the whole prefix
     const spd_layer_weights *layers;   // HOST array [n_layers]
-    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, cap_ctx, p0, T;
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, cap_ctx, p0, T, num_cu;
     float eps;
     const double *inv_freq;
     char *kv;

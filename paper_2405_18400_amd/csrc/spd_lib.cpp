@@ -481,7 +481,7 @@ int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
         PrefillChunk pc{};
         pc.embed = c->embed; pc.prefix = c->at<int32_t>(c->L.prefix); pc.layers = c->layers.data();
         pc.n_layers = mc.n_layers; pc.d_model = mc.d_model; pc.n_heads = mc.n_heads; pc.n_kv_heads = mc.n_kv_heads;
-        pc.d_ffn = mc.d_ffn; pc.cap_ctx = mc.max_ctx; pc.eps = mc.rms_eps;
+        pc.d_ffn = mc.d_ffn; pc.cap_ctx = mc.max_ctx; pc.eps = mc.rms_eps; pc.num_cu = c->num_cu;
         pc.inv_freq = c->at<double>(c->L.inv_freq); pc.kv = c->ws + c->L.kv; pc.kv_layer_bytes = c->L.kv_layer_bytes;
         pc.h = c->at<float>(c->L.pf_h); pc.h1 = c->at<float>(c->L.pf_h1); pc.q = c->at<float>(c->L.pf_q);
         pc.xhi = c->at<uint16_t>(c->L.pf_xhi); pc.xlo = c->at<uint16_t>(c->L.pf_xlo);

@@ -8,10 +8,11 @@
 // (16 mantissa bits together), and W x = W hi + W lo is two matrix-core products into the same
 // fp32 accumulator.  Feeding bf16(x) alone costs about 2e-2 of the logit scale over 32 layers.
 //
-// Operands need no LDS staging: with W row-major [rows, d] and activations [tokens, d], both
+// Operands need no transposition: with W row-major [rows, d] and activations [tokens, d], both
 // MFMA operands are "row index in the lane, 8 consecutive k in the register", i.e. plain
-// 16-byte loads.  The k-index assignment inside a 64-wide k step is permuted (each half of the
-// wave owns 32 consecutive k) so that a lane's four loads of a step are 64 contiguous bytes.
+// 16-byte pieces.  The k-index assignment inside a 64-wide k step is permuted (each half of the
+// wave owns 32 consecutive k) so that a lane's four weight loads of a step are 64 contiguous
+// bytes.
 #include "spd_device.h"
 
 using namespace spdd;
@@ -21,8 +22,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int GNT = 256;          // threads per GEMM block: 4 waves, each 32 columns of a 128-column tile
-constexpr int G_NB = 128;         // columns (weight rows) per block
 constexpr int KSTEP = 64;         // k per pipeline step (4 MFMAs of k = 16)
 
 __device__ __forceinline__ uint16_t bf16_rn(float v) {
@@ -87,83 +86,101 @@ struct PrefillGemmArgs {
     uint16_t *uhi, *ulo;         // [T_pad, N]
 };
 
-template <int NMAT>
-struct Frags {                    // one k step: 4 pieces of 8 k each
-    u32x4 a_hi[2][4], a_lo[2][4]; // two token tiles
-    u32x4 b[NMAT][4];
-};
+// Block: token tile blockIdx.x (32 * TT tokens), column tile blockIdx.y (32 * NWV columns);
+// wave w owns columns [32 w, 32 w + 32) of it, all TT token tiles.  Per k step of 64:
+//   * the activation tile (hi and lo, 32 TT rows x 64 k) is brought in ONCE per block through
+//     LDS (every wave needs all of it; fetched per wave it saturates the L2),
+//   * each lane fetches its own weight row's 64 k straight into registers,
+//   * 8 TT (x 2 for gate and up) matrix-core products per wave.
+// Both are double-buffered: the loads of step s + 1 are in flight during the products of
+// step s.  Token rows past T are computed and dropped.
+constexpr int A_ROW = KSTEP * 2 + 16;    // bytes per LDS row: 64 bf16 + 16 (rows 4 banks apart: conflict-free)
 
-template <int TT, int NMAT>
-__device__ __forceinline__ void load_step(const PrefillGemmArgs &a, Frags<NMAT> &f, int t0, int n, int k0, int lane) {
-    const size_t koff = (size_t)k0 + 32 * (lane / 32);
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const size_t row = (size_t)(t0 + 32 * tt + lane % 32) * a.K + koff;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f.a_hi[tt][j] = global_load16(a.xhi + row + 8 * j);
-            f.a_lo[tt][j] = global_load16(a.xlo + row + 8 * j);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        f.b[0][j] = stream_load16(a.W + (size_t)n * a.K + koff + 8 * j);
-        if (NMAT == 2) f.b[1][j] = stream_load16(a.W2 + (size_t)n * a.K + koff + 8 * j);
-    }
-}
-
-template <int TT, int NMAT>
-__device__ __forceinline__ void mma_step(const Frags<NMAT> &f, f32x16 (&acc)[NMAT][2]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int mt = 0; mt < NMAT; ++mt) {
-            const bf16x8 b = __builtin_bit_cast(bf16x8, f.b[mt][j]);
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a_hi[tt][j]), b, acc[mt][tt], 0, 0, 0);
-                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a_lo[tt][j]), b, acc[mt][tt], 0, 0, 0);
-            }
-        }
-}
-
-// Block: token tile blockIdx.x (32 * TT tokens), column tile blockIdx.y (128 columns); wave w
-// owns columns [32 w, 32 w + 32) of it.  Token rows past T are computed and dropped.
-template <int EPI, int TT>
-__global__ __launch_bounds__(GNT, 2) void prefill_gemm_kernel(const PrefillGemmArgs a) {
+template <int EPI, int TT, int NWV>
+__global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGemmArgs a) {
     constexpr int NMAT = EPI == PE_SWIGLU ? 2 : 1;
-    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
-    const int t0 = blockIdx.x * 32 * TT;
-    const int n = blockIdx.y * G_NB + 32 * w + lane % 32;      // this lane's weight row (load side)
-    const int nl = min(n, a.N - 1);                              // (a ragged last tile re-reads the last row)
-    f32x16 acc[NMAT][2];
+    constexpr int NTH = 64 * NWV;
+    constexpr int ROWS = 32 * TT;
+    constexpr int PIECES = ROWS * 8;                       // 16-byte pieces of one (hi or lo) tile
+    constexpr int PER_THREAD = (PIECES + NTH - 1) / NTH;   // staged per thread, per half
+    extern __shared__ __align__(16) char a_lds[];          // [2 buffers][hi, lo][ROWS][A_ROW]
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    const int t0 = blockIdx.x * ROWS;
+    const int n = blockIdx.y * (32 * NWV) + 32 * w + lane % 32;   // this lane's weight row (load side)
+    const int nl = min(n, a.N - 1);                                 // (a ragged last tile re-reads the last row)
+    f32x16 acc[NMAT][TT];
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][tt][r] = 0.f;
-    // Two steps in flight.  K is a multiple of two steps (the host checks), so the loop body has
-    // no branch at all: a load or a product under a branch makes the compiler wait for
-    // everything outstanding.  Past the end the last step is simply requested again.
-    Frags<NMAT> f0, f1;
-    const int k_last = a.K - KSTEP;
-    load_step<TT, NMAT>(a, f0, t0, nl, 0, lane);
-    for (int k0 = 0; k0 < a.K; k0 += 2 * KSTEP) {
-        // (the scheduling barriers keep the compiler from sinking a step's loads down to their
-        // first use, which would put a memory latency in front of every product)
-        load_step<TT, NMAT>(a, f1, t0, nl, k0 + KSTEP, lane);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step<TT, NMAT>(f0, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        load_step<TT, NMAT>(a, f0, t0, nl, min(k0 + 2 * KSTEP, k_last), lane);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step<TT, NMAT>(f1, acc);
-        __builtin_amdgcn_sched_barrier(0);
+
+    u32x4 stage_hi[PER_THREAD], stage_lo[PER_THREAD];      // activation pieces on their way to LDS
+    u32x4 wb[2][NMAT][4];                                  // weight pieces of two steps
+    const size_t w_row = (size_t)nl * a.K + 32 * (lane / 32);
+    auto lds_at = [&](int buf, int half, int row, int piece) -> char * {
+        return a_lds + (size_t)((buf * 2 + half) * ROWS + row) * A_ROW + piece * 16;
+    };
+#define FETCH_A(k0)                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < PER_THREAD; ++i) {                                              \
+        const int p = min(tid + NTH * i, PIECES - 1);                                                     \
+        const size_t at = (size_t)(t0 + p / 8) * a.K + (k0) + 8 * (p % 8);                                \
+        stage_hi[i] = global_load16(a.xhi + at);                                                          \
+        stage_lo[i] = global_load16(a.xlo + at);                                                          \
     }
+#define FETCH_W(slot, k0)                                                                                \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
+        wb[slot][0][j] = stream_load16(a.W + w_row + (k0) + 8 * j);                                       \
+        if (NMAT == 2) wb[slot][1][j] = stream_load16(a.W2 + w_row + (k0) + 8 * j);                       \
+    }
+#define STORE_A(buf)                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < PER_THREAD; ++i) {                                              \
+        const int p = tid + NTH * i;                                                                      \
+        if (PIECES % NTH == 0 || p < PIECES) {                                                            \
+            *(u32x4 *)lds_at(buf, 0, p / 8, p % 8) = stage_hi[i];                                         \
+            *(u32x4 *)lds_at(buf, 1, p / 8, p % 8) = stage_lo[i];                                         \
+        }                                                                                                 \
+    }
+#define PRODUCTS(buf, slot)                                                                              \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                         \
+        _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                               \
+            const bf16x8 xh = __builtin_bit_cast(bf16x8, *(const u32x4 *)lds_at(buf, 0, 32 * tt + lane % 32, 4 * (lane / 32) + j)); \
+            const bf16x8 xl = __builtin_bit_cast(bf16x8, *(const u32x4 *)lds_at(buf, 1, 32 * tt + lane % 32, 4 * (lane / 32) + j)); \
+            _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt) {                                         \
+                const bf16x8 wv = __builtin_bit_cast(bf16x8, wb[slot][mt][j]);                            \
+                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, wv, acc[mt][tt], 0, 0, 0);     \
+                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, wv, acc[mt][tt], 0, 0, 0);     \
+            }                                                                                             \
+        }
+
+    // K is a multiple of two steps (the host checks): the loop body has no branch, and the
+    // scheduling barriers keep the compiler from sinking a step's loads down to their first use.
+    const int k_last = a.K - KSTEP;
+    FETCH_A(0) FETCH_W(0, 0)
+    STORE_A(0)
+    __syncthreads();
+    for (int k0 = 0; k0 < a.K; k0 += 2 * KSTEP) {
+        FETCH_A(k0 + KSTEP) FETCH_W(1, k0 + KSTEP)
+        __builtin_amdgcn_sched_barrier(0);
+        PRODUCTS(0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        STORE_A(1)
+        __syncthreads();
+        FETCH_A(min(k0 + 2 * KSTEP, k_last)) FETCH_W(0, min(k0 + 2 * KSTEP, k_last))
+        __builtin_amdgcn_sched_barrier(0);
+        PRODUCTS(1, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        STORE_A(0)
+        __syncthreads();
+    }
+#undef FETCH_A
+#undef FETCH_W
+#undef STORE_A
+#undef PRODUCTS
 
     // C layout: lane -> column nc = tile + lane % 32; register r -> token 8 (r / 4) + 4 (lane / 32) + r % 4
-    const int nc = blockIdx.y * G_NB + 32 * w + lane % 32;
+    const int nc = blockIdx.y * (32 * NWV) + 32 * w + lane % 32;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -213,45 +230,58 @@ struct PrefillAttnArgs {
 };
 
 __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs a) {
-    extern __shared__ float lds[];
-    const int dh = a.d_head, ldk = dh + 1, lds_s = AK + 1;   // (odd row strides: no LDS bank conflicts)
-    float *Qs = lds;                       // [AQ][dh + 1]
-    float *Ks = Qs + AQ * ldk;             // [AK][dh + 1]
+    extern __shared__ __align__(16) float lds[];
+    // row strides: 16-byte aligned, and consecutive rows 4 banks apart (no conflicts for the
+    // 8 rows the 8 threads of a query read side by side)
+    const int dh = a.d_head, ldk = dh + 4, lds_s = AK + 1;
+    float *Qs = lds;                       // [AQ][dh + 4]
+    float *Ks = Qs + AQ * ldk;             // [AK][dh + 4]
     float *Vs = Ks + AK * ldk;             // [AK][dh]
     float *Ss = Vs + AK * dh;              // [AQ][AK + 1]
     const int tid = threadIdx.x;
     const int h = blockIdx.y, g = h / (a.n_heads / a.n_kv_heads);
     const int q0 = blockIdx.x * AQ;
-    const int nqd = a.n_heads * dh;
+    const int nqd = a.n_heads * dh, dh4 = dh / 4;
     const float scale = 1.0f / sqrtf((float)dh);
-    for (int e = tid; e < AQ * dh; e += ANT) {
-        const int i = e / dh, t = q0 + i;
-        Qs[i * ldk + e % dh] = t < a.T ? as_global(a.q)[(size_t)t * nqd + (size_t)h * dh + e % dh] : 0.f;
+    for (int e = tid; e < AQ * dh4; e += ANT) {
+        const int i = e / dh4, c = 4 * (e % dh4), t = q0 + i;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (t < a.T) v = global_load_float4(a.q + (size_t)t * nqd + (size_t)h * dh + c);
+        *(float4 *)(Qs + i * ldk + c) = v;
     }
     const int qi = tid / 8, sub = tid % 8;          // this thread's query, and its share of keys / dims
     const int qpos = a.p0 + q0 + qi;                // cached positions 0 .. qpos are visible
-    float m = -INFINITY, l = 0.f, acc[16];          // dims sub + 8 dd (d_head <= 128)
+    float m = -INFINITY, l = 0.f;
+    float4 acc[4];                                  // dims 4 (sub + 8 g4) .. + 3, g4 = 0 .. 3 (d_head <= 128)
 #pragma unroll
-    for (int dd = 0; dd < 16; ++dd) acc[dd] = 0.f;
+    for (int g4 = 0; g4 < 4; ++g4) acc[g4] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int last = min(a.p0 + q0 + AQ - 1, a.p0 + a.T - 1);   // last position any query of the tile sees
     const float *Kg = a.kcache + (size_t)g * a.cap_ctx * dh, *Vg = a.vcache + (size_t)g * a.cap_ctx * dh;
     for (int c0 = 0; c0 <= last; c0 += AK) {
         __syncthreads();
-        for (int e = tid; e < AK * dh; e += ANT) {
-            const int j = e / dh, d = e % dh, pos = c0 + j;
-            const bool ok = pos <= last;
-            Ks[j * ldk + d] = ok ? as_global(Kg)[(size_t)pos * dh + d] : 0.f;
-            Vs[j * dh + d] = ok ? as_global(Vg)[(size_t)pos * dh + d] : 0.f;
+        for (int e = tid; e < AK * dh4; e += ANT) {
+            const int j = e / dh4, c = 4 * (e % dh4), pos = c0 + j;
+            float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
+            if (pos <= last) {
+                kv = global_load_float4(Kg + (size_t)pos * dh + c);
+                vv = global_load_float4(Vg + (size_t)pos * dh + c);
+            }
+            *(float4 *)(Ks + j * ldk + c) = kv;
+            *(float4 *)(Vs + j * dh + c) = vv;
         }
         __syncthreads();
         // scores of query qi with keys sub + 8 jj
         float s[8], cmax = -INFINITY;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) s[jj] = 0.f;
-        for (int d = 0; d < dh; ++d) {
-            const float qv = Qs[qi * ldk + d];
+        for (int d = 0; d < dh; d += 4) {
+            const float4 qv = *(const float4 *)(Qs + qi * ldk + d);
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) s[jj] = fmaf(qv, Ks[(sub + 8 * jj) * ldk + d], s[jj]);
+            for (int jj = 0; jj < 8; ++jj) {
+                const float4 kv = *(const float4 *)(Ks + (sub + 8 * jj) * ldk + d);
+                s[jj] = fmaf(qv.x, kv.x, s[jj]); s[jj] = fmaf(qv.y, kv.y, s[jj]);
+                s[jj] = fmaf(qv.z, kv.z, s[jj]); s[jj] = fmaf(qv.w, kv.w, s[jj]);
+            }
         }
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
@@ -263,7 +293,7 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
         cmax = fmaxf(cmax, __shfl_xor(cmax, 1, WAVE));
         cmax = fmaxf(cmax, __shfl_xor(cmax, 2, WAVE));
         cmax = fmaxf(cmax, __shfl_xor(cmax, 4, WAVE));
-        const float m_new = fmaxf(m, cmax);          // finite: position c0 <= qpos whenever this chunk matters
+        const float m_new = fmaxf(m, cmax);
         float psum = 0.f;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
@@ -279,19 +309,27 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
         m = m_new;
         __syncthreads();
 #pragma unroll
-        for (int dd = 0; dd < 16; ++dd) acc[dd] *= corr;
+        for (int g4 = 0; g4 < 4; ++g4) { acc[g4].x *= corr; acc[g4].y *= corr; acc[g4].z *= corr; acc[g4].w *= corr; }
         for (int j = 0; j < AK; ++j) {
             const float p = Ss[qi * lds_s + j];
 #pragma unroll
-            for (int dd = 0; dd < 16; ++dd)
-                if (sub + 8 * dd < dh) acc[dd] = fmaf(p, Vs[j * dh + sub + 8 * dd], acc[dd]);
+            for (int g4 = 0; g4 < 4; ++g4)
+                if (4 * (sub + 8 * g4) < dh) {
+                    const float4 v = *(const float4 *)(Vs + j * dh + 4 * (sub + 8 * g4));
+                    acc[g4].x = fmaf(p, v.x, acc[g4].x); acc[g4].y = fmaf(p, v.y, acc[g4].y);
+                    acc[g4].z = fmaf(p, v.z, acc[g4].z); acc[g4].w = fmaf(p, v.w, acc[g4].w);
+                }
         }
     }
     const int t = q0 + qi;
     if (t < a.T) {
 #pragma unroll
-        for (int dd = 0; dd < 16; ++dd)
-            if (sub + 8 * dd < dh) split_store(a.ohi, a.olo, (size_t)t * nqd + (size_t)h * dh + sub + 8 * dd, acc[dd] / l);
+        for (int g4 = 0; g4 < 4; ++g4)
+            if (4 * (sub + 8 * g4) < dh) {
+                const size_t at = (size_t)t * nqd + (size_t)h * dh + 4 * (sub + 8 * g4);
+                split_store(a.ohi, a.olo, at, acc[g4].x / l); split_store(a.ohi, a.olo, at + 1, acc[g4].y / l);
+                split_store(a.ohi, a.olo, at + 2, acc[g4].z / l); split_store(a.ohi, a.olo, at + 3, acc[g4].w / l);
+            }
     }
 }
 
@@ -299,10 +337,31 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
 
 namespace spdk {
 
-size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 1) + AK * (d_head + 1) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
+size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (d_head + 4) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
+
+// Launch with the widest column tile that still gives every compute unit a block.
+template <int EPI, int TT>
+static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
+    const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
+    const size_t lds = (size_t)2 * 2 * (32 * TT) * A_ROW;
+    auto blocks = [&](int nwv) { return t_tiles * ((g.N + 32 * nwv - 1) / (32 * nwv)); };
+    if (blocks(4) >= num_cu)
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 4>), dim3(t_tiles, (g.N + 127) / 128), dim3(256), lds, s, g);
+    else if (blocks(2) >= num_cu)
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 2>), dim3(t_tiles, (g.N + 63) / 64), dim3(128), lds, s, g);
+    else
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 1>), dim3(t_tiles, (g.N + 31) / 32), dim3(64), lds, s, g);
+}
 
 hipError_t prefill_init() {
-    return hipFuncSetAttribute((const void *)prefill_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
+    hipError_t e = hipFuncSetAttribute((const void *)prefill_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
+    const int lds4 = 2 * 2 * 128 * A_ROW, lds2 = 2 * 2 * 64 * A_ROW;
+#define SPD_LDS(K, B) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, B)
+    SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 1>), lds4);
+    SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 1>), lds4);
+    SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), lds2);
+#undef SPD_LDS
+    return e;
 }
 
 // One chunk of T prefix tokens at positions p0 .. p0 + T - 1 through the whole stack.  On
@@ -310,7 +369,6 @@ hipError_t prefill_init() {
 // extended; the caller finishes the last token (final norm + LM head).
 hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
     const int T = c.T, d = c.d_model, dh = d / c.n_heads, nq = c.n_heads * dh, nkv = c.n_kv_heads * dh;
-    const int tt2 = (T + 63) / 64, tt1 = (T + 31) / 32;
     hipLaunchKernelGGL(embed_rows_kernel, dim3(T), dim3(256), 0, s, (const uint16_t *)c.embed, c.prefix, c.p0, T, d, c.h);
     hipLaunchKernelGGL(rope_table_kernel, dim3((T * (dh / 2) + 255) / 256), dim3(256), 0, s, c.inv_freq, c.p0, T, dh / 2, c.rope);
     float *h = c.h, *h1 = c.h1;
@@ -322,24 +380,24 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         g.q = c.q; g.kcache = (float *)(c.kv + (size_t)(2 * l) * c.kv_layer_bytes);
         g.vcache = (float *)(c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes);
         g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
-        hipLaunchKernelGGL((prefill_gemm_kernel<PE_QKV, 2>), dim3(tt2, (g.N + G_NB - 1) / G_NB), dim3(GNT), 0, s, g);
+        launch_gemm<PE_QKV, 4>(s, g, c.num_cu);
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx};
         hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
 
         PrefillGemmArgs o{};
         o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1;
-        hipLaunchKernelGGL((prefill_gemm_kernel<PE_RESID, 2>), dim3(tt2, (o.N + G_NB - 1) / G_NB), dim3(GNT), 0, s, o);
+        launch_gemm<PE_RESID, 4>(s, o, c.num_cu);
 
         hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h1, (const uint16_t *)w.ffn_norm, c.eps, d, c.xhi, c.xlo);
         PrefillGemmArgs f{};
         f.xhi = c.xhi; f.xlo = c.xlo; f.W = (const uint16_t *)w.w_gate; f.W2 = (const uint16_t *)w.w_up; f.T = T; f.N = c.d_ffn; f.K = d;
         f.uhi = c.uhi; f.ulo = c.ulo;
-        hipLaunchKernelGGL((prefill_gemm_kernel<PE_SWIGLU, 1>), dim3(tt1, (f.N + G_NB - 1) / G_NB), dim3(GNT), 0, s, f);
+        launch_gemm<PE_SWIGLU, 2>(s, f, c.num_cu);
 
         PrefillGemmArgs dn{};
         dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h;
-        hipLaunchKernelGGL((prefill_gemm_kernel<PE_RESID, 2>), dim3(tt2, (dn.N + G_NB - 1) / G_NB), dim3(GNT), 0, s, dn);
+        launch_gemm<PE_RESID, 4>(s, dn, c.num_cu);
     }
     return hipGetLastError();
 }
