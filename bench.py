@@ -248,6 +248,23 @@ def main():
     ntok, nlp = sess.spd_nucleus_step(sc, 0.5)
     assert 0 <= ntok < shape.vocab and np.isfinite(nlp)
 
+    # the prefix pass alone (the first-timestep forward over M), dense on the matrix cores where
+    # the model allows it: tokens/s, and model flops (2 x parameters of the layers x tokens; the
+    # matrix cores do twice that, each activation being fed as a hi + lo bf16 pair)
+    sess.spd_prefill(prefix)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    sess.spd_prefill(prefix)
+    torch.cuda.synchronize()
+    prefill_ms = (time.perf_counter() - t2) * 1e3
+    layer_params = shape.streamed_params() - shape.vocab * shape.d_model
+    prefill = {"tokens": m, "ms": prefill_ms, "tokens_per_s": m / prefill_ms * 1e3,
+               "dense": bool(sess.spd_get_dense_prefill()),
+               "model_tflops": 2.0 * layer_params * m / (prefill_ms * 1e-3) / 1e12}
+    if prefill["dense"]:
+        prefill["mfma_tflops"] = 2.0 * prefill["model_tflops"]
+        prefill["mfma_frac_of_bf16_peak"] = prefill["mfma_tflops"] / 2500.0
+
     # end-to-end generation as the paper times it: prefix pass + 10 tokens
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -273,6 +290,7 @@ def main():
                                  "kind": "k nucleus-sampling passes (top-p 0.9), one token per pass per step",
                                  "greedy_ms_per_pass_step": greedy_ms,
                                  "speedup_of_spd_over_k_greedy": k * greedy_ms / ms_per_step},
+        "prefill": prefill,
         "generate_10_tokens_ms": e2e_ms,
         "setup_s": t_setup,
     }
