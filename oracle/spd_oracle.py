@@ -382,3 +382,40 @@ def nucleus_generate(lm, prefix, top_p: float, tau: float, us, keep_logits: bool
         total += rec.logp
         recs.append(rec)
     return toks, total, recs
+
+
+# ================================================================ resets and the splice
+# Section 5.1 ("Superposed Decoding Resets"): every s timesteps one of the k drafts is
+# sampled and draft generation restarts from the text extended by it.  Section 4.5: a
+# nucleus-sampled generation can serve as the prefix at any timestep ("splice").  Both are
+# "commit one draft, restart from the longer prefix".  Reading: the draft is sampled with its
+# superposition weight gamma_i = p_i / sum_j p_j (Eq. 2) -- the paper only says "sample" --
+# by inverse CDF over the drafts in rank order with a draw u in [0, 1) supplied by the caller.
+def choose_draft(logscores, u: float) -> int:
+    gamma = superposition_weights(logscores).astype(np.float64)
+    cum = np.cumsum(gamma)
+    i = int(np.searchsorted(cum, u * cum[-1], side="right"))
+    return min(i, len(gamma) - 1)
+
+
+def commit_draft(state: SpdState, u: float):
+    """-> (index of the sampled draft, the new prefix = old prefix + that draft)."""
+    i = choose_draft(state.logscores, u)
+    return i, list(state.prefix) + list(state.drafts[i])
+
+
+def generate_with_resets(lm, tables, prefix, cfg: DecodeCfg, n_tokens: int, s: int, us, dtype=np.float32):
+    """n_tokens tokens per draft in segments of s timesteps; after each full segment one draft
+    is committed (draw us[j] for the j-th reset) and generation restarts.  Returns (committed
+    text beyond the original prefix, final SpdState of the last segment, chosen indices)."""
+    text, chosen, left, j = list(map(int, prefix)), [], n_tokens, 0
+    state = None
+    while left > 0:
+        seg = min(s, left)
+        state, _ = generate(lm, tables, text, cfg, seg, dtype, keep_logits=False)
+        left -= seg
+        if left > 0:
+            i, text = commit_draft(state, float(us[j]))
+            chosen.append(i)
+            j += 1
+    return text[len(prefix):], state, chosen
