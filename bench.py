@@ -138,7 +138,7 @@ def main():
     k, alpha, tau, delta = args.k, 0.54, 1.0, 0.1
     lambdas = synth.PAPER_LAMBDAS
     K, W = args.steps, args.warmup
-    max_ctx = m + W + K + 2
+    max_ctx = m + max(W + K, 32) + 2
 
     t_setup = time.time()
     if shape.dtype == "bf16":
@@ -234,7 +234,7 @@ def main():
     # the paper's own comparison (Section 4.3): k independent passes of nucleus sampling, here
     # top-p 0.9 (BASELINE config 3), each step = the same forward + the sampler; seeded draws
     sc = pkg.SpdSampleCfg(0.9, tau)
-    us = np.random.default_rng(0).random(W + K + 1).astype(np.float32)
+    us = np.random.default_rng(0).random(max(W + K + 1, 8)).astype(np.float32)
     sess.spd_prefill(prefix)
     sess.spd_nucleus_step(sc, float(us[0]), fetch=False)
     for i in range(W):
@@ -271,6 +271,32 @@ def main():
     drafts, scores = sess.spd_generate(prefix, dc, 10)
     e2e_ms = (time.perf_counter() - t2) * 1e3
 
+    # resets (Section 5.1): one of the k drafts is committed every s = 8 timesteps and its 8
+    # tokens are passed again as ordinary prefix tokens; splice (Section 4.5): a one-draft nucleus
+    # opening is committed, which passes only its newest token again
+    def timed(f):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        r = f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3, r
+    s_reset = 8
+    sess.spd_prefill(prefix)
+    for _ in range(s_reset):
+        sess.spd_step(dc, fetch=False)
+    sess.spd_commit(0.5)                                    # untimed: first use of this chunk size
+    for _ in range(s_reset):
+        sess.spd_step(dc, fetch=False)
+    commit_ms, _ = timed(lambda: sess.spd_commit(0.5))
+    seg_ms, _ = timed(lambda: [sess.spd_step(dc, fetch=False) for _ in range(s_reset)])
+    sess.spd_prefill(prefix)
+    for i in range(4):
+        sess.spd_nucleus_step(sc, float(us[i]), fetch=False)
+    splice_ms, (ci, ctoks) = timed(lambda: sess.spd_commit(0.5))
+    assert ci == 0 and len(ctoks) == 4
+    resets = {"s": s_reset, "commit_ms": commit_ms, "segment_ms": seg_ms,
+              "overhead_frac": commit_ms / (commit_ms + seg_ms), "splice_commit_ms": splice_ms}
+
     out = {
         "metric": "draft-tokens/sec at k=3 (7B-shape bf16, batch 1); % of peak HBM GB/s",
         "value": k * K / wall, "unit": "draft-tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -291,6 +317,7 @@ def main():
                                  "greedy_ms_per_pass_step": greedy_ms,
                                  "speedup_of_spd_over_k_greedy": k * greedy_ms / ms_per_step},
         "prefill": prefill,
+        "resets": resets,
         "generate_10_tokens_ms": e2e_ms,
         "setup_s": t_setup,
     }

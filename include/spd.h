@@ -176,6 +176,18 @@ int spd_get_step_info(spd_ctx *ctx, int32_t *out_top_ids, float *out_top_logp,
  * not touch the KV cache or the position.  Does not synchronise. */
 int spd_expand_prune(spd_ctx *ctx, const spd_decode_cfg *dc, const float *dev_logits, int32_t first);
 
+/* Commit one draft and restart (Section 5.1, "Superposed Decoding Resets": every s timesteps
+ * one of the k drafts is sampled and draft generation restarts; Section 4.5: a nucleus-sampled
+ * generation serves as the prefix of a Superposed Decoding run, "spliced in at any timestep").
+ * Draft i is sampled with its superposition weight gamma_i (Eq. 2) by inverse CDF over the
+ * drafts in rank order with the caller's draw u in [0, 1); its tokens since the last
+ * spd_prefill / spd_commit are appended to the text, the cache positions they occupy are
+ * recomputed from the tokens themselves (with one draft, k = 1, only the newest token's), and
+ * the context is left as after spd_prefill of the extended text: the next spd_step (any k) or
+ * spd_nucleus_step starts a generation from it.  Outputs are HOST, each may be NULL: the
+ * sampled draft's index, its tokens (cap entries available) and their number.  Synchronises. */
+int spd_commit(spd_ctx *ctx, float u, int32_t *out_chosen, int32_t *out_tokens, int32_t cap, int32_t *out_n);
+
 /* ---- the comparison decoder: one pass of nucleus (top-p) sampling ----
  * Section 4.3 times Superposed Decoding against k independent passes of nucleus sampling;
  * Section 2 describes the sampler: the next-token distribution is cut to the smallest set of

@@ -72,6 +72,7 @@ def lib():
             "spd_step": [vp, C.POINTER(SpdDecodeCfg), vp, vp, vp],
             "spd_nucleus_step": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, vp],
             "spd_get_nucleus_info": [vp, vp, vp, vp],
+            "spd_commit": [vp, C.c_float, vp, vp, i32, vp],
             "spd_set_dense_prefill": [vp, i32],
             "spd_get_dense_prefill": [vp, C.POINTER(i32)],
             "spd_nucleus_sample": [vp, C.POINTER(SpdSampleCfg), C.c_float, vp, i32],
@@ -244,6 +245,14 @@ class Session:
         tok, par, sc = np.zeros(dc.k, np.int32), np.zeros(dc.k, np.int32), np.zeros(dc.k, np.float32)
         self._chk(self.L.spd_step(self.ctx, C.byref(dc), _np_ptr(tok), _np_ptr(par), _np_ptr(sc)), "spd_step")
         return tok, par, sc
+
+    def spd_commit(self, u: float):
+        """-> (index of the sampled draft, its tokens since the last prefill / commit)."""
+        cap = self.cfg.max_ctx
+        chosen, n = C.c_int32(0), C.c_int32(0)
+        toks = np.zeros(cap, np.int32)
+        self._chk(self.L.spd_commit(self.ctx, float(u), C.byref(chosen), _np_ptr(toks), cap, C.byref(n)), "spd_commit")
+        return chosen.value, toks[:n.value].copy()
 
     def spd_set_dense_prefill(self, enable: bool):
         self._chk(self.L.spd_set_dense_prefill(self.ctx, int(enable)), "spd_set_dense_prefill")

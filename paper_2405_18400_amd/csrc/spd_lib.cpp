@@ -119,6 +119,7 @@ struct spd_ctx {
     NgramDev ng;
     bool have_ng;
     int state, pos, n_gen, k;
+    std::vector<int32_t> text;   // committed tokens: the prefix, extended by spd_commit
     char *pinned;
     size_t pinned_bytes;
     bool use_graph, timing, use_fused, use_dense;
@@ -451,30 +452,28 @@ int spd_load_ngrams(spd_ctx *c, const spd_ngram_host_tables *t, void *dev_buf, s
     return SPD_OK;
 }
 
-int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
-    if (!c) return SPD_EINVAL;
-    if (!prefix) return fail(c, SPD_EINVAL, "prefix is null");
-    if (m < 1) return fail(c, SPD_EINVAL, "prefix must hold at least one token");
-    if (m >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "prefix does not fit max_ctx");
-    for (int i = 0; i < m; ++i)
-        if (prefix[i] < 0 || prefix[i] >= c->cfg.vocab) return fail(c, SPD_EINVAL, "prefix token id outside [0, vocab)");
+// The prefix pass over tokens p0 .. m-1 of c->text (cache positions 0 .. p0-1 are in place):
+// stages the draft-state header and the token ids, fills the cache, keeps the logits of token
+// m-1.  Dense (whole chunks on the matrix cores) where the model allows it.
+static int run_prefix_pass(spd_ctx *c, int p0, int m) {
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));   // the pinned staging area may still be in flight
-    // staged image: DevState header (pos = 0, prefix tail) followed by the prefix ids
     DevState *hs = (DevState *)c->pinned;
     std::memset(hs, 0, sizeof(DevState));
+    hs->pos = p0;
     for (int q = 0; q < SPD_TAIL; ++q) {
         const int src = m - SPD_TAIL + q;
-        hs->prefix_tail[q] = src >= 0 ? prefix[src] : NG_PAD;
+        hs->prefix_tail[q] = src >= 0 ? c->text[src] : NG_PAD;
     }
     int32_t *hp = (int32_t *)(c->pinned + up(sizeof(DevState)));
-    std::memcpy(hp, prefix, (size_t)m * 4);
+    std::memcpy(hp, c->text.data() + p0, (size_t)(m - p0) * 4);
     HIPCHK(c, hipMemcpyAsync(c->st(), hs, sizeof(DevState), hipMemcpyHostToDevice, c->stream));
-    HIPCHK(c, hipMemcpyAsync(c->ws + c->L.prefix, hp, (size_t)m * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->ws + c->L.prefix + (size_t)p0 * 4, hp, (size_t)(m - p0) * 4, hipMemcpyHostToDevice, c->stream));
     c->state = ST_CREATED;
-    c->pos = 0; c->n_gen = 0; c->k = 0;
+    c->pos = p0; c->n_gen = 0; c->k = 0;
+    const int n = m - p0;
 
-    if (c->use_dense && m >= DENSE_PREFILL_MIN) {
+    if (c->use_dense && n >= DENSE_PREFILL_MIN) {
         // whole chunks of prefix tokens on the matrix cores; the last token's final norm and
         // LM head go through the matrix-vector kernel
         const spd_model_cfg &mc = c->cfg;
@@ -488,8 +487,8 @@ int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
         pc.uhi = c->at<uint16_t>(c->L.pf_uhi); pc.ulo = c->at<uint16_t>(c->L.pf_ulo);
         pc.rope = c->at<float2>(c->L.pf_rope);
         int last_T = 0;
-        for (int p0 = 0; p0 < m; p0 += PREFILL_CHUNK) {
-            pc.p0 = p0; pc.T = last_T = (m - p0 < PREFILL_CHUNK) ? m - p0 : PREFILL_CHUNK;
+        for (int at = p0; at < m; at += PREFILL_CHUNK) {
+            pc.p0 = at; pc.T = last_T = (m - at < PREFILL_CHUNK) ? m - at : PREFILL_CHUNK;
             HIPCHK(c, spdk::prefill_chunk(c->stream, pc));
         }
         GemvArgs g{};
@@ -506,20 +505,31 @@ int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
         if (e == hipSuccess) e = spdk::advance(c->stream, c->st());
         return e;
     };
-    if (graphs_usable(c) && m > 2) {
+    if (graphs_usable(c) && n > 2) {
         if (!c->prefill_exec) {
             const int rc = capture(c, &c->prefill_exec, one_token);
             if (rc != SPD_OK) return rc;
         }
-        for (int i = 0; i < m - 1; ++i) HIPCHK(c, hipGraphLaunch(c->prefill_exec, c->stream));
+        for (int i = 0; i < n - 1; ++i) HIPCHK(c, hipGraphLaunch(c->prefill_exec, c->stream));
     } else {
-        for (int i = 0; i < m - 1; ++i) HIPCHK(c, one_token());
+        for (int i = 0; i < n - 1; ++i) HIPCHK(c, one_token());
     }
     HIPCHK(c, enqueue_forward(c, 0, 1, true));   // last prefix position: keep its logits
     HIPCHK(c, spdk::advance(c->stream, c->st()));
     c->pos = m;
     c->state = ST_PREFILLED;
     return SPD_OK;
+}
+
+int spd_prefill(spd_ctx *c, const int32_t *prefix, int32_t m) {
+    if (!c) return SPD_EINVAL;
+    if (!prefix) return fail(c, SPD_EINVAL, "prefix is null");
+    if (m < 1) return fail(c, SPD_EINVAL, "prefix must hold at least one token");
+    if (m >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "prefix does not fit max_ctx");
+    for (int i = 0; i < m; ++i)
+        if (prefix[i] < 0 || prefix[i] >= c->cfg.vocab) return fail(c, SPD_EINVAL, "prefix token id outside [0, vocab)");
+    c->text.assign(prefix, prefix + m);
+    return run_prefix_pass(c, 0, m);
 }
 
 static int copy_step_outputs(spd_ctx *c, int k, int32_t *out_tok, int32_t *out_par, float *out_sc) {
@@ -570,6 +580,52 @@ int spd_step(spd_ctx *c, const spd_decode_cfg *dc, int32_t *out_tok, int32_t *ou
     c->pos += 1;
     c->n_gen += 1;
     return copy_step_outputs(c, dc->k, out_tok, out_par, out_sc);
+}
+
+int spd_commit(spd_ctx *c, float u, int32_t *out_chosen, int32_t *out_tokens, int32_t cap, int32_t *out_n) {
+    if (!c) return SPD_EINVAL;
+    if (!(u >= 0.f && u < 1.f)) return fail(c, SPD_EINVAL, "the draw u must lie in [0, 1)");
+    if (c->state != ST_STEPPING) return fail(c, SPD_ESTATE, "no drafts to commit: run spd_step or spd_nucleus_step first");
+    const int k = c->k, n = c->n_gen, base = (int)c->text.size();
+    if (base + n >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "committed text does not fit max_ctx");
+    if (out_tokens && cap < n) return fail(c, SPD_EINVAL, "token buffer too small");
+    const size_t hist_bytes = (size_t)n * SPD_K_MAX * 4;
+    DevState *hs = (DevState *)c->pinned;
+    int32_t *ht = (int32_t *)(c->pinned + up(sizeof(DevState)));
+    int32_t *hp = ht + (size_t)c->cfg.max_ctx * SPD_K_MAX;
+    HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(ht, c->ws + c->L.hist_tok, hist_bytes, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(hp, c->ws + c->L.hist_par, hist_bytes, hipMemcpyDeviceToHost, c->stream));
+    if (c->timing) HIPCHK(c, drain_timing(c));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    // sample draft i with its superposition weight (Eq. 2): inverse CDF over the rank order
+    double total = 0.0;
+    for (int i = 0; i < k; ++i) total += (double)hs->gamma[i];
+    int chosen = k - 1;
+    double cum = 0.0;
+    for (int i = 0; i < k; ++i) {
+        cum += (double)hs->gamma[i];
+        if (cum > (double)u * total) { chosen = i; break; }
+    }
+    std::vector<int32_t> toks((size_t)n);
+    int slot = chosen;
+    for (int t = n - 1; t >= 0; --t) {   // walk the parent indices back from the last timestep
+        toks[(size_t)t] = ht[(size_t)t * SPD_K_MAX + slot];
+        const int par = hp[(size_t)t * SPD_K_MAX + slot];
+        if (t > 0 && (par < 0 || par >= k)) return fail(c, SPD_EHIP, "corrupt parent index in the device history");
+        if (t > 0) slot = par;
+    }
+    for (int t = 0; t < n; ++t)
+        if (toks[(size_t)t] < 0 || toks[(size_t)t] >= c->cfg.vocab) return fail(c, SPD_EHIP, "corrupt token in the device history");
+    if (out_chosen) *out_chosen = chosen;
+    if (out_n) *out_n = n;
+    if (out_tokens) std::memcpy(out_tokens, toks.data(), (size_t)n * 4);
+    c->text.insert(c->text.end(), toks.begin(), toks.end());
+    // One draft (a greedy or nucleus pass): the cache already holds exactly this text except for
+    // its newest token.  k > 1: positions base .. hold keys/values of superposed inputs; redo them.
+    const int p0 = (k == 1) ? base + n - 1 : base;
+    return run_prefix_pass(c, p0, base + n);
 }
 
 static const char *check_sample(const spd_sample_cfg *sc, float u);

@@ -217,6 +217,113 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
         }
 }
 
+// ------------------------------------------------------------------ few tokens: split-k GEMM
+// With at most a few dozen tokens the product is bound by streaming the weights, and the tiling
+// above leaves most of the chip idle (few blocks, one k sweep each).  Here a block owns 32
+// weight rows and one 32-token tile, and its NWV waves split the k range between them: wave w
+// takes the 64-wide k steps w, w + NWV, ...  No operand is shared between the waves, so both
+// operands go from global memory straight into registers, double-buffered; the weights are read
+// once from HBM, the (small) activations come out of the L2.  The waves' partial accumulators
+// are summed through LDS in wave order (a fixed order: results do not vary from run to run),
+// and the epilogue runs on the sums: wave w finishes accumulator registers w, w + NWV, ...
+template <int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillGemmArgs a) {
+    constexpr int NMAT = EPI == PE_SWIGLU ? 2 : 1;
+    extern __shared__ __align__(16) char a_lds[];          // float [NWV][NMAT][16][64]
+    float *red = (float *)a_lds;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    const int t0 = blockIdx.y * 32;
+    const int nl = min((int)blockIdx.x * 32 + lane % 32, a.N - 1);   // (a ragged last tile re-reads the last row)
+    const int S = a.K / KSTEP;
+    const int n_w = w < S ? (S - w + NWV - 1) / NWV : 0;             // k steps of this wave
+    f32x16 acc[NMAT];
+#pragma unroll
+    for (int mt = 0; mt < NMAT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+
+    u32x4 wb[2][NMAT][4], xh[2][4], xl[2][4];
+    const size_t w_row = (size_t)nl * a.K + 32 * (lane / 32);
+    const size_t x_row = (size_t)(t0 + lane % 32) * a.K + 32 * (lane / 32);   // rows past T exist (padded arena)
+#define FETCH(slot, i)                                                                                   \
+    {                                                                                                     \
+        const int k0 = KSTEP * min(w + NWV * (i), S - 1);                                                 \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
+            wb[slot][0][j] = stream_load16(a.W + w_row + k0 + 8 * j);                                     \
+            if (NMAT == 2) wb[slot][1][j] = stream_load16(a.W2 + w_row + k0 + 8 * j);                     \
+            xh[slot][j] = global_load16(a.xhi + x_row + k0 + 8 * j);                                      \
+            xl[slot][j] = global_load16(a.xlo + x_row + k0 + 8 * j);                                      \
+        }                                                                                                 \
+    }
+#define PRODUCTS(slot)                                                                                   \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                         \
+        _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt) {                                             \
+            const bf16x8 wv = __builtin_bit_cast(bf16x8, wb[slot][mt][j]);                                \
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xh[slot][j]), wv, acc[mt], 0, 0, 0); \
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xl[slot][j]), wv, acc[mt], 0, 0, 0); \
+        }
+    // Loads are unconditional (clamped to the last step); only the products of a step past the
+    // wave's share are skipped, on a wave-uniform condition.
+    FETCH(0, 0)
+    for (int i = 0; i < n_w; i += 2) {
+        FETCH(1, i + 1)
+        __builtin_amdgcn_sched_barrier(0);
+        PRODUCTS(0)
+        __builtin_amdgcn_sched_barrier(0);
+        FETCH(0, i + 2)
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 1 < n_w) { PRODUCTS(1) }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef FETCH
+#undef PRODUCTS
+
+#pragma unroll
+    for (int mt = 0; mt < NMAT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[((w * NMAT + mt) * 16 + r) * WAVE + lane] = acc[mt][r];
+    __syncthreads();
+
+    // C layout: lane -> column nc = tile + lane % 32; register r -> token 8 (r / 4) + 4 (lane / 32) + r % 4
+    const int nc = blockIdx.x * 32 + lane % 32;
+    for (int r = w; r < 16; r += NWV) {
+        float sum[NMAT];
+#pragma unroll
+        for (int mt = 0; mt < NMAT; ++mt) {
+            sum[mt] = 0.f;
+            for (int ww = 0; ww < NWV; ++ww) sum[mt] += red[((ww * NMAT + mt) * 16 + r) * WAVE + lane];
+        }
+        const int t = t0 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        const float v = sum[0];
+        if (EPI == PE_QKV) {
+            const float other = dpp_move<0xB1, 0xF>(v, 0.f);   // rotary partner: the neighbouring column
+            if (t < a.T && nc < a.N) {
+                if (nc < a.n_q_rows + a.n_kv_rows) {
+                    const size_t ri = 2 * ((size_t)t * (a.d_head / 2) + (nc % a.d_head) / 2);
+                    const float cs_x = as_global((const float *)a.rope)[ri], cs_y = as_global((const float *)a.rope)[ri + 1];
+                    const float rot = (nc & 1) ? __fadd_rn(__fmul_rn(other, cs_y), __fmul_rn(v, cs_x))
+                                               : __fsub_rn(__fmul_rn(v, cs_x), __fmul_rn(other, cs_y));
+                    if (nc < a.n_q_rows) as_global(a.q)[(size_t)t * a.n_q_rows + nc] = rot;
+                    else {
+                        const int rr = nc - a.n_q_rows;
+                        as_global(a.kcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = rot;
+                    }
+                } else {
+                    const int rr = nc - a.n_q_rows - a.n_kv_rows;
+                    as_global(a.vcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = v;
+                }
+            }
+        } else if (t < a.T && nc < a.N) {
+            if (EPI == PE_RESID) {
+                as_global(a.out)[(size_t)t * a.N + nc] = as_global(a.resid)[(size_t)t * a.N + nc] + v;
+            } else {   // PE_SWIGLU: gate in sum[0], up in sum[1]
+                const float up = sum[NMAT - 1];
+                split_store(a.uhi, a.ulo, (size_t)t * a.N + nc, v / (1.0f + expf(-v)) * up);
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ causal attention over the chunk
 // One block: one query head, AQ queries of the chunk; keys / values streamed through LDS in
 // chunks of AK cached positions (fp32 cache), online softmax.  Output as the (hi, lo) pair.
@@ -340,8 +447,16 @@ namespace spdk {
 size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (d_head + 4) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
 
 // Launch with the widest column tile that still gives every compute unit a block.
+constexpr int SKINNY_WAVES = 8;
+constexpr int SKINNY_MAX_T = 64;      // up to here the split-k kernel is the faster one
+
 template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
+    if (g.T <= SKINNY_MAX_T) {
+        const size_t red = (size_t)SKINNY_WAVES * (EPI == PE_SWIGLU ? 2 : 1) * 16 * 64 * sizeof(float);
+        hipLaunchKernelGGL((prefill_skinny_kernel<EPI, SKINNY_WAVES>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(64 * SKINNY_WAVES), red, s, g);
+        return;
+    }
     const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
     const size_t lds = (size_t)2 * 2 * (32 * TT) * A_ROW;
     auto blocks = [&](int nwv) { return t_tiles * ((g.N + 32 * nwv - 1) / (32 * nwv)); };
@@ -360,6 +475,9 @@ hipError_t prefill_init() {
     SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 1>), lds4);
     SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 1>), lds4);
     SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), lds2);
+    SPD_LDS((prefill_skinny_kernel<PE_QKV, SKINNY_WAVES>), SKINNY_WAVES * 16 * 64 * 4);
+    SPD_LDS((prefill_skinny_kernel<PE_RESID, SKINNY_WAVES>), SKINNY_WAVES * 16 * 64 * 4);
+    SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, SKINNY_WAVES>), SKINNY_WAVES * 2 * 16 * 64 * 4);
 #undef SPD_LDS
     return e;
 }

@@ -79,12 +79,14 @@ def compare_step(sess, rec, dc, rtol, first, check_logits=True):
     return stats
 
 
-def teacher_forced(sess, lm, tables_np, lambdas, prefix, cfg, n_tokens, rtol, dc):
+def teacher_forced(sess, lm, tables_np, lambdas, prefix, cfg, n_tokens, rtol, dc, prefilled=False):
     """Run the oracle free; before every GPU step load the oracle's drafts and scores into the
-    GPU (its KV cache stays its own), so each step is compared on its own."""
+    GPU (its KV cache stays its own), so each step is compared on its own.  With `prefilled`
+    the session already stands at the end of `prefix` (after a commit) and is not prefilled."""
     otabs = O.NgramTables(tables_np) if tables_np is not None else None
     state, recs = O.generate(lm, otabs, prefix, cfg, n_tokens)
-    sess.spd_prefill(prefix)
+    if not prefilled:
+        sess.spd_prefill(prefix)
     all_stats = []
     for t, rec in enumerate(recs):
         if t > 0:
