@@ -84,8 +84,9 @@ Layout make_layout(const spd_model_cfg &c) {
     L.pi = take((size_t)L.n_part * SPD_K_MAX * 4);
     L.pm = take((size_t)L.n_part * 4);
     L.ps = take((size_t)L.n_part * 4);
-    // dense prefix pass (matrix cores): bf16 weights, d_head <= 128, widths the tiles divide
-    L.dense = c.dtype == SPD_DTYPE_BF16 && dh <= 128 && c.d_model % 128 == 0 && c.d_ffn % 128 == 0 &&
+    // dense prefix pass (matrix cores): bf16 weights, d_head <= 128, widths the tiles divide,
+    // d_model within what its norm kernel keeps in registers
+    L.dense = c.dtype == SPD_DTYPE_BF16 && dh <= 128 && c.d_model % 128 == 0 && c.d_model <= 8192 && c.d_ffn % 128 == 0 &&
               (c.n_heads * dh) % 128 == 0 && c.n_layers > 0;
     if (L.dense) {
         const size_t nq = (size_t)c.n_heads * dh, wide = nq > (size_t)c.d_model ? nq : (size_t)c.d_model;
@@ -857,7 +858,7 @@ int spd_set_fused(spd_ctx *c, int32_t enable) {
 
 int spd_set_dense_prefill(spd_ctx *c, int32_t enable) {
     if (!c) return SPD_EINVAL;
-    if (enable && !c->L.dense) return fail(c, SPD_EINVAL, "no dense prefix pass for this model (bf16 weights, d_head <= 128, widths divisible by 128)");
+    if (enable && !c->L.dense) return fail(c, SPD_EINVAL, "no dense prefix pass for this model (bf16 weights, d_head <= 128, widths divisible by 128, d_model <= 8192)");
     c->use_dense = enable != 0;
     return SPD_OK;
 }

@@ -37,6 +37,17 @@ __device__ __forceinline__ void split_store(uint16_t *hi, uint16_t *lo, size_t a
     as_global(lo)[at] = bf16_rn(x - bf16_f(h));
 }
 
+// Where element (token t, feature k) of a [T, K] activation operand lives.  Row-major for the
+// LDS-tiled GEMM; for the split-k GEMM of short chunks the operand is stored the way the matrix
+// cores take it, so that every load of a wave is 1 KB contiguous: 32-token tile, then 64-wide
+// k step, then the step's four 16-wide products j, then the lane (token t % 32 in lanes
+// 0..31 for the step's first 32 k, in lanes 32..63 for the other 32), then 8 consecutive k.
+__device__ __forceinline__ size_t act_at(bool tiled, int t, int k, int K) {
+    if (!tiled) return (size_t)t * K + k;
+    const int kk = k % KSTEP;
+    return ((((size_t)(t / 32) * (K / KSTEP) + k / KSTEP) * 4 + (kk % 32) / 8) * WAVE + (t % 32) + 32 * (kk / 32)) * 8 + k % 8;
+}
+
 // ------------------------------------------------------------------ token rows, norms, rotary table
 __global__ __launch_bounds__(256) void embed_rows_kernel(const uint16_t *embed, const int32_t *prefix, int p0, int T,
                                                          int d, float *H) {
@@ -45,18 +56,49 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const uint16_t *embed, 
     for (int c = threadIdx.x; c < d; c += 256) as_global(H)[(size_t)t * d + c] = bf16_f(as_global(embed)[(size_t)tok * d + c]);
 }
 
-// xn = x * rsqrt(mean x^2 + eps) * gain, written as the (hi, lo) pair
+// xn = x * rsqrt(mean x^2 + eps) * gain, written as the (hi, lo) pair.  One block per token; a
+// thread keeps its runs of 8 consecutive features in registers (one read of the row) and
+// writes each run as one 16-byte store per half (8 consecutive k are contiguous in both layouts).
+constexpr int NORM_RUNS = 4;      // runs per thread: d_model <= 256 * 8 * NORM_RUNS
+
 __global__ __launch_bounds__(256) void rmsnorm_split_kernel(const float *H, const uint16_t *gain, float eps, int d,
-                                                            uint16_t *hi, uint16_t *lo) {
+                                                            uint16_t *hi, uint16_t *lo, bool tiled) {
     __shared__ float red[256 / WAVE];
     const int t = blockIdx.x;
     const float *x = H + (size_t)t * d;
+    float v[NORM_RUNS][8];
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += 256) { const float v = as_global(x)[c]; ss += v * v; }
+#pragma unroll
+    for (int i = 0; i < NORM_RUNS; ++i) {
+        const int c = 8 * (threadIdx.x + 256 * i);
+        if (c < d) {
+            const float4 a = global_load_float4(x + c), b = global_load_float4(x + c + 4);
+            v[i][0] = a.x; v[i][1] = a.y; v[i][2] = a.z; v[i][3] = a.w; v[i][4] = b.x; v[i][5] = b.y; v[i][6] = b.z; v[i][7] = b.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[i][e] * v[i][e];
+        }
+    }
     const float tot = block_sum<256>(ss, red);
     const float rs = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += 256)
-        split_store(hi, lo, (size_t)t * d + c, as_global(x)[c] * rs * bf16_f(as_global(gain)[c]));
+#pragma unroll
+    for (int i = 0; i < NORM_RUNS; ++i) {
+        const int c = 8 * (threadIdx.x + 256 * i);
+        if (c < d) {
+            const u32x4 g = global_load16(gain + c);
+            uint32_t h[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const uint32_t gw = e < 2 ? g.x : e < 4 ? g.y : e < 6 ? g.z : g.w;
+                const float y0 = v[i][e] * rs * __uint_as_float(gw << 16), y1 = v[i][e + 1] * rs * __uint_as_float(gw & 0xFFFF0000u);
+                const uint16_t h0 = bf16_rn(y0), h1 = bf16_rn(y1);
+                h[e / 2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                l[e / 2] = (uint32_t)bf16_rn(y0 - bf16_f(h0)) | ((uint32_t)bf16_rn(y1 - bf16_f(h1)) << 16);
+            }
+            const size_t at = act_at(tiled, t, c, d);
+            *(u32x4 __attribute__((address_space(1))) *)(hi + at) = u32x4{h[0], h[1], h[2], h[3]};
+            *(u32x4 __attribute__((address_space(1))) *)(lo + at) = u32x4{l[0], l[1], l[2], l[3]};
+        }
+    }
 }
 
 // (cos, sin) of (p0 + t) * theta^(-2i/d_head), in double as everywhere else
@@ -84,6 +126,7 @@ struct PrefillGemmArgs {
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx, p0;
     // PE_SWIGLU
     uint16_t *uhi, *ulo;         // [T_pad, N]
+    bool tiled;                  // layout of xhi / xlo and of uhi / ulo: see act_at
 };
 
 // Block: token tile blockIdx.x (32 * TT tokens), column tile blockIdx.y (32 * NWV columns);
@@ -221,19 +264,26 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
 // With at most a few dozen tokens the product is bound by streaming the weights, and the tiling
 // above leaves most of the chip idle (few blocks, one k sweep each).  Here a block owns 32
 // weight rows and one 32-token tile, and its NWV waves split the k range between them: wave w
-// takes the 64-wide k steps w, w + NWV, ...  No operand is shared between the waves, so both
-// operands go from global memory straight into registers, double-buffered; the weights are read
-// once from HBM, the (small) activations come out of the L2.  The waves' partial accumulators
-// are summed through LDS in wave order (a fixed order: results do not vary from run to run),
-// and the epilogue runs on the sums: wave w finishes accumulator registers w, w + NWV, ...
+// takes the 64-wide k steps w, w + NWV, ...  No operand is shared between the waves:
+//   * the weights are fetched coalesced (a wave's load = 8 rows x 128 bytes) and turned into
+//     the matrix-core layout (row in the lane) through a wave-private LDS tile -- fetched in
+//     that layout directly, every load touches 32 cache lines and the address path, not the
+//     HBM, is the bound;
+//   * the activations are stored in the matrix-core layout by their producers (act_at) and go
+//     straight into registers, 1 KB contiguous per load, out of the L2.
+// The waves' partial accumulators are summed through LDS in wave order (a fixed order: results
+// do not vary from run to run), and the epilogue runs on the sums: wave w finishes accumulator
+// registers w, w + NWV, ...
+constexpr int W_ROW = KSTEP * 2 + 16;    // bytes per LDS row of the weight tile (as A_ROW)
+
 template <int EPI, int NWV>
 __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillGemmArgs a) {
     constexpr int NMAT = EPI == PE_SWIGLU ? 2 : 1;
-    extern __shared__ __align__(16) char a_lds[];          // float [NWV][NMAT][16][64]
+    constexpr int TILE = NMAT * 32 * W_ROW;                // one wave's weight tile(s)
+    extern __shared__ __align__(16) char a_lds[];          // weight tiles [NWV][TILE]; then float [NWV][NMAT][16][64]
     float *red = (float *)a_lds;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     const int t0 = blockIdx.y * 32;
-    const int nl = min((int)blockIdx.x * 32 + lane % 32, a.N - 1);   // (a ragged last tile re-reads the last row)
     const int S = a.K / KSTEP;
     const int n_w = w < S ? (S - w + NWV - 1) / NWV : 0;             // k steps of this wave
     f32x16 acc[NMAT];
@@ -242,42 +292,69 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-    u32x4 wb[2][NMAT][4], xh[2][4], xl[2][4];
-    const size_t w_row = (size_t)nl * a.K + 32 * (lane / 32);
-    const size_t x_row = (size_t)(t0 + lane % 32) * a.K + 32 * (lane / 32);   // rows past T exist (padded arena)
-#define FETCH(slot, i)                                                                                   \
+    // fetch side: load i of a step takes rows 8 i + lane / 8, 16-byte piece lane % 8
+    size_t w_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        w_row[i] = (size_t)min((int)blockIdx.x * 32 + 8 * i + lane / 8, a.N - 1) * a.K + 8 * (lane % 8);   // (ragged last tile: re-reads the last row)
+    char *tile = a_lds + (size_t)w * TILE;
+    const int put = (lane / 8) * W_ROW + (lane % 8) * 16;            // + (mt * 32 + 8 i) * W_ROW
+    const int get = (lane % 32) * W_ROW + (lane / 32) * 64;          // + mt * 32 * W_ROW + 16 j
+    const size_t x_tile = (size_t)blockIdx.y * S * (4 * WAVE * 8) + (size_t)lane * 8;   // act_at of this lane, step 0, j = 0
+
+    u32x4 stage[2][NMAT][4], xh[2][4], xl[2][4];
+#define FETCH_W(slot, i_)                                                                                \
     {                                                                                                     \
-        const int k0 = KSTEP * min(w + NWV * (i), S - 1);                                                 \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
-            wb[slot][0][j] = stream_load16(a.W + w_row + k0 + 8 * j);                                     \
-            if (NMAT == 2) wb[slot][1][j] = stream_load16(a.W2 + w_row + k0 + 8 * j);                     \
-            xh[slot][j] = global_load16(a.xhi + x_row + k0 + 8 * j);                                      \
-            xl[slot][j] = global_load16(a.xlo + x_row + k0 + 8 * j);                                      \
+        const int k0 = KSTEP * min(w + NWV * (i_), S - 1);                                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
+            stage[slot][0][i] = stream_load16(a.W + w_row[i] + k0);                                       \
+            if (NMAT == 2) stage[slot][1][i] = stream_load16(a.W2 + w_row[i] + k0);                       \
         }                                                                                                 \
     }
-#define PRODUCTS(slot)                                                                                   \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                         \
-        _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt) {                                             \
-            const bf16x8 wv = __builtin_bit_cast(bf16x8, wb[slot][mt][j]);                                \
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xh[slot][j]), wv, acc[mt], 0, 0, 0); \
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xl[slot][j]), wv, acc[mt], 0, 0, 0); \
-        }
-    // Loads are unconditional (clamped to the last step); only the products of a step past the
-    // wave's share are skipped, on a wave-uniform condition.
-    FETCH(0, 0)
-    for (int i = 0; i < n_w; i += 2) {
-        FETCH(1, i + 1)
-        __builtin_amdgcn_sched_barrier(0);
-        PRODUCTS(0)
-        __builtin_amdgcn_sched_barrier(0);
-        FETCH(0, i + 2)
-        __builtin_amdgcn_sched_barrier(0);
-        if (i + 1 < n_w) { PRODUCTS(1) }
-        __builtin_amdgcn_sched_barrier(0);
+#define FETCH_X(slot, i_)                                                                                \
+    {                                                                                                     \
+        const size_t at = x_tile + (size_t)min(w + NWV * (i_), S - 1) * (4 * WAVE * 8);                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
+            xh[slot][j] = global_load16(a.xhi + at + j * (WAVE * 8));                                     \
+            xl[slot][j] = global_load16(a.xlo + at + j * (WAVE * 8));                                     \
+        }                                                                                                 \
     }
-#undef FETCH
-#undef PRODUCTS
+    // Step i: its weights (asked for two steps ago) go through the LDS tile; then the requests
+    // of the coming steps -- activations of step i + 1 first, weights of step i + 2 behind them,
+    // since a wave's loads complete in the order they were issued and the next step must not
+    // have to wait for weights it does not need yet -- and the products of step i.
+#define STEP(slot, i_)                                                                                   \
+    {                                                                                                     \
+        _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt)                                               \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                 \
+                *(u32x4 *)(tile + put + (mt * 32 + 8 * i) * W_ROW) = stage[slot][mt][i];                  \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        FETCH_X(1 - slot, (i_) + 1)                                                                       \
+        FETCH_W(slot, (i_) + 2)                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                     \
+            _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt) {                                         \
+                const bf16x8 wv = __builtin_bit_cast(bf16x8, *(const u32x4 *)(tile + get + mt * 32 * W_ROW + 16 * j)); \
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xh[slot][j]), wv, acc[mt], 0, 0, 0); \
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xl[slot][j]), wv, acc[mt], 0, 0, 0); \
+            }                                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+    // The tile is private to the wave and the LDS serves a wave's accesses in order: no barrier
+    // inside the loop.  Loads are unconditional (clamped to the last step); a step past the
+    // wave's share is skipped as a whole on a wave-uniform condition.
+    FETCH_W(0, 0)
+    FETCH_X(0, 0)
+    FETCH_W(1, 1)
+    for (int i = 0; i < n_w; i += 2) {
+        STEP(0, i)
+        if (i + 1 < n_w) STEP(1, i + 1)
+    }
+#undef FETCH_W
+#undef FETCH_X
+#undef STEP
 
+    __syncthreads();                                       // every wave is done with its weight tile
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt)
 #pragma unroll
@@ -318,7 +395,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
                 as_global(a.out)[(size_t)t * a.N + nc] = as_global(a.resid)[(size_t)t * a.N + nc] + v;
             } else {   // PE_SWIGLU: gate in sum[0], up in sum[1]
                 const float up = sum[NMAT - 1];
-                split_store(a.uhi, a.ulo, (size_t)t * a.N + nc, v / (1.0f + expf(-v)) * up);
+                split_store(a.uhi, a.ulo, act_at(true, t, nc, a.N), v / (1.0f + expf(-v)) * up);
             }
         }
     }
@@ -334,6 +411,7 @@ struct PrefillAttnArgs {
     const float *kcache, *vcache; // [n_kv_heads, cap_ctx, d_head]
     uint16_t *ohi, *olo;          // [T_pad, n_heads * d_head]
     int32_t T, p0, n_heads, n_kv_heads, d_head, cap_ctx;
+    bool tiled;                   // layout of ohi / olo: see act_at
 };
 
 __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs a) {
@@ -433,7 +511,7 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4)
             if (4 * (sub + 8 * g4) < dh) {
-                const size_t at = (size_t)t * nqd + (size_t)h * dh + 4 * (sub + 8 * g4);
+                const size_t at = act_at(a.tiled, t, h * dh + 4 * (sub + 8 * g4), nqd);   // 4 consecutive k share a run of 8
                 split_store(a.ohi, a.olo, at, acc[g4].x / l); split_store(a.ohi, a.olo, at + 1, acc[g4].y / l);
                 split_store(a.ohi, a.olo, at + 2, acc[g4].z / l); split_store(a.ohi, a.olo, at + 3, acc[g4].w / l);
             }
@@ -447,14 +525,16 @@ namespace spdk {
 size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (d_head + 4) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
 
 // Launch with the widest column tile that still gives every compute unit a block.
-constexpr int SKINNY_WAVES = 8;
+static size_t skinny_lds(int nmat, int nwv) {
+    const size_t tiles = (size_t)nwv * nmat * 32 * W_ROW, red = (size_t)nwv * nmat * 16 * 64 * sizeof(float);
+    return tiles > red ? tiles : red;
+}
 constexpr int SKINNY_MAX_T = 64;      // up to here the split-k kernel is the faster one
 
 template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
-    if (g.T <= SKINNY_MAX_T) {
-        const size_t red = (size_t)SKINNY_WAVES * (EPI == PE_SWIGLU ? 2 : 1) * 16 * 64 * sizeof(float);
-        hipLaunchKernelGGL((prefill_skinny_kernel<EPI, SKINNY_WAVES>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(64 * SKINNY_WAVES), red, s, g);
+    if (g.tiled) {
+        hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
         return;
     }
     const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
@@ -475,9 +555,9 @@ hipError_t prefill_init() {
     SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 1>), lds4);
     SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 1>), lds4);
     SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), lds2);
-    SPD_LDS((prefill_skinny_kernel<PE_QKV, SKINNY_WAVES>), SKINNY_WAVES * 16 * 64 * 4);
-    SPD_LDS((prefill_skinny_kernel<PE_RESID, SKINNY_WAVES>), SKINNY_WAVES * 16 * 64 * 4);
-    SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, SKINNY_WAVES>), SKINNY_WAVES * 2 * 16 * 64 * 4);
+    SPD_LDS((prefill_skinny_kernel<PE_QKV, 8>), (int)skinny_lds(1, 8));
+    SPD_LDS((prefill_skinny_kernel<PE_RESID, 8>), (int)skinny_lds(1, 8));
+    SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8>), (int)skinny_lds(2, 8));
 #undef SPD_LDS
     return e;
 }
@@ -490,31 +570,32 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
     hipLaunchKernelGGL(embed_rows_kernel, dim3(T), dim3(256), 0, s, (const uint16_t *)c.embed, c.prefix, c.p0, T, d, c.h);
     hipLaunchKernelGGL(rope_table_kernel, dim3((T * (dh / 2) + 255) / 256), dim3(256), 0, s, c.inv_freq, c.p0, T, dh / 2, c.rope);
     float *h = c.h, *h1 = c.h1;
+    const bool tiled = T <= SKINNY_MAX_T;      // short chunk: split-k GEMMs, operands in their layout
     for (int l = 0; l < c.n_layers; ++l) {
         const spd_layer_weights &w = c.layers[l];
-        hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h, (const uint16_t *)w.attn_norm, c.eps, d, c.xhi, c.xlo);
+        hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h, (const uint16_t *)w.attn_norm, c.eps, d, c.xhi, c.xlo, tiled);
         PrefillGemmArgs g{};
         g.xhi = c.xhi; g.xlo = c.xlo; g.W = (const uint16_t *)w.wqkv; g.T = T; g.N = nq + 2 * nkv; g.K = d;
         g.q = c.q; g.kcache = (float *)(c.kv + (size_t)(2 * l) * c.kv_layer_bytes);
         g.vcache = (float *)(c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes);
-        g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
+        g.tiled = tiled; g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
         launch_gemm<PE_QKV, 4>(s, g, c.num_cu);
 
-        PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx};
+        PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
         hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
 
         PrefillGemmArgs o{};
-        o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1;
+        o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled;
         launch_gemm<PE_RESID, 4>(s, o, c.num_cu);
 
-        hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h1, (const uint16_t *)w.ffn_norm, c.eps, d, c.xhi, c.xlo);
+        hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h1, (const uint16_t *)w.ffn_norm, c.eps, d, c.xhi, c.xlo, tiled);
         PrefillGemmArgs f{};
         f.xhi = c.xhi; f.xlo = c.xlo; f.W = (const uint16_t *)w.w_gate; f.W2 = (const uint16_t *)w.w_up; f.T = T; f.N = c.d_ffn; f.K = d;
-        f.uhi = c.uhi; f.ulo = c.ulo;
+        f.uhi = c.uhi; f.ulo = c.ulo; f.tiled = tiled;
         launch_gemm<PE_SWIGLU, 2>(s, f, c.num_cu);
 
         PrefillGemmArgs dn{};
-        dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h;
+        dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h; dn.tiled = tiled;
         launch_gemm<PE_RESID, 4>(s, dn, c.num_cu);
     }
     return hipGetLastError();
