@@ -104,6 +104,46 @@ def cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta):
             "ms_per_step": step_s * 1e3}
 
 
+def probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args):
+    """Cost of the n-gram stage against the number of orders interpolated (the storage-saving
+    variant keeps n = 2..4 only) and against k: average duration of the expand_prune kernel
+    (k^2 options x orders probes of the hash tables, interpolation, prune) and of the whole step."""
+    import torch
+    n_steps = min(args.steps, 24)
+    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 4, k_max=16)
+    rows = []
+    for orders in (None, (2, 3), (2, 3, 4), (2, 3, 4, 5, 6)):
+        alpha = 0.0
+        if orders is not None:
+            sub = {n: tables[n] for n in orders}
+            sess.spd_load_ngrams(sub, lambdas)
+            alpha = 0.55 if orders == (2, 3, 4) else 0.54
+        for k in (1, 3, 5, 10):
+            dc = pkg.SpdDecodeCfg(k, alpha, tau, delta)
+            sess.spd_prefill(prefix)
+            for _ in range(1 + args.warmup):
+                sess.spd_step(dc, fetch=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n_steps):
+                sess.spd_step(dc, fetch=False)
+            torch.cuda.synchronize()
+            step_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+            sess.spd_prefill(prefix)
+            for _ in range(1 + args.warmup):
+                sess.spd_step(dc, fetch=False)
+            sess.spd_set_kernel_timing(True)
+            for _ in range(n_steps):
+                sess.spd_step(dc, fetch=False)
+            timing = sess.spd_get_kernel_timing()
+            sess.spd_set_kernel_timing(False)
+            ms, n = timing["expand_prune"]
+            rows.append({"orders": list(orders) if orders else [], "entries": sum(len(tables[n][1]) for n in (orders or ())),
+                         "alpha": alpha, "k": k, "expand_prune_us": ms * 1e3 / n, "ms_per_step": step_ms})
+    sess.close()
+    print(json.dumps({"probe_sweep": rows, "workload": shape.name, "prefix": len(prefix), "steps": n_steps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -118,6 +158,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a known traffic for scaling HBM counters)")
+    ap.add_argument("--probe-sweep", action="store_true",
+                    help="instead of the benchmark: time the n-gram stage (expand_prune kernel) against the "
+                         "orders loaded (none, 2..3, 2..4, 2..6) and k = 1, 3, 5, 10; prints one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the SPD step is a single-GPU, batch-1 path); "
@@ -151,6 +194,8 @@ def main():
     else:
         tables = synth.make_ngram_tables_zipf(shape.vocab, entries, seed=0)
         prefix = synth.make_prefix_zipf(shape.vocab, m, seed=0)
+    if args.probe_sweep:
+        return probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args)
     sess = pkg.Session(shape, weights, max_ctx=max_ctx, k_max=max(k, 8))
     sess.spd_load_ngrams(tables, lambdas)
     if args.no_graph:

@@ -529,7 +529,10 @@ static size_t skinny_lds(int nmat, int nwv) {
     const size_t tiles = (size_t)nwv * nmat * 32 * W_ROW, red = (size_t)nwv * nmat * 16 * 64 * sizeof(float);
     return tiles > red ? tiles : red;
 }
-constexpr int SKINNY_MAX_T = 64;      // up to here the split-k kernel is the faster one
+#ifndef SPD_SKINNY_MAX_T
+#define SPD_SKINNY_MAX_T 192
+#endif
+constexpr int SKINNY_MAX_T = SPD_SKINNY_MAX_T;      // up to here the split-k kernel is the faster one
 
 template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {

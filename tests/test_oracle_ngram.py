@@ -102,3 +102,29 @@ def test_planting_makes_visited_ngrams_hit():
     assert O.p_ngram(tabs, O.LAMBDAS_PAPER, [1, 2, 3, 4, 5, 6], 7) > 0
     for n, (keys, counts) in synth.plant_ngrams(base, visits, 1000, seed=0, frac=1.0).items():
         assert len(np.unique(keys, axis=0)) == len(keys)
+
+
+def test_reduced_orders_are_the_full_mixture_without_the_missing_terms(toy):
+    """The storage-saving variant (appendix "Perplexity Evaluation with Fewer N-Grams") loads
+    n = 2..4 only and keeps the same interpolation weights: an order without a table adds
+    nothing.  Recounted from the corpus, and equal to the full tables with those weights at 0."""
+    corpus, full = toy
+    small = O.NgramTables(corpus_tables(corpus, orders=(2, 3, 4)))
+    lam = synth.PAPER_LAMBDAS
+    rng = np.random.default_rng(3)
+    n_pos = 0
+    for _ in range(60):
+        at = int(rng.integers(6, len(corpus) - 1))
+        hist, tok = corpus[:at], int(corpus[at]) if rng.random() < 0.7 else int(rng.integers(0, 6))
+        want = 0.0
+        for n in (2, 3, 4):
+            ctx = tuple(hist[-(n - 1):])
+            total = sum(1 for i in range(len(corpus) - n + 1) if tuple(corpus[i:i + n - 1]) == ctx)
+            hits = sum(1 for i in range(len(corpus) - n + 1) if tuple(corpus[i:i + n]) == ctx + (tok,))
+            want += lam[n - 2] * (hits / total if total else 0.0)
+        got = float(O.p_ngram(small, lam, hist, tok, np.float64))
+        assert abs(got - want) < 1e-12
+        assert got == float(O.p_ngram(full, lam[:3] + (0.0, 0.0), hist, tok, np.float64))
+        assert got <= float(O.p_ngram(full, lam, hist, tok, np.float64)) + 1e-15
+        n_pos += got > 0
+    assert n_pos > 20
