@@ -518,6 +518,150 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
     }
 }
 
+// The same attention on the matrix cores, in fp32 (v_mfma_f32_32x32x2_f32: exact fp32 products,
+// as on the step path), for d_head 64 and 128.  One block: 32 queries of one head; its four
+// waves share the cached positions between them (wave w takes the 32-key tiles w, w + 4, ...),
+// each flash-style (running maximum and sum per query), and their partial results are merged
+// through LDS at the end.  Both products are formed transposed, so that a query lives in a
+// lane from start to end:
+//   S^T [key, query] = K [key, d] Q^T [d, query]      -- d_head / 2 products
+//   O^T [d, query]  += V^T [d, key] P^T [key, query]  -- 16 products per 32 columns of d
+// The accumulator layout (lane = column, register r = row 8 (r / 4) + 4 (lane / 32) + r % 4)
+// of S^T is, register by register, the operand layout the second product wants for P^T when
+// its k index (step i, lane half h) stands for key 8 (i / 4) + 4 h + i % 4: the probabilities
+// never leave their registers.  For the first product k index (i, h) stands for feature
+// (d_head / 2) h + i, so a lane reads half a row of K as contiguous 16-byte pieces.
+// Q sits in LDS in operand order; K and V come straight from the cache into the same registers,
+// one after the other, which keeps a wave under half the register file: two waves share a
+// SIMD and one computes while the other waits for its loads.
+template <int DH>
+__global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const PrefillAttnArgs a) {
+    constexpr int HALF = DH / 2, NT = DH / 32, NWV = 4;
+    constexpr int SLOT = (2 + 16 * NT) * WAVE;               // one wave's partial result: m, sum, O^T
+    __shared__ float q_lds[HALF * WAVE];
+    __shared__ float merge[2 * SLOT];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE, h = lane / 32, c = lane % 32;
+    const int head = blockIdx.y, kvh = head / (a.n_heads / a.n_kv_heads);
+    const int q0 = blockIdx.x * 32;                          // < T: the grid has ceil(T / 32) tiles
+    const int nqd = a.n_heads * DH;
+    const float scale = 1.0f / sqrtf((float)DH);
+    if (w == 0) {   // this lane's operand values of Q: query q0 + c (clamped), features HALF h + i
+        const float *qrow = a.q + (size_t)min(q0 + c, a.T - 1) * nqd + (size_t)head * DH + HALF * h;
+#pragma unroll
+        for (int i = 0; i < HALF; i += 4) {
+            const float4 v = global_load_float4(qrow + i);
+            q_lds[(i + 0) * WAVE + lane] = v.x; q_lds[(i + 1) * WAVE + lane] = v.y;
+            q_lds[(i + 2) * WAVE + lane] = v.z; q_lds[(i + 3) * WAVE + lane] = v.w;
+        }
+    }
+    const float *Kb = a.kcache + (size_t)kvh * a.cap_ctx * DH, *Vb = a.vcache + (size_t)kvh * a.cap_ctx * DH;
+    const int qpos = a.p0 + q0 + c;                          // cached positions 0 .. qpos are visible to this lane's query
+    const int last_key = a.p0 + min(q0 + 31, a.T - 1);       // last position any query of the tile sees
+    float m = -INFINITY, lsum = 0.f;
+    f32x16 o[NT];
+#pragma unroll
+    for (int dt = 0; dt < NT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    __syncthreads();                                         // Q is in place
+
+    for (int k0 = 32 * w; k0 <= last_key; k0 += 32 * NWV) {
+        f32x16 st;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = 0.f;
+        {
+            float kreg[HALF];
+            const float *krow = Kb + (size_t)min(k0 + c, last_key) * DH + HALF * h;
+#pragma unroll
+            for (int i = 0; i < HALF; i += 4) {
+                const float4 v = global_load_float4(krow + i);
+                kreg[i] = v.x; kreg[i + 1] = v.y; kreg[i + 2] = v.z; kreg[i + 3] = v.w;
+            }
+#pragma unroll
+            for (int i = 0; i < HALF; ++i) st = __builtin_amdgcn_mfma_f32_32x32x2f32(kreg[i], q_lds[i * WAVE + lane], st, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // V of this tile: requested once K's registers are free (a second wave on the same
+        // SIMD covers the wait), in flight during the softmax
+        float vreg[NT][16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float *vrow = Vb + (size_t)min(k0 + 8 * (i / 4) + 4 * h + i % 4, last_key) * DH + c;
+#pragma unroll
+            for (int dt = 0; dt < NT; ++dt) vreg[dt][i] = as_global(vrow)[32 * dt];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float mx = m;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = k0 + 8 * (r / 4) + 4 * h + r % 4;
+            st[r] = key <= qpos ? st[r] * scale : -INFINITY;
+            mx = fmaxf(mx, st[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));                  // the other half of the keys
+        // a query that sees none of this tile's keys and none before it: keep exp() away from inf - inf
+        const float ref = mx == -INFINITY ? 0.f : mx;
+        const float alpha = expf(m - ref);
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { st[r] = expf(st[r] - ref); psum += st[r]; }
+        lsum = lsum * alpha + psum;
+        m = mx;
+#pragma unroll
+        for (int dt = 0; dt < NT; ++dt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(vreg[dt][i], st[i], o[dt], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // merge: waves 2, 3 -> waves 0, 1; wave 1 -> wave 0.  Wave 0 holds key 0, visible to every
+    // query, so the merged maximum is finite.
+    auto put = [&](int slot) {
+        float *b = merge + slot * SLOT;
+        b[lane] = m; b[WAVE + lane] = lsum;
+#pragma unroll
+        for (int dt = 0; dt < NT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) b[(2 + 16 * dt + r) * WAVE + lane] = o[dt][r];
+    };
+    auto take = [&](int slot) {
+        const float *b = merge + slot * SLOT;
+        const float m2 = b[lane], mt = fmaxf(m, m2);
+        const float ref = mt == -INFINITY ? 0.f : mt;
+        const float f1 = expf(m - ref), f2 = expf(m2 - ref);
+        lsum = lsum * f1 + b[WAVE + lane] * f2;
+#pragma unroll
+        for (int dt = 0; dt < NT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * f1 + b[(2 + 16 * dt + r) * WAVE + lane] * f2;
+        m = mt;
+    };
+    if (w >= 2) put(w - 2);
+    __syncthreads();
+    if (w < 2) take(w);
+    __syncthreads();
+    if (w == 1) put(0);
+    __syncthreads();
+    if (w != 0) return;
+    take(0);
+    lsum += __shfl_xor(lsum, 32);
+    const int t = q0 + c;
+    if (t < a.T) {
+        const float inv = 1.0f / lsum;
+#pragma unroll
+        for (int dt = 0; dt < NT; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {                 // registers 4 r4 .. 4 r4 + 3: four consecutive features
+                const size_t at = act_at(a.tiled, t, head * DH + 32 * dt + 8 * r4 + 4 * h, nqd);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) split_store(a.ohi, a.olo, at + e, o[dt][4 * r4 + e] * inv);
+            }
+    }
+}
+
 }  // namespace
 
 namespace spdk {
@@ -585,7 +729,12 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         launch_gemm<PE_QKV, 4>(s, g, c.num_cu);
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
-        hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
+        if (dh == 128)
+            hipLaunchKernelGGL(prefill_attn_mfma_kernel<128>, dim3((T + 31) / 32, c.n_heads), dim3(256), 0, s, at);
+        else if (dh == 64)
+            hipLaunchKernelGGL(prefill_attn_mfma_kernel<64>, dim3((T + 31) / 32, c.n_heads), dim3(256), 0, s, at);
+        else
+            hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
 
         PrefillGemmArgs o{};
         o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled;
