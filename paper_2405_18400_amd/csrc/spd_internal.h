@@ -183,7 +183,10 @@ struct FusedArgsHost {
 
 // One chunk of the dense prefix pass (bf16 weights): T <= PREFILL_CHUNK prefix tokens at
 // positions p0 .. p0 + T - 1.  Arena buffers are DEVICE, sized for PREFILL_CHUNK rows.
-constexpr int PREFILL_CHUNK = 512;
+#ifndef SPD_PREFILL_CHUNK
+#define SPD_PREFILL_CHUNK 1024
+#endif
+constexpr int PREFILL_CHUNK = SPD_PREFILL_CHUNK;
 struct PrefillChunk {
     const void *embed;
     const int32_t *prefix;             // DEVICE token ids of the whole prefix

@@ -133,7 +133,9 @@ struct PrefillGemmArgs {
 // wave w owns columns [32 w, 32 w + 32) of it, all TT token tiles.  Per k step of 64:
 //   * the activation tile (hi and lo, 32 TT rows x 64 k) is brought in ONCE per block through
 //     LDS (every wave needs all of it; fetched per wave it saturates the L2),
-//   * each lane fetches its own weight row's 64 k straight into registers,
+//   * each wave fetches its 32 weight rows' 64 k coalesced (one load = 8 rows x 128 bytes) and turns
+//     them into the operand layout (row in the lane) through a wave-private LDS tile; fetched in
+//     that layout directly, every load touches 32 cache lines and the address path saturates,
 //   * 8 TT (x 2 for gate and up) matrix-core products per wave.
 // Both are double-buffered: the loads of step s + 1 are in flight during the products of
 // step s.  Token rows past T are computed and dropped.
@@ -160,8 +162,15 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
             for (int r = 0; r < 16; ++r) acc[mt][tt][r] = 0.f;
 
     u32x4 stage_hi[PER_THREAD], stage_lo[PER_THREAD];      // activation pieces on their way to LDS
-    u32x4 wb[2][NMAT][4];                                  // weight pieces of two steps
-    const size_t w_row = (size_t)nl * a.K + 32 * (lane / 32);
+    u32x4 ws[NMAT][4];                                     // weight pieces on their way to LDS
+    // weights, fetch side: load i of a step takes rows 8 i + lane / 8 of the wave's 32, piece lane % 8
+    size_t w_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        w_row[i] = (size_t)min((int)blockIdx.y * (32 * NWV) + 32 * w + 8 * i + lane / 8, a.N - 1) * a.K + 8 * (lane % 8);   // (ragged last tile: re-reads the last row)
+    char *w_tile = a_lds + (size_t)2 * 2 * ROWS * A_ROW + (size_t)w * (NMAT * 32 * A_ROW);   // wave-private
+    const int w_put = (lane / 8) * A_ROW + (lane % 8) * 16;           // + (mt * 32 + 8 i) * A_ROW
+    const int w_get = (lane % 32) * A_ROW + (lane / 32) * 64;         // + mt * 32 * A_ROW + 16 j
     auto lds_at = [&](int buf, int half, int row, int piece) -> char * {
         return a_lds + (size_t)((buf * 2 + half) * ROWS + row) * A_ROW + piece * 16;
     };
@@ -172,10 +181,10 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
         stage_hi[i] = global_load16(a.xhi + at);                                                          \
         stage_lo[i] = global_load16(a.xlo + at);                                                          \
     }
-#define FETCH_W(slot, k0)                                                                                \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
-        wb[slot][0][j] = stream_load16(a.W + w_row + (k0) + 8 * j);                                       \
-        if (NMAT == 2) wb[slot][1][j] = stream_load16(a.W2 + w_row + (k0) + 8 * j);                       \
+#define FETCH_W(k0)                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                       \
+        ws[0][i] = stream_load16(a.W + w_row[i] + (k0));                                                  \
+        if (NMAT == 2) ws[1][i] = stream_load16(a.W2 + w_row[i] + (k0));                                  \
     }
 #define STORE_A(buf)                                                                                     \
     _Pragma("unroll") for (int i = 0; i < PER_THREAD; ++i) {                                              \
@@ -185,38 +194,48 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
             *(u32x4 *)lds_at(buf, 1, p / 8, p % 8) = stage_lo[i];                                         \
         }                                                                                                 \
     }
-#define PRODUCTS(buf, slot)                                                                              \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                         \
+#define STORE_W                                                                                          \
+    _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt)                                                   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                     \
+            *(u32x4 *)(w_tile + w_put + (mt * 32 + 8 * i) * A_ROW) = ws[mt][i];
+#define PRODUCTS(buf)                                                                                    \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
+        bf16x8 wv[NMAT];                                                                                  \
+        _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt)                                               \
+            wv[mt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(w_tile + w_get + mt * 32 * A_ROW + 16 * j)); \
         _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                               \
             const bf16x8 xh = __builtin_bit_cast(bf16x8, *(const u32x4 *)lds_at(buf, 0, 32 * tt + lane % 32, 4 * (lane / 32) + j)); \
             const bf16x8 xl = __builtin_bit_cast(bf16x8, *(const u32x4 *)lds_at(buf, 1, 32 * tt + lane % 32, 4 * (lane / 32) + j)); \
             _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt) {                                         \
-                const bf16x8 wv = __builtin_bit_cast(bf16x8, wb[slot][mt][j]);                            \
-                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, wv, acc[mt][tt], 0, 0, 0);     \
-                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, wv, acc[mt][tt], 0, 0, 0);     \
+                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, wv[mt], acc[mt][tt], 0, 0, 0); \
+                acc[mt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, wv[mt], acc[mt][tt], 0, 0, 0); \
             }                                                                                             \
-        }
+        }                                                                                                 \
+    }
 
     // K is a multiple of two steps (the host checks): the loop body has no branch, and the
     // scheduling barriers keep the compiler from sinking a step's loads down to their first use.
+    // The weight tile is private to its wave and the LDS serves a wave's accesses in order: the
+    // tile of the next step is written behind the reads of this one without a barrier.
     const int k_last = a.K - KSTEP;
-    FETCH_A(0) FETCH_W(0, 0)
-    STORE_A(0)
+    FETCH_A(0) FETCH_W(0)
+    STORE_A(0) STORE_W
     __syncthreads();
     for (int k0 = 0; k0 < a.K; k0 += 2 * KSTEP) {
-        FETCH_A(k0 + KSTEP) FETCH_W(1, k0 + KSTEP)
+        FETCH_A(k0 + KSTEP) FETCH_W(k0 + KSTEP)
         __builtin_amdgcn_sched_barrier(0);
-        PRODUCTS(0, 0)
+        PRODUCTS(0)
         __builtin_amdgcn_sched_barrier(0);
-        STORE_A(1)
+        STORE_A(1) STORE_W
         __syncthreads();
-        FETCH_A(min(k0 + 2 * KSTEP, k_last)) FETCH_W(0, min(k0 + 2 * KSTEP, k_last))
+        FETCH_A(min(k0 + 2 * KSTEP, k_last)) FETCH_W(min(k0 + 2 * KSTEP, k_last))
         __builtin_amdgcn_sched_barrier(0);
-        PRODUCTS(1, 1)
+        PRODUCTS(1)
         __builtin_amdgcn_sched_barrier(0);
-        STORE_A(0)
+        STORE_A(0) STORE_W
         __syncthreads();
     }
+#undef STORE_W
 #undef FETCH_A
 #undef FETCH_W
 #undef STORE_A
@@ -669,12 +688,17 @@ namespace spdk {
 size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (d_head + 4) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
 
 // Launch with the widest column tile that still gives every compute unit a block.
+#ifndef SPD_GEMM_TT
+#define SPD_GEMM_TT 2
+#endif
+constexpr int GEMM_TT = SPD_GEMM_TT;    // 32-token tiles per block of the one-matrix products
+
 static size_t skinny_lds(int nmat, int nwv) {
     const size_t tiles = (size_t)nwv * nmat * 32 * W_ROW, red = (size_t)nwv * nmat * 16 * 64 * sizeof(float);
     return tiles > red ? tiles : red;
 }
 #ifndef SPD_SKINNY_MAX_T
-#define SPD_SKINNY_MAX_T 192
+#define SPD_SKINNY_MAX_T 96
 #endif
 constexpr int SKINNY_MAX_T = SPD_SKINNY_MAX_T;      // up to here the split-k kernel is the faster one
 
@@ -685,23 +709,24 @@ static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
         return;
     }
     const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
-    const size_t lds = (size_t)2 * 2 * (32 * TT) * A_ROW;
+    const int nmat = EPI == PE_SWIGLU ? 2 : 1;
+    auto lds_of = [&](int nwv) { return (size_t)(2 * 2 * (32 * TT) + nwv * nmat * 32) * A_ROW; };
     auto blocks = [&](int nwv) { return t_tiles * ((g.N + 32 * nwv - 1) / (32 * nwv)); };
     if (blocks(4) >= num_cu)
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 4>), dim3(t_tiles, (g.N + 127) / 128), dim3(256), lds, s, g);
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 4>), dim3(t_tiles, (g.N + 127) / 128), dim3(256), lds_of(4), s, g);
     else if (blocks(2) >= num_cu)
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 2>), dim3(t_tiles, (g.N + 63) / 64), dim3(128), lds, s, g);
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 2>), dim3(t_tiles, (g.N + 63) / 64), dim3(128), lds_of(2), s, g);
     else
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 1>), dim3(t_tiles, (g.N + 31) / 32), dim3(64), lds, s, g);
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 1>), dim3(t_tiles, (g.N + 31) / 32), dim3(64), lds_of(1), s, g);
 }
 
 hipError_t prefill_init() {
     hipError_t e = hipFuncSetAttribute((const void *)prefill_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
-    const int lds4 = 2 * 2 * 128 * A_ROW, lds2 = 2 * 2 * 64 * A_ROW;
+    const int big = (2 * 2 * 128 + 4 * 2 * 32) * A_ROW;     // at least what any instantiation asks for
 #define SPD_LDS(K, B) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, B)
-    SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_QKV, 4, 1>), lds4);
-    SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 4>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 2>), lds4); SPD_LDS((prefill_gemm_kernel<PE_RESID, 4, 1>), lds4);
-    SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), lds2); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), lds2);
+    SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 1>), big);
+    SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 1>), big);
+    SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), big);
     SPD_LDS((prefill_skinny_kernel<PE_QKV, 8>), (int)skinny_lds(1, 8));
     SPD_LDS((prefill_skinny_kernel<PE_RESID, 8>), (int)skinny_lds(1, 8));
     SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8>), (int)skinny_lds(2, 8));
@@ -726,7 +751,7 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         g.q = c.q; g.kcache = (float *)(c.kv + (size_t)(2 * l) * c.kv_layer_bytes);
         g.vcache = (float *)(c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes);
         g.tiled = tiled; g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
-        launch_gemm<PE_QKV, 4>(s, g, c.num_cu);
+        launch_gemm<PE_QKV, GEMM_TT>(s, g, c.num_cu);
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
         if (dh == 128)
@@ -738,7 +763,7 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
 
         PrefillGemmArgs o{};
         o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled;
-        launch_gemm<PE_RESID, 4>(s, o, c.num_cu);
+        launch_gemm<PE_RESID, GEMM_TT>(s, o, c.num_cu);
 
         hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h1, (const uint16_t *)w.ffn_norm, c.eps, d, c.xhi, c.xlo, tiled);
         PrefillGemmArgs f{};
@@ -748,7 +773,7 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
 
         PrefillGemmArgs dn{};
         dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h; dn.tiled = tiled;
-        launch_gemm<PE_RESID, 4>(s, dn, c.num_cu);
+        launch_gemm<PE_RESID, GEMM_TT>(s, dn, c.num_cu);
     }
     return hipGetLastError();
 }

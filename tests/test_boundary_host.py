@@ -39,9 +39,9 @@ def test_workspace_bytes_and_config_validation(pkg):
     cfg = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)
     need = pkg.spd_workspace_bytes(cfg)
     kv = 2 * 32 * 32 * 128 * 128 * 4                      # K and V, 32 layers, 32 heads, 128 positions, d_head 128, fp32
-    # arena of the dense prefix pass, 512 token rows: residual stream twice and queries in fp32,
+    # arena of the dense prefix pass, 1024 token rows: residual stream twice and queries in fp32,
     # the (hi, lo) bf16 pairs of the normalised input and of the SwiGLU output, the rotary table
-    arena = 512 * (3 * 4096 * 4 + 2 * 4096 * 2 + 2 * 11008 * 2 + 64 * 8)
+    arena = 1024 * (3 * 4096 * 4 + 2 * 4096 * 2 + 2 * 11008 * 2 + 64 * 8)
     assert kv + arena <= need < kv + arena + 8 * 2 ** 20
     for field, bad in [("dtype", 7), ("n_heads", 3), ("n_kv_heads", 5), ("k_max", 17), ("k_max", 0), ("max_ctx", 1),
                        ("vocab", 31999), ("d_ffn", 11004), ("d_model", 0)]:

@@ -181,13 +181,13 @@ def test_70b_shape_one_layer(forward_path):
     _layer_truncated(synth.LLAMA70B, 1, 131, 3, 3, 70, forward_path)
 
 
-@pytest.mark.parametrize("m", [8, 31, 33, 64, 160, 257, 300, 531])
+@pytest.mark.parametrize("m", [8, 31, 33, 64, 96, 160, 257, 300, 531, 1043])
 def test_dense_prefix_pass_matches_the_oracle_and_the_token_by_token_pass(m):
-    """The prefix pass on the matrix cores (512 tokens per weight pass) against the oracle's
+    """The prefix pass on the matrix cores (1024 tokens per weight pass) against the oracle's
     full-sequence forward and against the token-by-token pass: logits after the prefix, and
     three timesteps on top of the cache it filled.  Sizes straddle the 32- and 64-token tiles
-    the 128-token activation tiles, the switch between the two GEMM kernels (192 tokens) and
-    the 512-token chunk (531 = one full chunk + a short one at a non-zero position); grouped
+    the 128-token activation tiles, the switch between the two GEMM kernels (96 tokens) and
+    the 1024-token chunk (1043 = one full chunk + a short one at a non-zero position); grouped
     key/value heads."""
     pkg = P()
     shape = synth.ModelShape("small-bf16-dense", 3, 512, 8, 2, 1408, 2048, "bf16")
