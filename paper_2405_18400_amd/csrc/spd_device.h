@@ -84,6 +84,9 @@ __device__ __forceinline__ u32x4 stream_load16(const void *uniform_base, uint32_
     return __builtin_nontemporal_load((global_u32x4_ptr)(b + lane_offset));
 }
 __device__ __forceinline__ u32x4 global_load16(const void *p) { return *(global_u32x4_ptr)p; }
+__device__ __forceinline__ u32x4 global_load16(const void *uniform_base, uint32_t lane_offset) {
+    return *(global_u32x4_ptr)((global_char_ptr)uniform_base + lane_offset);
+}
 __device__ __forceinline__ float4 global_load_float4(const float *p) {
     const f32x4 v = *(global_f32x4_ptr)p;
     return make_float4(v.x, v.y, v.z, v.w);

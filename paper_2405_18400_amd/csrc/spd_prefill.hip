@@ -127,9 +127,10 @@ struct PrefillGemmArgs {
     // PE_SWIGLU
     uint16_t *uhi, *ulo;         // [T_pad, N]
     bool tiled;                  // layout of xhi / xlo and of uhi / ulo: see act_at
+    int32_t t_tiles, n_tiles;    // tiled kernel: token tiles and column tiles of the launch
 };
 
-// Block: token tile blockIdx.x (32 * TT tokens), column tile blockIdx.y (32 * NWV columns);
+// Block: one token tile (32 * TT tokens) and one column tile (32 * NWV columns);
 // wave w owns columns [32 w, 32 w + 32) of it, all TT token tiles.  Per k step of 64:
 //   * the activation tile (hi and lo, 32 TT rows x 64 k) is brought in ONCE per block through
 //     LDS (every wave needs all of it; fetched per wave it saturates the L2),
@@ -150,9 +151,13 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
     constexpr int PER_THREAD = (PIECES + NTH - 1) / NTH;   // staged per thread, per half
     extern __shared__ __align__(16) char a_lds[];          // [2 buffers][hi, lo][ROWS][A_ROW]
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
-    const int t0 = blockIdx.x * ROWS;
-    const int n = blockIdx.y * (32 * NWV) + 32 * w + lane % 32;   // this lane's weight row (load side)
-    const int nl = min(n, a.N - 1);                                 // (a ragged last tile re-reads the last row)
+    // Workgroups go to the 8 XCDs round-robin and each XCD has its own L2: all token tiles of a
+    // column tile are placed on one XCD, so a weight tile is fetched into one L2 only (the
+    // activations, an order of magnitude smaller, are what every L2 holds).
+    const int xcd = blockIdx.x % 8, slot_in_xcd = blockIdx.x / 8;
+    const int tile_y = (slot_in_xcd / a.t_tiles) * 8 + xcd, tile_x = slot_in_xcd % a.t_tiles;
+    if (tile_y >= a.n_tiles) return;
+    const int t0 = tile_x * ROWS;
     f32x16 acc[NMAT][TT];
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt)
@@ -161,43 +166,49 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][tt][r] = 0.f;
 
-    u32x4 stage_hi[PER_THREAD], stage_lo[PER_THREAD];      // activation pieces on their way to LDS
-    u32x4 ws[NMAT][4];                                     // weight pieces on their way to LDS
-    // weights, fetch side: load i of a step takes rows 8 i + lane / 8 of the wave's 32, piece lane % 8
-    size_t w_row[4];
+    // pieces on their way to LDS: two steps are in flight (one step's products are shorter than a
+    // trip to memory), in two register slots
+    u32x4 stage_hi[2][PER_THREAD], stage_lo[2][PER_THREAD], ws[2][NMAT][4];
+    // weights, fetch side: load i of a step takes rows 8 i + lane / 8 of the wave's 32, piece lane % 8.
+    // Addresses are a wave-uniform base (matrix + k offset, scalar registers) plus a 32-bit byte
+    // offset per lane, computed once.
+    uint32_t w_off[4], x_off[PER_THREAD];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        w_row[i] = (size_t)min((int)blockIdx.y * (32 * NWV) + 32 * w + 8 * i + lane / 8, a.N - 1) * a.K + 8 * (lane % 8);   // (ragged last tile: re-reads the last row)
+        w_off[i] = ((uint32_t)min(tile_y * (32 * NWV) + 32 * w + 8 * i + lane / 8, a.N - 1) * (uint32_t)a.K + 8 * (lane % 8)) * 2u;   // (ragged last tile: re-reads the last row)
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int p = min(tid + NTH * i, PIECES - 1);
+        x_off[i] = ((uint32_t)(t0 + p / 8) * (uint32_t)a.K + 8 * (p % 8)) * 2u;
+    }
     char *w_tile = a_lds + (size_t)2 * 2 * ROWS * A_ROW + (size_t)w * (NMAT * 32 * A_ROW);   // wave-private
     const int w_put = (lane / 8) * A_ROW + (lane % 8) * 16;           // + (mt * 32 + 8 i) * A_ROW
     const int w_get = (lane % 32) * A_ROW + (lane / 32) * 64;         // + mt * 32 * A_ROW + 16 j
     auto lds_at = [&](int buf, int half, int row, int piece) -> char * {
         return a_lds + (size_t)((buf * 2 + half) * ROWS + row) * A_ROW + piece * 16;
     };
-#define FETCH_A(k0)                                                                                      \
+#define FETCH_A(slot, k0)                                                                                      \
     _Pragma("unroll") for (int i = 0; i < PER_THREAD; ++i) {                                              \
-        const int p = min(tid + NTH * i, PIECES - 1);                                                     \
-        const size_t at = (size_t)(t0 + p / 8) * a.K + (k0) + 8 * (p % 8);                                \
-        stage_hi[i] = global_load16(a.xhi + at);                                                          \
-        stage_lo[i] = global_load16(a.xlo + at);                                                          \
+        stage_hi[slot][i] = global_load16(a.xhi + (k0), x_off[i]);                                        \
+        stage_lo[slot][i] = global_load16(a.xlo + (k0), x_off[i]);                                        \
     }
-#define FETCH_W(k0)                                                                                      \
+#define FETCH_W(slot, k0)                                                                                      \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                       \
-        ws[0][i] = stream_load16(a.W + w_row[i] + (k0));                                                  \
-        if (NMAT == 2) ws[1][i] = stream_load16(a.W2 + w_row[i] + (k0));                                  \
+        ws[slot][0][i] = stream_load16(a.W + (k0), w_off[i]);                                             \
+        if (NMAT == 2) ws[slot][1][i] = stream_load16(a.W2 + (k0), w_off[i]);                             \
     }
-#define STORE_A(buf)                                                                                     \
+#define STORE_A(buf, slot)                                                                                   \
     _Pragma("unroll") for (int i = 0; i < PER_THREAD; ++i) {                                              \
         const int p = tid + NTH * i;                                                                      \
         if (PIECES % NTH == 0 || p < PIECES) {                                                            \
-            *(u32x4 *)lds_at(buf, 0, p / 8, p % 8) = stage_hi[i];                                         \
-            *(u32x4 *)lds_at(buf, 1, p / 8, p % 8) = stage_lo[i];                                         \
+            *(u32x4 *)lds_at(buf, 0, p / 8, p % 8) = stage_hi[slot][i];                                     \
+            *(u32x4 *)lds_at(buf, 1, p / 8, p % 8) = stage_lo[slot][i];                                     \
         }                                                                                                 \
     }
-#define STORE_W                                                                                          \
+#define STORE_W(slot)                                                                                  \
     _Pragma("unroll") for (int mt = 0; mt < NMAT; ++mt)                                                   \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                     \
-            *(u32x4 *)(w_tile + w_put + (mt * 32 + 8 * i) * A_ROW) = ws[mt][i];
+            *(u32x4 *)(w_tile + w_put + (mt * 32 + 8 * i) * A_ROW) = ws[slot][mt][i];
 #define PRODUCTS(buf)                                                                                    \
     _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                       \
         bf16x8 wv[NMAT];                                                                                  \
@@ -218,21 +229,23 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
     // The weight tile is private to its wave and the LDS serves a wave's accesses in order: the
     // tile of the next step is written behind the reads of this one without a barrier.
     const int k_last = a.K - KSTEP;
-    FETCH_A(0) FETCH_W(0)
-    STORE_A(0) STORE_W
+    FETCH_A(0, 0) FETCH_W(0, 0)
+    FETCH_A(1, KSTEP) FETCH_W(1, KSTEP)
+    STORE_A(0, 0) STORE_W(0)
     __syncthreads();
     for (int k0 = 0; k0 < a.K; k0 += 2 * KSTEP) {
-        FETCH_A(k0 + KSTEP) FETCH_W(k0 + KSTEP)
+        // LDS buffer 0 holds step k0, slot 1 (in flight) step k0 + 1; slot 0 is free
+        FETCH_A(0, min(k0 + 2 * KSTEP, k_last)) FETCH_W(0, min(k0 + 2 * KSTEP, k_last))
         __builtin_amdgcn_sched_barrier(0);
         PRODUCTS(0)
         __builtin_amdgcn_sched_barrier(0);
-        STORE_A(1) STORE_W
+        STORE_A(1, 1) STORE_W(1)
         __syncthreads();
-        FETCH_A(min(k0 + 2 * KSTEP, k_last)) FETCH_W(min(k0 + 2 * KSTEP, k_last))
+        FETCH_A(1, min(k0 + 3 * KSTEP, k_last)) FETCH_W(1, min(k0 + 3 * KSTEP, k_last))
         __builtin_amdgcn_sched_barrier(0);
         PRODUCTS(1)
         __builtin_amdgcn_sched_barrier(0);
-        STORE_A(0) STORE_W
+        STORE_A(0, 0) STORE_W(0)
         __syncthreads();
     }
 #undef STORE_W
@@ -242,7 +255,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
 #undef PRODUCTS
 
     // C layout: lane -> column nc = tile + lane % 32; register r -> token 8 (r / 4) + 4 (lane / 32) + r % 4
-    const int nc = blockIdx.y * (32 * NWV) + 32 * w + lane % 32;
+    const int nc = tile_y * (32 * NWV) + 32 * w + lane % 32;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -691,7 +704,11 @@ size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (
 #ifndef SPD_GEMM_TT
 #define SPD_GEMM_TT 2
 #endif
-constexpr int GEMM_TT = SPD_GEMM_TT;    // 32-token tiles per block of the one-matrix products
+constexpr int GEMM_TT = SPD_GEMM_TT;
+#ifndef SPD_SWIGLU_TT
+#define SPD_SWIGLU_TT 2
+#endif
+constexpr int SWIGLU_TT = SPD_SWIGLU_TT;  // the same for gate and up side by side
 
 static size_t skinny_lds(int nmat, int nwv) {
     const size_t tiles = (size_t)nwv * nmat * 32 * W_ROW, red = (size_t)nwv * nmat * 16 * 64 * sizeof(float);
@@ -712,12 +729,15 @@ static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
     const int nmat = EPI == PE_SWIGLU ? 2 : 1;
     auto lds_of = [&](int nwv) { return (size_t)(2 * 2 * (32 * TT) + nwv * nmat * 32) * A_ROW; };
     auto blocks = [&](int nwv) { return t_tiles * ((g.N + 32 * nwv - 1) / (32 * nwv)); };
-    if (blocks(4) >= num_cu)
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 4>), dim3(t_tiles, (g.N + 127) / 128), dim3(256), lds_of(4), s, g);
-    else if (blocks(2) >= num_cu)
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 2>), dim3(t_tiles, (g.N + 63) / 64), dim3(128), lds_of(2), s, g);
-    else
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TT, 1>), dim3(t_tiles, (g.N + 31) / 32), dim3(64), lds_of(1), s, g);
+    PrefillGemmArgs a = g;
+    a.t_tiles = t_tiles;
+    auto launch = [&](auto kernel, int nwv) {
+        a.n_tiles = (g.N + 32 * nwv - 1) / (32 * nwv);
+        hipLaunchKernelGGL(kernel, dim3(t_tiles * ((a.n_tiles + 7) / 8) * 8), dim3(64 * nwv), lds_of(nwv), s, a);
+    };
+    if (blocks(4) >= num_cu) launch(prefill_gemm_kernel<EPI, TT, 4>, 4);
+    else if (blocks(2) >= num_cu) launch(prefill_gemm_kernel<EPI, TT, 2>, 2);
+    else launch(prefill_gemm_kernel<EPI, TT, 1>, 1);
 }
 
 hipError_t prefill_init() {
@@ -726,7 +746,7 @@ hipError_t prefill_init() {
 #define SPD_LDS(K, B) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, B)
     SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 1>), big);
     SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 1>), big);
-    SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, 2, 1>), big);
+    SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 1>), big);
     SPD_LDS((prefill_skinny_kernel<PE_QKV, 8>), (int)skinny_lds(1, 8));
     SPD_LDS((prefill_skinny_kernel<PE_RESID, 8>), (int)skinny_lds(1, 8));
     SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8>), (int)skinny_lds(2, 8));
@@ -769,7 +789,7 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         PrefillGemmArgs f{};
         f.xhi = c.xhi; f.xlo = c.xlo; f.W = (const uint16_t *)w.w_gate; f.W2 = (const uint16_t *)w.w_up; f.T = T; f.N = c.d_ffn; f.K = d;
         f.uhi = c.uhi; f.ulo = c.ulo; f.tiled = tiled;
-        launch_gemm<PE_SWIGLU, 2>(s, f, c.num_cu);
+        launch_gemm<PE_SWIGLU, SWIGLU_TT>(s, f, c.num_cu);
 
         PrefillGemmArgs dn{};
         dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h; dn.tiled = tiled;
