@@ -573,8 +573,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
     __shared__ float q_lds[HALF * WAVE];
     __shared__ float merge[2 * SLOT];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE, h = lane / 32, c = lane % 32;
-    const int head = blockIdx.y, kvh = head / (a.n_heads / a.n_kv_heads);
-    const int q0 = blockIdx.x * 32;                          // < T: the grid has ceil(T / 32) tiles
+    // Workgroups go to the 8 XCDs round-robin: all query tiles of a head are placed on one XCD (its
+    // L2 then holds that head's keys and values once), the tiles that see the most keys first.
+    const int q_tiles = (a.T + 31) / 32;
+    const int xcd = blockIdx.x % 8, slot_in_xcd = blockIdx.x / 8;
+    const int head = (slot_in_xcd / q_tiles) * 8 + xcd;
+    if (head >= a.n_heads) return;
+    const int kvh = head / (a.n_heads / a.n_kv_heads);
+    const int q0 = (q_tiles - 1 - slot_in_xcd % q_tiles) * 32;
     const int nqd = a.n_heads * DH;
     const float scale = 1.0f / sqrtf((float)DH);
     if (w == 0) {   // this lane's operand values of Q: query q0 + c (clamped), features HALF h + i
@@ -775,9 +781,9 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
         if (dh == 128)
-            hipLaunchKernelGGL(prefill_attn_mfma_kernel<128>, dim3((T + 31) / 32, c.n_heads), dim3(256), 0, s, at);
+            hipLaunchKernelGGL(prefill_attn_mfma_kernel<128>, dim3(((T + 31) / 32) * ((c.n_heads + 7) / 8) * 8), dim3(256), 0, s, at);
         else if (dh == 64)
-            hipLaunchKernelGGL(prefill_attn_mfma_kernel<64>, dim3((T + 31) / 32, c.n_heads), dim3(256), 0, s, at);
+            hipLaunchKernelGGL(prefill_attn_mfma_kernel<64>, dim3(((T + 31) / 32) * ((c.n_heads + 7) / 8) * 8), dim3(256), 0, s, at);
         else
             hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
 
