@@ -557,7 +557,9 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
 // through LDS at the end.  Both products are formed transposed, so that a query lives in a
 // lane from start to end:
 //   S^T [key, query] = K [key, d] Q^T [d, query]      -- d_head / 2 products
-//   O^T [d, query]  += V^T [d, key] P^T [key, query]  -- 16 products per 32 columns of d
+//   O^T [d, query]  += V^T [d, key] P^T [key, query]  -- 16 products per 32 features d; tile dt holds
+//                                                        features {(d_head / 32) rho + dt}, so that a lane
+//                                                        reads a key's values as one 16-byte piece
 // The accumulator layout (lane = column, register r = row 8 (r / 4) + 4 (lane / 32) + r % 4)
 // of S^T is, register by register, the operand layout the second product wants for P^T when
 // its k index (step i, lane half h) stands for key 8 (i / 4) + 4 h + i % 4: the probabilities
@@ -623,10 +625,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
         // SIMD covers the wait), in flight during the softmax
         float vreg[NT][16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float *vrow = Vb + (size_t)min(k0 + 8 * (i / 4) + 4 * h + i % 4, last_key) * DH + c;
-#pragma unroll
-            for (int dt = 0; dt < NT; ++dt) vreg[dt][i] = as_global(vrow)[32 * dt];
+        for (int i = 0; i < 16; ++i) {   // one 16-byte piece per key: features NT c .. NT c + NT - 1, one for each product tile
+            const float *vrow = Vb + (size_t)min(k0 + 8 * (i / 4) + 4 * h + i % 4, last_key) * DH + NT * c;
+            if (NT == 4) {
+                const float4 v = global_load_float4(vrow);
+                vreg[0][i] = v.x; vreg[1][i] = v.y; vreg[2][i] = v.z; vreg[3 % NT][i] = v.w;
+            } else {
+                vreg[0][i] = as_global(vrow)[0]; vreg[1 % NT][i] = as_global(vrow)[1];
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         float mx = m;
@@ -690,13 +696,11 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
     if (t < a.T) {
         const float inv = 1.0f / lsum;
 #pragma unroll
-        for (int dt = 0; dt < NT; ++dt)
+        for (int r = 0; r < 16; ++r) {                       // row rho of product tile dt is feature NT rho + dt
+            const size_t at = act_at(a.tiled, t, head * DH + NT * (8 * (r / 4) + 4 * h + r % 4), nqd);
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {                 // registers 4 r4 .. 4 r4 + 3: four consecutive features
-                const size_t at = act_at(a.tiled, t, head * DH + 32 * dt + 8 * r4 + 4 * h, nqd);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) split_store(a.ohi, a.olo, at + e, o[dt][4 * r4 + e] * inv);
-            }
+            for (int dt = 0; dt < NT; ++dt) split_store(a.ohi, a.olo, at + dt, o[dt][r] * inv);
+        }
     }
 }
 
