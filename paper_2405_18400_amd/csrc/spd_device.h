@@ -266,9 +266,11 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     const char *Kg = (const char *)a.K + (size_t)g * a.cap_ctx * dh * sizeof(KT);
     const char *Vg = (const char *)a.V + (size_t)g * a.cap_ctx * dh * sizeof(KT);
 
-    // Cached rows are requested ATTN_BATCH at a time per lane, and the first batch of value
+    // Cached rows are requested ATTN_BATCH at a time per lane (10: one batch covers a chunk of up to
+    // 160 positions, which is what contexts up to 1280 give on 256 blocks and 32 heads; 12 spills
+    // registers in the persistent kernel), and the first batch of value
     // rows together with the keys: this phase is a chain of memory latencies, not bandwidth.
-    constexpr int ATTN_BATCH = 8;
+    constexpr int ATTN_BATCH = 10;
     const int tbase = t0 + wid * PPW + sub;
     // query heads [hq0, hq1) of the group that shares key/value head g
     for (int hq = hq0; hq < min(hq1, group); ++hq) {
