@@ -71,6 +71,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const void *row, 
 __device__ __forceinline__ u32x4 stream_load16(__amdgpu_buffer_rsrc_t row, uint32_t lane_offset) {
     return __builtin_amdgcn_raw_buffer_load_b128(row, (int)lane_offset, 0, 2);   // 2 = non-temporal
 }
+// Cached 16-byte load through a descriptor: a lane whose offset lies past the extent gets zeros.
+__device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_offset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_offset, 0, 0);
+}
 
 typedef const char __attribute__((address_space(1))) *global_char_ptr;
 

@@ -332,7 +332,14 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     char *tile = a_lds + (size_t)w * TILE;
     const int put = (lane / 8) * W_ROW + (lane % 8) * 16;            // + (mt * 32 + 8 i) * W_ROW
     const int get = (lane % 32) * W_ROW + (lane / 32) * 64;          // + mt * 32 * W_ROW + 16 j
-    const size_t x_tile = (size_t)blockIdx.y * S * (4 * WAVE * 8) + (size_t)lane * 8;   // act_at of this lane, step 0, j = 0
+    // Activations: one descriptor per half over this token tile's region (act_at order: step, j,
+    // lane, 8 k).  Lanes whose token does not exist get an offset past the extent: zeros come
+    // back and nothing is fetched, so a tile with few tokens costs few cache lines per load.
+    const uint32_t tile_bytes = (uint32_t)S * (4 * WAVE * 8) * 2u;
+    const __amdgpu_buffer_rsrc_t xh_rsrc = row_resource(a.xhi + (size_t)blockIdx.y * S * (4 * WAVE * 8), tile_bytes);
+    const __amdgpu_buffer_rsrc_t xl_rsrc = row_resource(a.xlo + (size_t)blockIdx.y * S * (4 * WAVE * 8), tile_bytes);
+    const bool token_exists = t0 + lane % 32 < a.T;
+    const uint32_t x_lane = token_exists ? (uint32_t)lane * 16u : 0xFFFFFFF0u - 4u * (WAVE * 16u);   // (+ 3 j pieces stays past the extent, no wrap)
 
     u32x4 stage[2][NMAT][4], xh[2][4], xl[2][4];
 #define FETCH_W(slot, i_)                                                                                \
@@ -345,10 +352,10 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     }
 #define FETCH_X(slot, i_)                                                                                \
     {                                                                                                     \
-        const size_t at = x_tile + (size_t)min(w + NWV * (i_), S - 1) * (4 * WAVE * 8);                   \
+        const uint32_t at = (token_exists ? (uint32_t)min(w + NWV * (i_), S - 1) * (4 * WAVE * 16u) : 0u) + x_lane; \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
-            xh[slot][j] = global_load16(a.xhi + at + j * (WAVE * 8));                                     \
-            xl[slot][j] = global_load16(a.xlo + at + j * (WAVE * 8));                                     \
+            xh[slot][j] = buffer_load16(xh_rsrc, at + j * (WAVE * 16u));                                  \
+            xl[slot][j] = buffer_load16(xl_rsrc, at + j * (WAVE * 16u));                                  \
         }                                                                                                 \
     }
     // Step i: its weights (asked for two steps ago) go through the LDS tile; then the requests
