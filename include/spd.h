@@ -238,10 +238,12 @@ int spd_get_fused(const spd_ctx *ctx, int32_t *out_enabled);
 
 /* spd_prefill runs the prefix either one token at a time through the timestep's forward, or
  * ("dense": the default for bf16 models whose widths allow it, for prefixes of 8 tokens or
- * more) 256 prefix tokens at a time as matrix-matrix products on the matrix cores, reading the
- * weights once per 256 tokens.  Both fill the same cache and leave the same logits up to fp32
- * rounding.  spd_set_dense_prefill switches (SPD_EINVAL when asked for a dense pass the model
- * has none for). */
+ * more; spd_commit uses the same pass) up to 1024 prefix tokens at a time as matrix-matrix
+ * products on the matrix cores, reading the weights once per chunk.  Both fill the same cache
+ * and leave the same logits up to fp32 rounding.  A dense pass exists for bf16 weights,
+ * d_head <= 128, d_model <= 8192 and d_model, d_ffn, n_heads * d_head divisible by 128; it adds
+ * 1024 rows of activations to spd_workspace_bytes.  spd_set_dense_prefill switches (SPD_EINVAL
+ * when asked for a dense pass the model has none for). */
 int spd_set_dense_prefill(spd_ctx *ctx, int32_t enable);
 int spd_get_dense_prefill(const spd_ctx *ctx, int32_t *out_enabled);
 
