@@ -81,3 +81,19 @@ def test_missing_library_fails_loudly(pkg, monkeypatch):
     monkeypatch.setattr(b, "library_path", lambda: "/nonexistent/libspd.so")
     with pytest.raises(ImportError):
         b.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's throughput; asked for more it must say so and exit."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_entry_points_exist():
+    import importlib
+    ge = importlib.import_module("__graft_entry__")
+    assert callable(ge.build) and callable(ge.smoke)
