@@ -420,16 +420,21 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 
 #define SPD_BARRIER(ALL_WAVES_STORED)                                        \
     do {                                                                     \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();      \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0)] = wall_clock64();      \
         grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err, sh);        \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch - 1] = wall_clock64();  \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0) - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
     long long *prof = (a.prof && blockIdx.x < FUSED_PROF_BLOCKS) ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
     const int pos = uniform(as_global(st)->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;
-    unsigned epoch = 0;
+    // The barrier counters run on from launch to launch (the host zeroes them only when a prefix
+    // pass begins): `epoch` continues from the number of barriers all earlier launches passed,
+    // which block 0 leaves behind when it ends.  Every block has read it before it arrives at
+    // this launch's first barrier, and block 0 cannot get past that barrier without them.
+    const unsigned epoch0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.barrier) + BAR_EPOCH_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    unsigned epoch = epoch0;
 
     // phase 0: the input vector (Section 3.1, Eq. 1 and 2); every block keeps this position's
     // rotary table in LDS
@@ -439,7 +444,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     wait_stores();
     u32x4 buf[NBUF];
     GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
-    if (threadIdx.x == 0) { sh.tick = 0; sh.released = 0; }
+    if (threadIdx.x == 0) { sh.tick = 0; sh.released = epoch0; }
     __syncthreads();
     if (!is_wave0()) {   // (not sliced: before this barrier the whole block meets first)
         if (a.n_layers > 0) Qkv::prefetch(cur, buf);
@@ -517,7 +522,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         }
     }
     if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf, epoch);
-    if (prof && threadIdx.x == 0) as_global(prof)[2 * epoch] = wall_clock64();
+    if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0)] = wall_clock64();
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(as_global(a.barrier) + BAR_EPOCH_WORD, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #undef SPD_BARRIER
 }
 

@@ -207,7 +207,8 @@ constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
 constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
-constexpr int BAR_WORDS = 64 * (1 + BAR_MAX_GROUPS);
+constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
+constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
 constexpr int ATTN_CHUNK_MIN = 64;     // the fused kernel picks the chunk per step within these bounds

@@ -206,8 +206,6 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
         f.head = head ? 1 : 0; f.eps = m.rms_eps;
-        e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, BAR_WORDS);
-        if (e != hipSuccess) return e;
         return launch(c, KC_FUSED, [&] { return spdk::fused_forward(c->stream, m.dtype, f, c->fused_blocks); });
     }
     e = launch(c, KC_SUPERPOSE, [&] { return spdk::superpose(c->stream, m.dtype, sa); });
@@ -469,6 +467,8 @@ static int run_prefix_pass(spd_ctx *c, int p0, int m) {
     int32_t *hp = (int32_t *)(c->pinned + up(sizeof(DevState)));
     std::memcpy(hp, c->text.data() + p0, (size_t)(m - p0) * 4);
     HIPCHK(c, hipMemcpyAsync(c->st(), hs, sizeof(DevState), hipMemcpyHostToDevice, c->stream));
+    // the persistent kernel's barrier counters run on from launch to launch within a generation
+    HIPCHK(c, spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, BAR_WORDS));
     HIPCHK(c, hipMemcpyAsync(c->ws + c->L.prefix + (size_t)p0 * 4, hp, (size_t)(m - p0) * 4, hipMemcpyHostToDevice, c->stream));
     c->state = ST_CREATED;
     c->pos = p0; c->n_gen = 0; c->k = 0;
