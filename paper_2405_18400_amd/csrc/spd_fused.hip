@@ -51,7 +51,7 @@ struct FusedShared {
     float sc[ATTN_CHUNK_MAX];
     int s_last;
     unsigned tick;                // bumped by thread 0 whenever it has issued a synchronisation step
-    unsigned released;            // number of device-wide barriers this block has been released from
+    unsigned released;            // number of synchronisation points this block has been released from
 };
 
 // (volatile accesses must name the LDS address space, or they become generic-address
@@ -73,8 +73,8 @@ __device__ __forceinline__ void tick_bump(FusedShared &sh) {
 // memory side (~14 ns each), so this costs about a third of one flat counter.  (One counter
 // per group polled side by side by every block, without the top level, measured slower: the
 // polls of 256 blocks on each of 8 addresses take longer than the extra hop.)  All counters
-// increase monotonically within a launch; the host-side sequence zeroes them between
-// launches.  Bounded: if the grid is not co-resident the wait gives up, raises *err, and
+// increase monotonically and run on from launch to launch (the kernel continues from the
+// count its predecessor left behind); the host zeroes them when a prefix pass begins.  Bounded: if the grid is not co-resident the wait gives up, raises *err, and
 // every later wait returns at once, so the kernel always drains.
 //
 // Everything other blocks will read was stored with write-through (device-scope) stores and
@@ -89,7 +89,7 @@ __device__ __forceinline__ void tick_bump(FusedShared &sh) {
 // a whole tile of weight requests would wait for all of them, while a slice issued behind the
 // poll delays nothing and keeps the weight stream going through the barrier.
 template <bool ALL_WAVES_STORED>
-__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err, FusedShared &sh) {
+__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err, FusedShared &sh, unsigned seq) {
     if (ALL_WAVES_STORED) __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned g = blockIdx.x / BAR_GROUP;
@@ -112,7 +112,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
                 break;
             }
         }
-        *lds_flag(&sh.released) = epoch;
+        *lds_flag(&sh.released) = seq;
     }
     __syncthreads();
 }
@@ -286,7 +286,7 @@ struct Gemv {
     // block's first tile of phase Next (arguments `na`).
     template <typename Next>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
-                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned epoch) {
+                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned seq) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
@@ -349,7 +349,7 @@ struct Gemv {
         // Wave 0 runs the device-wide barrier next and asks for its share after the release
         // (see grid_barrier).
         if (is_wave0()) wait_stores();
-        else Next::prefetch_sliced(na, buf, sh, epoch + 1);   // `epoch` barriers have been passed so far
+        else Next::prefetch_sliced(na, buf, sh, seq + 1);   // `seq` synchronisation points have been passed so far
     }
 };
 
@@ -391,6 +391,47 @@ __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
     return g;
 }
 
+// After the QKV phase nothing but attention needs the new q, k and v, and attention for one
+// head needs only that head's rows.  So instead of a device-wide barrier there is an arrival
+// counter per key/value head that counts finished row pairs: a block adds, for every head, how
+// many of its row pairs belong to the head's query, key or value rows (one lane of wave 0 per
+// head, one atomic instruction), and a block about to run an attention item waits until the
+// head's counter shows all of its row pairs.  Blocks without an item do not wait at all.  The
+// counters run on from layer to layer and launch to launch like the barrier's.  Same rules as
+// grid_barrier: the arriving wave has waited for its write-through stores; the wait is bounded.
+__device__ __forceinline__ void qkv_arrive(unsigned *sync, const GemvArgs &q, FusedShared &sh, unsigned seq) {
+    if (is_wave0()) {
+        int lo, hi;
+        block_range(q.rows / 2, blockIdx.x, gridDim.x, lo, hi, q.first_block);
+        const int g = threadIdx.x, dh2 = q.d_head / 2, n_kv = q.n_kv_rows / q.d_head;
+        const int tq = (q.n_q_rows / q.n_kv_rows) * dh2, kb = q.n_q_rows / 2, vb = (q.n_q_rows + q.n_kv_rows) / 2;
+        auto overlap = [&](int a0, int a1) { return max(0, min(hi, a1) - max(lo, a0)); };
+        const int mine = overlap(g * tq, (g + 1) * tq) + overlap(kb + g * dh2, kb + (g + 1) * dh2) + overlap(vb + g * dh2, vb + (g + 1) * dh2);
+        if (g < n_kv && mine > 0)
+            __hip_atomic_fetch_add(as_global(sync) + 64 * g, (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (threadIdx.x == 0) {
+            tick_bump(sh);
+            *lds_flag(&sh.released) = seq;
+        }
+    }
+    __syncthreads();
+}
+__device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned target, int *err) {
+    if (threadIdx.x == 0) {
+        unsigned spins = 0;
+        while (__hip_atomic_load(as_global(sync) + 64 * kv_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(1);
+            ++spins;
+            if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+            if (spins > SPIN_LIMIT) {
+                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+        }
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
     GemvArgs g{};
     g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.al.h_in(a.act, a.n_layers); g.y = a.logits;
@@ -420,9 +461,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 
 #define SPD_BARRIER(ALL_WAVES_STORED)                                        \
     do {                                                                     \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0)] = wall_clock64();      \
-        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err, sh);        \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0) - 1] = wall_clock64();  \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();      \
+        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err, sh, ++seq);        \
+        if (prof && threadIdx.x == 0) as_global(prof)[2 * seq - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
     long long *prof = (a.prof && blockIdx.x < FUSED_PROF_BLOCKS) ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
@@ -435,6 +476,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     // this launch's first barrier, and block 0 cannot get past that barrier without them.
     const unsigned epoch0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.barrier) + BAR_EPOCH_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     unsigned epoch = epoch0;
+    unsigned seq = 0;   // synchronisation points passed in this launch (device-wide barriers and per-head arrivals)
+    const unsigned layers0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.barrier) + BAR_LAYER_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    unsigned *qkv_sync = a.barrier + QKV_SYNC_WORD0;
+    const bool per_head = a.n_kv_heads <= QKV_SYNC_MAX;
+    const unsigned head_units = (unsigned)((a.n_heads / a.n_kv_heads + 2) * (dh / 2));   // row pairs of one key/value head's q, k, v
 
     // phase 0: the input vector (Section 3.1, Eq. 1 and 2); every block keeps this position's
     // rotary table in LDS
@@ -444,7 +490,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     wait_stores();
     u32x4 buf[NBUF];
     GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
-    if (threadIdx.x == 0) { sh.tick = 0; sh.released = epoch0; }
+    if (threadIdx.x == 0) { sh.tick = 0; sh.released = 0; }
     __syncthreads();
     if (!is_wave0()) {   // (not sliced: before this barrier the whole block meets first)
         if (a.n_layers > 0) Qkv::prefetch(cur, buf);
@@ -476,8 +522,14 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         const int n_splits = (n_ctx + chunk - 1) / chunk;
         const int n_items = a.n_heads * n_splits;
         o.first_block = 4 * n_items <= (int)gridDim.x ? n_items : 0;
-        Qkv::template run<Oproj>(cur, o, pos, sh, buf, epoch);
-        SPD_BARRIER(false);
+        Qkv::template run<Oproj>(cur, o, pos, sh, buf, seq);
+        if (per_head) {   // no device-wide barrier here: see qkv_arrive
+            if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();
+            qkv_arrive(qkv_sync, cur, sh, ++seq);
+            if (prof && threadIdx.x == 0) as_global(prof)[2 * seq - 1] = wall_clock64();
+        } else {
+            SPD_BARRIER(false);
+        }
         if (is_wave0()) Oproj::prefetch(o, buf);
 
         {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
@@ -486,6 +538,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             const int group = a.n_heads / a.n_kv_heads;
             for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
+                if (per_head) qkv_wait(qkv_sync, h / group, (layers0 + l + 1) * head_units, &st->err);
                 attn_item<KvT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
                                          h % group, h % group + 1);
             }
@@ -496,24 +549,24 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         GemvArgs f{};
         f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
         f.rows = a.d_ffn; f.cols = a.d_model;
-        Oproj::template run<GateUp>(o, f, pos, sh, buf, epoch);
+        Oproj::template run<GateUp>(o, f, pos, sh, buf, seq);
         SPD_BARRIER(false);
         if (is_wave0()) GateUp::prefetch(f, buf);
 
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn;
-        GateUp::template run<Down>(f, d, pos, sh, buf, epoch);
+        GateUp::template run<Down>(f, d, pos, sh, buf, seq);
         SPD_BARRIER(false);
         if (is_wave0()) Down::prefetch(d, buf);
 
         if (l + 1 < a.n_layers) {
             cur = qkv_args(a, l + 1);
-            Down::template run<Qkv>(d, cur, pos, sh, buf, epoch);
+            Down::template run<Qkv>(d, cur, pos, sh, buf, seq);
         } else if (a.head) {
             cur = head_args(a);
-            Down::template run<Head>(d, cur, pos, sh, buf, epoch);
+            Down::template run<Head>(d, cur, pos, sh, buf, seq);
         } else {
-            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf, epoch);
+            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf, seq);
         }
         if (l + 1 < a.n_layers || a.head) SPD_BARRIER(false);
         if (is_wave0()) {
@@ -521,10 +574,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             else if (a.head) Head::prefetch(cur, buf);
         }
     }
-    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf, epoch);
-    if (prof && threadIdx.x == 0) as_global(prof)[2 * (epoch - epoch0)] = wall_clock64();
-    if (blockIdx.x == 0 && threadIdx.x == 0)
+    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf, seq);
+    if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         __hip_atomic_store(as_global(a.barrier) + BAR_EPOCH_WORD, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(a.barrier) + BAR_LAYER_WORD, layers0 + (unsigned)a.n_layers, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 #undef SPD_BARRIER
 }
 

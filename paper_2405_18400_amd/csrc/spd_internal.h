@@ -208,7 +208,10 @@ constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phas
 constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
-constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS);
+constexpr int BAR_LAYER_WORD = BAR_EPOCH_WORD + 16;         // layers passed by all launches since the last reset
+constexpr int QKV_SYNC_WORD0 = 64 * (2 + BAR_MAX_GROUPS);  // one arrival counter per key/value head, 256 bytes apart
+constexpr int QKV_SYNC_MAX = 64;        // (one lane of a wave per head)
+constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS + QKV_SYNC_MAX);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
 constexpr int ATTN_CHUNK_MIN = 64;     // the fused kernel picks the chunk per step within these bounds
