@@ -517,7 +517,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         if (n_ctx > ATTN_CHUNK) {
             const int per_head = max(1, (int)gridDim.x / a.n_heads);
             chunk = ((n_ctx + per_head - 1) / per_head + 15) & ~15;
-            chunk = min(ATTN_CHUNK_MAX, max(ATTN_CHUNK_MIN, chunk));
+            // (up to two full chunks, two chunks: few enough items that their blocks still leave
+            // their O-projection rows to the others, which measures faster than four short chunks)
+            chunk = min(ATTN_CHUNK_MAX, max(n_ctx <= 2 * ATTN_CHUNK ? ATTN_CHUNK : ATTN_CHUNK_MIN, chunk));
         }
         const int n_splits = (n_ctx + chunk - 1) / chunk;
         const int n_items = a.n_heads * n_splits;
