@@ -26,7 +26,10 @@ Readings taken where the paper is silent (each is an explicit option or document
 
 Parity pins: see tests/test_oracle_*.py.  "parity unpinned" items (nothing in the paper
 fixes them): the value of delta, where the temperature applies, the rotary pairing
-convention, the overlap granularity.
+convention, the overlap granularity, the distribution a reset samples its draft from
+(choose_draft: the superposition weights), and how the nucleus sampler breaks ties and maps
+the caller's uniform draw to a token (nucleus_sample: inverse CDF in (probability
+descending, id ascending) order).
 """
 from __future__ import annotations
 
