@@ -201,6 +201,8 @@ struct PrefillChunk {
     uint16_t *xhi, *xlo;               // [PREFILL_CHUNK, max(d_model, n_heads * d_head)] bf16 pair
     uint16_t *uhi, *ulo;               // [PREFILL_CHUNK, d_ffn] bf16 pair
     float2 *rope;                      // [PREFILL_CHUNK, d_head / 2]
+    float *ks_part;                    // [column tiles of the widest product, 2, 2, 16, 64]: partial tiles of the split-k kernel
+    int32_t *ks_count;                 // [column tiles of the widest product], zero between launches
 };
 
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase

@@ -21,6 +21,7 @@ const char *const KC_NAMES[KC_N] = {"superpose", "gemv_qkv", "attention", "gemv_
 
 struct Layout {
     size_t pf_h, pf_h1, pf_q, pf_xhi, pf_xlo, pf_uhi, pf_ulo, pf_rope;   // dense prefix pass arena (0 = none)
+    size_t pf_ks_part, pf_ks_count, pf_ks_tiles;
     bool dense;
     size_t state, barrier, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
@@ -98,6 +99,10 @@ Layout make_layout(const spd_model_cfg &c) {
         L.pf_uhi = take((size_t)PREFILL_CHUNK * c.d_ffn * 2);
         L.pf_ulo = take((size_t)PREFILL_CHUNK * c.d_ffn * 2);
         L.pf_rope = take((size_t)PREFILL_CHUNK * (dh / 2) * 8);
+        const size_t widest = std::max((size_t)(nq + 2 * c.n_kv_heads * dh), std::max((size_t)c.d_model, (size_t)c.d_ffn));
+        L.pf_ks_tiles = (widest + 31) / 32;
+        L.pf_ks_part = take(L.pf_ks_tiles * 2 * 2 * 16 * 64 * 4);
+        L.pf_ks_count = take(L.pf_ks_tiles * 4);
     }
     L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * sizeof(float));   // fp32 cache
     L.kv = take(L.kv_layer_bytes * 2 * (size_t)c.n_layers);
@@ -404,6 +409,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
                            hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, (int32_t *)c->st(), 0, sizeof(DevState) / 4);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads);
+    if (e == hipSuccess && L.dense) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.pf_ks_count), 0, (int)L.pf_ks_tiles);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return SPD_EHIP; }
     *out = c;
@@ -487,6 +493,7 @@ static int run_prefix_pass(spd_ctx *c, int p0, int m) {
         pc.xhi = c->at<uint16_t>(c->L.pf_xhi); pc.xlo = c->at<uint16_t>(c->L.pf_xlo);
         pc.uhi = c->at<uint16_t>(c->L.pf_uhi); pc.ulo = c->at<uint16_t>(c->L.pf_ulo);
         pc.rope = c->at<float2>(c->L.pf_rope);
+        pc.ks_part = c->at<float>(c->L.pf_ks_part); pc.ks_count = c->at<int32_t>(c->L.pf_ks_count);
         int last_T = 0;
         for (int at = p0; at < m; at += PREFILL_CHUNK) {
             pc.p0 = at; pc.T = last_T = (m - at < PREFILL_CHUNK) ? m - at : PREFILL_CHUNK;

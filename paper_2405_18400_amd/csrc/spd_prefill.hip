@@ -128,6 +128,8 @@ struct PrefillGemmArgs {
     uint16_t *uhi, *ulo;         // [T_pad, N]
     bool tiled;                  // layout of xhi / xlo and of uhi / ulo: see act_at
     int32_t t_tiles, n_tiles;    // tiled kernel: token tiles and column tiles of the launch
+    float *ks_part;              // split-k kernel, k range halved between two blocks: their partial tiles
+    int32_t *ks_count;           //   and one arrival count per tile (zero between launches)
 };
 
 // Block: one token tile (32 * TT tokens) and one column tile (32 * NWV columns);
@@ -308,16 +310,24 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
 // registers w, w + NWV, ...
 constexpr int W_ROW = KSTEP * 2 + 16;    // bytes per LDS row of the weight tile (as A_ROW)
 
-template <int EPI, int NWV>
+// KS = 2: two blocks share a tile, each with half of the k steps (twice the blocks: the 128
+// column tiles of a 4096-row matrix then fill 256 compute units, and 344 tiles spread more
+// evenly); the block that finishes second adds the other's partial tile (a sum of two terms:
+// the same whichever is second) and runs the epilogue.
+template <int EPI, int NWV, int KS>
 __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillGemmArgs a) {
     constexpr int NMAT = EPI == PE_SWIGLU ? 2 : 1;
     constexpr int TILE = NMAT * 32 * W_ROW;                // one wave's weight tile(s)
+    constexpr int NWE = NWV * KS;                          // waves that share the tile's k range
+    constexpr int RPW = 16 / NWV;                          // accumulator registers a wave finishes
     extern __shared__ __align__(16) char a_lds[];          // weight tiles [NWV][TILE]; then float [NWV][NMAT][16][64]
+    __shared__ int ks_second;
     float *red = (float *)a_lds;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    const int col_tile = blockIdx.x / KS, half = blockIdx.x % KS, we = w + NWV * half;
     const int t0 = blockIdx.y * 32;
     const int S = a.K / KSTEP;
-    const int n_w = w < S ? (S - w + NWV - 1) / NWV : 0;             // k steps of this wave
+    const int n_w = we < S ? (S - we + NWE - 1) / NWE : 0;           // k steps of this wave
     f32x16 acc[NMAT];
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt)
@@ -328,7 +338,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     size_t w_row[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        w_row[i] = (size_t)min((int)blockIdx.x * 32 + 8 * i + lane / 8, a.N - 1) * a.K + 8 * (lane % 8);   // (ragged last tile: re-reads the last row)
+        w_row[i] = (size_t)min(col_tile * 32 + 8 * i + lane / 8, a.N - 1) * a.K + 8 * (lane % 8);   // (ragged last tile: re-reads the last row)
     char *tile = a_lds + (size_t)w * TILE;
     const int put = (lane / 8) * W_ROW + (lane % 8) * 16;            // + (mt * 32 + 8 i) * W_ROW
     const int get = (lane % 32) * W_ROW + (lane / 32) * 64;          // + mt * 32 * W_ROW + 16 j
@@ -344,7 +354,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     u32x4 stage[2][NMAT][4], xh[2][4], xl[2][4];
 #define FETCH_W(slot, i_)                                                                                \
     {                                                                                                     \
-        const int k0 = KSTEP * min(w + NWV * (i_), S - 1);                                                \
+        const int k0 = KSTEP * min(we + NWE * (i_), S - 1);                                               \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
             stage[slot][0][i] = stream_load16(a.W + w_row[i] + k0);                                       \
             if (NMAT == 2) stage[slot][1][i] = stream_load16(a.W2 + w_row[i] + k0);                       \
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     }
 #define FETCH_X(slot, i_)                                                                                \
     {                                                                                                     \
-        const uint32_t at = (token_exists ? (uint32_t)min(w + NWV * (i_), S - 1) * (4 * WAVE * 16u) : 0u) + x_lane; \
+        const uint32_t at = (token_exists ? (uint32_t)min(we + NWE * (i_), S - 1) * (4 * WAVE * 16u) : 0u) + x_lane; \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                   \
             xh[slot][j] = buffer_load16(xh_rsrc, at + j * (WAVE * 16u));                                  \
             xl[slot][j] = buffer_load16(xl_rsrc, at + j * (WAVE * 16u));                                  \
@@ -401,14 +411,43 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     __syncthreads();
 
     // C layout: lane -> column nc = tile + lane % 32; register r -> token 8 (r / 4) + 4 (lane / 32) + r % 4
-    const int nc = blockIdx.x * 32 + lane % 32;
-    for (int r = w; r < 16; r += NWV) {
-        float sum[NMAT];
+    const int nc = col_tile * 32 + lane % 32;
+    float sums[RPW][NMAT];
+#pragma unroll
+    for (int ri = 0; ri < RPW; ++ri)
 #pragma unroll
         for (int mt = 0; mt < NMAT; ++mt) {
-            sum[mt] = 0.f;
-            for (int ww = 0; ww < NWV; ++ww) sum[mt] += red[((ww * NMAT + mt) * 16 + r) * WAVE + lane];
+            sums[ri][mt] = 0.f;
+            for (int ww = 0; ww < NWV; ++ww) sums[ri][mt] += red[((ww * NMAT + mt) * 16 + w + NWV * ri) * WAVE + lane];
         }
+    if (KS == 2) {
+        const size_t tile_lin = (size_t)blockIdx.y * (gridDim.x / KS) + col_tile;
+        float *mine = a.ks_part + ((tile_lin * 2 + half) * NMAT) * (16 * WAVE);
+        const float *other = a.ks_part + ((tile_lin * 2 + (1 - half)) * NMAT) * (16 * WAVE);
+#pragma unroll
+        for (int ri = 0; ri < RPW; ++ri)
+#pragma unroll
+            for (int mt = 0; mt < NMAT; ++mt) act_store<true>(mine + (mt * 16 + w + NWV * ri) * WAVE + lane, sums[ri][mt]);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // write-through stores acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(as_global(a.ks_count) + tile_lin, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ks_second = old;
+            if (old == 1) __hip_atomic_store(as_global(a.ks_count) + tile_lin, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!ks_second) return;
+#pragma unroll
+        for (int ri = 0; ri < RPW; ++ri)
+#pragma unroll
+            for (int mt = 0; mt < NMAT; ++mt) sums[ri][mt] += coherent_load(other + (mt * 16 + w + NWV * ri) * WAVE + lane);
+    }
+#pragma unroll
+    for (int ri = 0; ri < RPW; ++ri) {
+        const int r = w + NWV * ri;
+        float sum[NMAT];
+#pragma unroll
+        for (int mt = 0; mt < NMAT; ++mt) sum[mt] = sums[ri][mt];
         const int t = t0 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
         const float v = sum[0];
         if (EPI == PE_QKV) {
@@ -739,7 +778,11 @@ constexpr int SKINNY_MAX_T = SPD_SKINNY_MAX_T;      // up to here the split-k ke
 template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
     if (g.tiled) {
-        hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
+        // one 32-token tile: halve the k range between two blocks (more, smaller blocks balance better)
+        if (g.T <= 32 && g.ks_part != nullptr)
+            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 2>), dim3(2 * ((g.N + 31) / 32), 1), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
+        else
+            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 1>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
         return;
     }
     const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
@@ -764,9 +807,9 @@ hipError_t prefill_init() {
     SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 1>), big);
     SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_RESID, GEMM_TT, 1>), big);
     SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_SWIGLU, SWIGLU_TT, 1>), big);
-    SPD_LDS((prefill_skinny_kernel<PE_QKV, 8>), (int)skinny_lds(1, 8));
-    SPD_LDS((prefill_skinny_kernel<PE_RESID, 8>), (int)skinny_lds(1, 8));
-    SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8>), (int)skinny_lds(2, 8));
+    SPD_LDS((prefill_skinny_kernel<PE_QKV, 8, 1>), (int)skinny_lds(1, 8)); SPD_LDS((prefill_skinny_kernel<PE_QKV, 8, 2>), (int)skinny_lds(1, 8));
+    SPD_LDS((prefill_skinny_kernel<PE_RESID, 8, 1>), (int)skinny_lds(1, 8)); SPD_LDS((prefill_skinny_kernel<PE_RESID, 8, 2>), (int)skinny_lds(1, 8));
+    SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8, 1>), (int)skinny_lds(2, 8)); SPD_LDS((prefill_skinny_kernel<PE_SWIGLU, 8, 2>), (int)skinny_lds(2, 8));
 #undef SPD_LDS
     return e;
 }
@@ -787,7 +830,7 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         g.xhi = c.xhi; g.xlo = c.xlo; g.W = (const uint16_t *)w.wqkv; g.T = T; g.N = nq + 2 * nkv; g.K = d;
         g.q = c.q; g.kcache = (float *)(c.kv + (size_t)(2 * l) * c.kv_layer_bytes);
         g.vcache = (float *)(c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes);
-        g.tiled = tiled; g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
+        g.tiled = tiled; g.ks_part = c.ks_part; g.ks_count = c.ks_count; g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
         launch_gemm<PE_QKV, GEMM_TT>(s, g, c.num_cu);
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
@@ -799,17 +842,17 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
             hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
 
         PrefillGemmArgs o{};
-        o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled;
+        o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled; o.ks_part = c.ks_part; o.ks_count = c.ks_count;
         launch_gemm<PE_RESID, GEMM_TT>(s, o, c.num_cu);
 
         hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h1, (const uint16_t *)w.ffn_norm, c.eps, d, c.xhi, c.xlo, tiled);
         PrefillGemmArgs f{};
         f.xhi = c.xhi; f.xlo = c.xlo; f.W = (const uint16_t *)w.w_gate; f.W2 = (const uint16_t *)w.w_up; f.T = T; f.N = c.d_ffn; f.K = d;
-        f.uhi = c.uhi; f.ulo = c.ulo; f.tiled = tiled;
+        f.uhi = c.uhi; f.ulo = c.ulo; f.tiled = tiled; f.ks_part = c.ks_part; f.ks_count = c.ks_count;
         launch_gemm<PE_SWIGLU, SWIGLU_TT>(s, f, c.num_cu);
 
         PrefillGemmArgs dn{};
-        dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h; dn.tiled = tiled;
+        dn.xhi = c.uhi; dn.xlo = c.ulo; dn.W = (const uint16_t *)w.w_down; dn.T = T; dn.N = d; dn.K = c.d_ffn; dn.resid = h1; dn.out = h; dn.tiled = tiled; dn.ks_part = c.ks_part; dn.ks_count = c.ks_count;
         launch_gemm<PE_RESID, GEMM_TT>(s, dn, c.num_cu);
     }
     return hipGetLastError();

@@ -42,6 +42,8 @@ def test_workspace_bytes_and_config_validation(pkg):
     # arena of the dense prefix pass, 1024 token rows: residual stream twice and queries in fp32,
     # the (hi, lo) bf16 pairs of the normalised input and of the SwiGLU output, the rotary table
     arena = 1024 * (3 * 4096 * 4 + 2 * 4096 * 2 + 2 * 11008 * 2 + 64 * 8)
+    # partial tiles of the split-k products: two per 32-row tile of the widest product (QKV, 12288 rows), gate + up
+    arena += (12288 // 32) * 2 * 2 * 16 * 64 * 4
     assert kv + arena <= need < kv + arena + 8 * 2 ** 20
     for field, bad in [("dtype", 7), ("n_heads", 3), ("n_kv_heads", 5), ("k_max", 17), ("k_max", 0), ("max_ctx", 1),
                        ("vocab", 31999), ("d_ffn", 11004), ("d_model", 0)]:
