@@ -324,8 +324,16 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     __shared__ int ks_second;
     float *red = (float *)a_lds;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
-    const int col_tile = blockIdx.x / KS, half = blockIdx.x % KS, we = w + NWV * half;
-    const int t0 = blockIdx.y * 32;
+    // Block order (KS = 1, several token tiles): workgroups go to the 8 XCDs round-robin, so the
+    // token tiles of a column tile are 8 apart in the linear index: same XCD, started together,
+    // and the second one finds the weight tile in that XCD's L2.
+    const int n_col = (a.N + 31) / 32;
+    const int grp = blockIdx.x / (8 * a.t_tiles), rem = blockIdx.x % (8 * a.t_tiles);
+    const int ty = KS == 1 ? rem / 8 : 0;
+    const int col_tile = KS == 1 ? grp * 8 + rem % 8 : (int)blockIdx.x / KS;
+    const int half = KS == 1 ? 0 : (int)blockIdx.x % KS, we = w + NWV * half;
+    if (col_tile >= n_col) return;
+    const int t0 = ty * 32;
     const int S = a.K / KSTEP;
     const int n_w = we < S ? (S - we + NWE - 1) / NWE : 0;           // k steps of this wave
     f32x16 acc[NMAT];
@@ -346,8 +354,8 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
     // lane, 8 k).  Lanes whose token does not exist get an offset past the extent: zeros come
     // back and nothing is fetched, so a tile with few tokens costs few cache lines per load.
     const uint32_t tile_bytes = (uint32_t)S * (4 * WAVE * 8) * 2u;
-    const __amdgpu_buffer_rsrc_t xh_rsrc = row_resource(a.xhi + (size_t)blockIdx.y * S * (4 * WAVE * 8), tile_bytes);
-    const __amdgpu_buffer_rsrc_t xl_rsrc = row_resource(a.xlo + (size_t)blockIdx.y * S * (4 * WAVE * 8), tile_bytes);
+    const __amdgpu_buffer_rsrc_t xh_rsrc = row_resource(a.xhi + (size_t)ty * S * (4 * WAVE * 8), tile_bytes);
+    const __amdgpu_buffer_rsrc_t xl_rsrc = row_resource(a.xlo + (size_t)ty * S * (4 * WAVE * 8), tile_bytes);
     const bool token_exists = t0 + lane % 32 < a.T;
     const uint32_t x_lane = token_exists ? (uint32_t)lane * 16u : 0xFFFFFFF0u - 4u * (WAVE * 16u);   // (+ 3 j pieces stays past the extent, no wrap)
 
@@ -421,7 +429,7 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
             for (int ww = 0; ww < NWV; ++ww) sums[ri][mt] += red[((ww * NMAT + mt) * 16 + w + NWV * ri) * WAVE + lane];
         }
     if (KS == 2) {
-        const size_t tile_lin = (size_t)blockIdx.y * (gridDim.x / KS) + col_tile;
+        const size_t tile_lin = (size_t)col_tile;   // (KS = 2 runs with one token tile)
         float *mine = a.ks_part + ((tile_lin * 2 + half) * NMAT) * (16 * WAVE);
         const float *other = a.ks_part + ((tile_lin * 2 + (1 - half)) * NMAT) * (16 * WAVE);
 #pragma unroll
@@ -779,10 +787,13 @@ template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
     if (g.tiled) {
         // one 32-token tile: halve the k range between two blocks (more, smaller blocks balance better)
-        if (g.T <= 32 && g.ks_part != nullptr)
-            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 2>), dim3(2 * ((g.N + 31) / 32), 1), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
+        PrefillGemmArgs a = g;
+        a.t_tiles = (g.T + 31) / 32;
+        const int n_col = (g.N + 31) / 32;
+        if (a.t_tiles == 1 && g.ks_part != nullptr)
+            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 2>), dim3(2 * n_col), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, a);
         else
-            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 1>), dim3((g.N + 31) / 32, (g.T + 31) / 32), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, g);
+            hipLaunchKernelGGL((prefill_skinny_kernel<EPI, 8, 1>), dim3(((n_col + 7) / 8) * 8 * a.t_tiles), dim3(512), skinny_lds(EPI == PE_SWIGLU ? 2 : 1, 8), s, a);
         return;
     }
     const int t_tiles = (g.T + 32 * TT - 1) / (32 * TT);
