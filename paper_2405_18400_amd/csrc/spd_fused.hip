@@ -33,7 +33,7 @@ namespace {
 #define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested while the block synchronises
 #endif
 #ifndef SPD_FUSED_SLICE
-#define SPD_FUSED_SLICE 3         // of which this many go out per synchronisation step of wave 0
+#define SPD_FUSED_SLICE 4         // of which this many go out per synchronisation step of wave 0
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
