@@ -8,6 +8,10 @@
  *   k x k draft options -> n-gram mixture (Section 3.2, Eq. 3) -> interpolation (Eq. 4)
  *   or the no-overlap penalty form (Eq. 5) -> keep the k most probable options and update
  *   their probabilities (Section 3, Eq. for D and P).
+ * Around it: the pass over the prefix (Section 3, "First Timestep"; spd_prefill), one pass of
+ * nucleus sampling on the same forward (the comparison decoder of Section 4.3;
+ * spd_nucleus_step), and committing one draft to restart from it (resets, Section 5.1; a
+ * nucleus-sampled opening in front of Superposed Decoding, Section 4.5; spd_commit).
  *
  * Conventions
  *   - Every function returns SPD_OK (0) or a negative spd_status.  No exceptions, no global
