@@ -125,6 +125,15 @@ def test_many_attention_items(forward_path):
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=400, path=forward_path)
 
 
+def test_more_kv_heads_than_arrival_counters(forward_path):
+    """128 key/value heads: more than the fused kernel has per-head arrival counters for, so it
+    keeps the device-wide barrier after the QKV phase; small heads (d_head 16)."""
+    shape = synth.ModelShape("heads128-fp32", 2, 2048, 128, 128, 1024, 1024, "fp32")
+    w = synth.make_weights(shape, seed=12)
+    prefix = synth.make_prefix_uniform(shape.vocab, 19, seed=12)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, path=forward_path)
+
+
 def test_wide_ffn_three_pass_rows(forward_path):
     """d_ffn wider than one block pass (bf16: 4096 columns), ragged against the pass width,
     like the 7B shape's 11008: exercises the multi-pass rows of the fused kernel."""
