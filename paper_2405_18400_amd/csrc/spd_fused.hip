@@ -70,12 +70,15 @@ __device__ __forceinline__ void tick_bump(FusedShared &sh) {
 // Device-wide barrier, two levels: blocks arrive on their group's counter (BAR_GROUP
 // consecutive blocks per group, counters 256 bytes apart), the last arriver of a group bumps
 // the top counter, everyone polls the top counter.  Same-address atomics serialise at the
-// memory side (~14 ns each), so this costs about a third of one flat counter.  (One counter
-// per group polled side by side by every block, without the top level, measured slower: the
-// polls of 256 blocks on each of 8 addresses take longer than the extra hop.)  All counters
-// increase monotonically and run on from launch to launch (the kernel continues from the
-// count its predecessor left behind); the host zeroes them when a prefix pass begins.  Bounded: if the grid is not co-resident the wait gives up, raises *err, and
-// every later wait returns at once, so the kernel always drains.
+// memory side (~14 ns each): a flat counter pays for 256 of them, a top counter fed by many
+// small groups for the groups' bumps landing on the line everybody polls.  Measured per step
+// at the 7B shape (256 blocks): groups of 8 / 16 / 32 / 64 / 96 / 128 / 256 blocks = +170 / +80 /
+// +32 / +8 / 0 / +13 / +60 us.  (One counter per group polled side by side by every block,
+// without the top level, measured slower: the polls of 256 blocks on each of 8 addresses take
+// longer than the extra hop.)  All counters increase monotonically and run on from launch to
+// launch (the kernel continues from the count its predecessor left behind); the host zeroes
+// them when a prefix pass begins.  Bounded: if the grid is not co-resident the wait gives up,
+// raises *err, and every later wait returns at once, so the kernel always drains.
 //
 // Everything other blocks will read was stored with write-through (device-scope) stores and
 // every storing wave has waited for its own stores (wait_stores) before getting here.

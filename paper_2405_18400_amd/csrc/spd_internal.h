@@ -207,7 +207,10 @@ struct PrefillChunk {
 
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
-constexpr int BAR_GROUP = 32;          // blocks per group of the two-level device-wide barrier
+#ifndef SPD_BAR_GROUP
+#define SPD_BAR_GROUP 96
+#endif
+constexpr int BAR_GROUP = SPD_BAR_GROUP;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
 constexpr int BAR_LAYER_WORD = BAR_EPOCH_WORD + 16;         // layers passed by all launches since the last reset
