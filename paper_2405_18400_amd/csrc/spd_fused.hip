@@ -35,6 +35,9 @@ namespace {
 #ifndef SPD_FUSED_SLICE
 #define SPD_FUSED_SLICE 4         // of which this many go out per synchronisation step of wave 0
 #endif
+#ifndef SPD_BAR_SLEEP
+#define SPD_BAR_SLEEP 32           // s_sleep units (64 cycles) between two polls of the barrier
+#endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
 constexpr int MAX_U = 32;
@@ -107,7 +110,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
             const unsigned seen = __hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             tick_bump(sh);
             if (seen >= epoch * n_groups) break;
-            __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_s_sleep(SPD_BAR_SLEEP);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             if (spins > SPIN_LIMIT) {
