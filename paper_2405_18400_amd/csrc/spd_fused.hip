@@ -30,13 +30,16 @@ namespace {
 #define SPD_FUSED_UO_EXTRA 4      // extra rows per tile of the O projection
 #endif
 #ifndef SPD_FUSED_QD
-#define SPD_FUSED_QD 64           // 16-byte pieces per lane of the next tile requested while the block synchronises
+#define SPD_FUSED_QD 12           // 16-byte pieces per lane of the next tile requested while the block synchronises
 #endif
 #ifndef SPD_FUSED_SLICE
 #define SPD_FUSED_SLICE 4         // of which this many go out per synchronisation step of wave 0
 #endif
 #ifndef SPD_BAR_SLEEP
-#define SPD_BAR_SLEEP 32           // s_sleep units (64 cycles) between two polls of the barrier
+#define SPD_BAR_SLEEP 48           // s_sleep units (64 cycles) between two polls of the barrier
+#endif
+#ifndef SPD_QKV_SLEEP
+#define SPD_QKV_SLEEP 1            // the same between two polls of a head's arrival counter
 #endif
 constexpr int NT = SPD_FUSED_NT;  // threads per block
 constexpr int NW = 8;             // waves side by side on one row
@@ -426,7 +429,7 @@ __device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned t
     if (threadIdx.x == 0) {
         unsigned spins = 0;
         while (__hip_atomic_load(as_global(sync) + 64 * kv_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_s_sleep(SPD_QKV_SLEEP);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             if (spins > SPIN_LIMIT) {
