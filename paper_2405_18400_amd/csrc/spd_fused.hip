@@ -104,10 +104,19 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
         const unsigned g = blockIdx.x / BAR_GROUP;
         const unsigned n_groups = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
         const unsigned my_size = min((unsigned)BAR_GROUP, gridDim.x - g * BAR_GROUP);
-        unsigned *top = ctr, *grp = ctr + 64 * (1 + g);
+        // The top counter exists BAR_TOPS times, kilobytes away from the group counters (the last
+        // lines of the range reserved for groups): the last arriver of a group bumps every copy, a
+        // block polls only its own.  Half the pollers per line, and no poll lands next to a line that
+        // 96 arrivals are being added to: 1.1 % of a step against one top counter in the first line.
+        unsigned *grp = ctr + 64 * (1 + g);
+        unsigned *tops = ctr + 64 * (1 + BAR_MAX_GROUPS - BAR_TOPS), *top = tops + 64 * (blockIdx.x % BAR_TOPS);
         const unsigned old = __hip_atomic_fetch_add(as_global(grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         tick_bump(sh);
-        if (old + 1 == epoch * my_size) __hip_atomic_fetch_add(as_global(top), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == epoch * my_size) {
+#pragma unroll
+            for (int r = 0; r < BAR_TOPS; ++r)
+                __hip_atomic_fetch_add(as_global(tops) + 64 * r, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         unsigned spins = 0;
         while (true) {
             const unsigned seen = __hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

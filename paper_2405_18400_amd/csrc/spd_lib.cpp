@@ -393,7 +393,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
         int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
         if (per_cu > 1) per_cu = 1;
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
-        if (c->fused_blocks > BAR_GROUP * BAR_MAX_GROUPS) c->fused_blocks = 0;
+        if (c->fused_blocks > BAR_GROUP * (BAR_MAX_GROUPS - BAR_TOPS)) c->fused_blocks = 0;
         if (c->fused_blocks > 0 && (4 * cfg->d_model) / (3 * c->fused_blocks) + 4 > FUSED_MAX_EPI) c->fused_blocks = 0;   // residual slice per block (a quarter of the blocks may sit a phase out)
     }
 
