@@ -364,7 +364,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
             else __threadfence();
             __syncthreads();
             if (tid == 0) {
-                const int old = __hip_atomic_fetch_add(as_global(a.counters) + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int old = __hip_atomic_fetch_add(as_global(a.counters) + (size_t)h * ATTN_COUNTER_STRIDE, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 *s_last = (old == n_splits - 1);
             }
             __syncthreads();
@@ -411,7 +411,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                 }
                 if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
                 // (written through: the next user of this counter may sit behind another L2)
-                if (tid == 0) __hip_atomic_store(as_global(a.counters) + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0) __hip_atomic_store(as_global(a.counters) + (size_t)h * ATTN_COUNTER_STRIDE, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();   // sc / dyn / s_last are reused by the next query head or item

@@ -95,12 +95,15 @@ struct GemvArgs {
     int32_t first_block;        // fused kernel: blocks below this index take no rows of this phase
 };
 
+constexpr int ATTN_COUNTER_STRIDE = 64;
+
 struct AttnArgs {
     const float *q;   // [n_heads, d_head]
     const void *K, *V;
     float *out;       // [n_heads, d_head]
     float *part;      // [n_heads, max_splits, d_head + 2]
-    int32_t *counters;  // [n_heads], zero between launches
+    int32_t *counters;  // [n_heads] x ATTN_COUNTER_STRIDE ints (one 256-byte line per head: the chunks' arrivals on different
+                        // heads do not queue behind one another), zero between launches
     const DevState *st;  // n_ctx = st->pos + 1 when non-null
     int32_t n_ctx;       // used when st is null
     int32_t n_heads, n_kv_heads, d_head, cap_ctx, chunk, max_splits;

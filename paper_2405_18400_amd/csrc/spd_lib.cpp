@@ -76,7 +76,7 @@ Layout make_layout(const spd_model_cfg &c) {
     }
     L.logits = take((size_t)c.vocab * 4);
     L.part = take((size_t)c.n_heads * L.max_splits * (dh + 2) * 4);
-    L.counters = take((size_t)c.n_heads * 4);
+    L.counters = take((size_t)c.n_heads * ATTN_COUNTER_STRIDE * 4);
     L.inv_freq = take((size_t)(dh / 2) * 8);
     L.prefix = take((size_t)c.max_ctx * 4);
     L.hist_tok = take((size_t)c.max_ctx * SPD_K_MAX * 4);
@@ -408,7 +408,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
         e = hipMemcpyAsync(c->ws + L.layers_dev, hl, (size_t)cfg->n_layers * sizeof(spd_layer_weights),
                            hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, (int32_t *)c->st(), 0, sizeof(DevState) / 4);
-    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads * ATTN_COUNTER_STRIDE);
     if (e == hipSuccess && L.dense) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.pf_ks_count), 0, (int)L.pf_ks_tiles);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return SPD_EHIP; }
@@ -960,7 +960,7 @@ int spd_op_swiglu(int32_t dtype, const void *Wg, const void *Wu, const void *gai
 size_t spd_op_attention_scratch_bytes(int32_t n_heads, int32_t d_head, int32_t cap_ctx) {
     if (n_heads <= 0 || d_head <= 0 || cap_ctx <= 0) return 0;
     const size_t splits = (size_t)(cap_ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
-    return up((size_t)n_heads * 4) + up((size_t)n_heads * splits * (d_head + 2) * 4);
+    return up((size_t)n_heads * ATTN_COUNTER_STRIDE * 4) + up((size_t)n_heads * splits * (d_head + 2) * 4);
 }
 
 int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V, float *out, void *scratch,
@@ -975,8 +975,8 @@ int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V
     if (n_ctx < 1 || n_ctx > cap_ctx || ((uintptr_t)scratch & (ALIGN - 1))) return SPD_EINVAL;
     hipStream_t s = (hipStream_t)hip_stream;
     int32_t *counters = (int32_t *)scratch;
-    float *part = (float *)((char *)scratch + up((size_t)n_heads * 4));
-    if (spdk::fill_i32(s, counters, 0, n_heads) != hipSuccess) return SPD_EHIP;
+    float *part = (float *)((char *)scratch + up((size_t)n_heads * ATTN_COUNTER_STRIDE * 4));
+    if (spdk::fill_i32(s, counters, 0, n_heads * ATTN_COUNTER_STRIDE) != hipSuccess) return SPD_EHIP;
     AttnArgs a{q, K, V, out, part, counters, nullptr, n_ctx, n_heads, n_kv_heads, d_head, cap_ctx, ATTN_CHUNK,
                (cap_ctx + ATTN_CHUNK - 1) / ATTN_CHUNK};
     return spdk::attention(s, dtype, a) == hipSuccess ? SPD_OK : SPD_EHIP;
