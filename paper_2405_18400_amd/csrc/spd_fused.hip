@@ -35,6 +35,9 @@ namespace {
 #ifndef SPD_FUSED_SLICE
 #define SPD_FUSED_SLICE 4         // of which this many go out per synchronisation step of wave 0
 #endif
+#ifndef SPD_FUSED_ONE_CHUNK
+#define SPD_FUSED_ONE_CHUNK 256   // contexts up to this long are one attention item per head (no merge across blocks)
+#endif
 #ifndef SPD_BAR_SLEEP
 #define SPD_BAR_SLEEP 48           // s_sleep units (64 cycles) between two polls of the barrier
 #endif
@@ -192,6 +195,7 @@ struct Gemv {
     static constexpr int NS = U * P;
     static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U, "tile does not fit the register window");
     static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
+    static_assert(SPD_FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
 
     static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
 
@@ -526,18 +530,20 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
-        // Attention items: one per (query head, chunk of cached positions).  Short contexts are
-        // one chunk; longer ones are cut so that every block gets an item if the chunk bounds
-        // allow.  While few blocks have an item those take no rows of the O projection: they
-        // would hold everybody up fetching their tile after the attention.
+        // Attention items: one per (query head, chunk of cached positions).  Up to
+        // SPD_FUSED_ONE_CHUNK positions a head is ONE item (one or two batches of loads in one
+        // block): a second batch costs about 2 us, merging chunks across blocks about 4 us (an
+        // acknowledged store, an atomic and two dependent loads), but one compute unit's share
+        // of the bandwidth makes a single block the slower choice past some 270 positions.
+        // Longer contexts are cut so that every block gets an item if the chunk bounds allow.
+        // While few blocks have an item those take no rows of the O projection: they would hold
+        // everybody up fetching their tile after the attention.
         const int n_ctx = pos + 1;
-        int chunk = ATTN_CHUNK;
-        if (n_ctx > ATTN_CHUNK) {
+        int chunk = SPD_FUSED_ONE_CHUNK;
+        if (n_ctx > SPD_FUSED_ONE_CHUNK) {
             const int per_head = max(1, (int)gridDim.x / a.n_heads);
             chunk = ((n_ctx + per_head - 1) / per_head + 15) & ~15;
-            // (up to two full chunks, two chunks: few enough items that their blocks still leave
-            // their O-projection rows to the others, which measures faster than four short chunks)
-            chunk = min(ATTN_CHUNK_MAX, max(n_ctx <= 2 * ATTN_CHUNK ? ATTN_CHUNK : ATTN_CHUNK_MIN, chunk));
+            chunk = min(ATTN_CHUNK_MAX, max(ATTN_CHUNK_MIN, chunk));
         }
         const int n_splits = (n_ctx + chunk - 1) / chunk;
         const int n_items = a.n_heads * n_splits;
