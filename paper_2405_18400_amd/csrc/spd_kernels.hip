@@ -206,16 +206,32 @@ __global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
 }
 
 // ------------------------------------------------------------------ expand, interpolate, prune
+// Linear probing, NG_PROBE_BATCH consecutive slots per trip to memory (32-byte slots: a batch
+// is one or two cache lines; every trip is a random access into a table far larger than any
+// cache, and the kernel waits for the longest chain of all its probes).  The slots are then
+// examined in probing order, so the result is that of a slot-by-slot walk.
+constexpr int NG_PROBE_BATCH = 4;
 __device__ __forceinline__ unsigned long long ngram_probe(const NgramDev &ng, const int32_t *key) {
     uint64_t at = ngram_home(ngram_hash(key), ng.capacity);
-    for (int p = 0; p <= ng.max_probe; ++p, at = (at + 1 == ng.capacity) ? 0 : at + 1) {
-        const NgramSlot *sl = ng.slots + at;
-        const u32x4 lo = *(const u32x4 *)sl;
-        const u32x4 hi = *((const u32x4 *)sl + 1);
-        if ((int32_t)lo.x == NG_EMPTY) return 0ull;
-        if ((int32_t)lo.x == key[0] && (int32_t)lo.y == key[1] && (int32_t)lo.z == key[2] &&
-            (int32_t)lo.w == key[3] && (int32_t)hi.x == key[4] && (int32_t)hi.y == key[5])
-            return ((unsigned long long)hi.w << 32) | hi.z;
+    for (int p = 0; p <= ng.max_probe; p += NG_PROBE_BATCH) {
+        u32x4 lo[NG_PROBE_BATCH], hi[NG_PROBE_BATCH];
+#pragma unroll
+        for (int j = 0; j < NG_PROBE_BATCH; ++j) {
+            uint64_t idx = at + (uint64_t)j;
+            while (idx >= ng.capacity) idx -= ng.capacity;
+            const NgramSlot *sl = ng.slots + idx;
+            lo[j] = *(const u32x4 *)sl;
+            hi[j] = *((const u32x4 *)sl + 1);
+        }
+#pragma unroll
+        for (int j = 0; j < NG_PROBE_BATCH; ++j) {
+            if (p + j > ng.max_probe || (int32_t)lo[j].x == NG_EMPTY) return 0ull;
+            if ((int32_t)lo[j].x == key[0] && (int32_t)lo[j].y == key[1] && (int32_t)lo[j].z == key[2] &&
+                (int32_t)lo[j].w == key[3] && (int32_t)hi[j].x == key[4] && (int32_t)hi[j].y == key[5])
+                return ((unsigned long long)hi[j].w << 32) | hi[j].z;
+        }
+        at += NG_PROBE_BATCH;
+        while (at >= ng.capacity) at -= ng.capacity;
     }
     return 0ull;
 }
@@ -230,6 +246,8 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
     __shared__ int s_top[SPD_K_MAX];
     __shared__ float s_logp[SPD_K_MAX];
     __shared__ float s_lse;
+    __shared__ float s_red[NWAVE];
+    __shared__ float s_new[SPD_K_MAX];
     __shared__ int s_tails[SPD_K_MAX][SPD_TAIL];
     __shared__ float s_old[SPD_K_MAX];
     __shared__ unsigned long long s_cnt[SPD_KK * SPD_N_ORDERS];
@@ -241,14 +259,39 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
     const int tid = threadIdx.x, k = a.k;
     DevState *st = a.st;
 
-    // global top-k of the slices' candidates
+    // Everything this kernel reads from memory before the probes is requested at once: the
+    // slices' candidates (a thread's first one stays in registers for all k rounds), the
+    // slices' (max, sum-exp) pairs, the drafts' state.
     const int n_cand = a.n_part * k;
+    float c0v = -INFINITY;
+    int c0i = INT_MAX;
+    if (tid < n_cand) {
+        const int at = (tid / k) * SPD_K_MAX + (tid % k);
+        c0v = a.pv[at];
+        c0i = a.pi[at];
+    }
+    float my_m = -INFINITY;
+    for (int b = tid; b < a.n_part; b += BLOCK) my_m = fmaxf(my_m, a.pm[b]);
+    if (tid < SPD_K_MAX) {
+        s_old[tid] = st->logscore[tid];
+        s_any[tid] = 0;
+        for (int q = 0; q < SPD_TAIL; ++q)
+            s_tails[tid][q] = a.first ? st->prefix_tail[q] : st->tails[tid][q];
+    }
+    // log-sum-exp over the slices: M = max of the maxima, S = sum of sum-exp * exp(max - M)
+    const float M = block_max<BLOCK>(my_m, s_red);
+    float my_s = 0.f;
+    for (int b = tid; b < a.n_part; b += BLOCK) my_s += a.ps[b] * expf(a.pm[b] - M);
+    const float S = block_sum<BLOCK>(my_s, s_red);
+    if (tid == 0) s_lse = M + logf(S);
+    // global top-k of the slices' candidates
     float pv = INFINITY;
     int pi = -1;
     for (int r = 0; r < k; ++r) {
         float bv = -INFINITY;
         int bi = INT_MAX;
-        for (int c = tid; c < n_cand; c += BLOCK) {
+        if (better(pv, pi, c0v, c0i) && better(c0v, c0i, bv, bi)) { bv = c0v; bi = c0i; }
+        for (int c = tid + BLOCK; c < n_cand; c += BLOCK) {
             const int at = (c / k) * SPD_K_MAX + (c % k);
             const float v = a.pv[at];
             const int i = a.pi[at];
@@ -257,19 +300,6 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
         block_best(bv, bi, sv, si);
         if (tid == 0) { s_top[r] = bi; s_logp[r] = bv; }
         pv = bv; pi = bi;
-    }
-    if (tid == 0) {
-        float M = -INFINITY;
-        for (int b = 0; b < a.n_part; ++b) M = fmaxf(M, a.pm[b]);
-        float S = 0.f;
-        for (int b = 0; b < a.n_part; ++b) S += a.ps[b] * expf(a.pm[b] - M);
-        s_lse = M + logf(S);
-    }
-    if (tid < SPD_K_MAX) {
-        s_old[tid] = st->logscore[tid];
-        s_any[tid] = 0;
-        for (int q = 0; q < SPD_TAIL; ++q)
-            s_tails[tid][q] = a.first ? st->prefix_tail[q] : st->tails[tid][q];
     }
     __syncthreads();
     if (tid < k) {
@@ -284,6 +314,7 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
             for (int q = 0; q < SPD_TAIL - 1; ++q) st->tails[tid][q] = s_tails[tid][q + 1];
             st->tails[tid][SPD_TAIL - 1] = s_top[tid];
             st->logscore[tid] = s_logp[tid];
+            s_new[tid] = s_logp[tid];
             st->new_tok[tid] = s_top[tid];
             st->new_parent[tid] = -1;
             a.hist_tok[tid] = s_top[tid];
@@ -364,6 +395,7 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
                 for (int q = 0; q < SPD_TAIL - 1; ++q) st->tails[rank][q] = s_tails[i][q + 1];
                 st->tails[rank][SPD_TAIL - 1] = s_top[j];
                 st->logscore[rank] = s_score[tid];
+                s_new[rank] = s_score[tid];
                 st->new_tok[rank] = s_top[j];
                 st->new_parent[rank] = i;
                 if (gen < a.max_gen) {
@@ -377,8 +409,8 @@ __global__ __launch_bounds__(BLOCK) void expand_prune_kernel(const ExpandArgs a)
     __threadfence_block();
     if (tid == 0) {  // Eq. 2 on the new scores
         float mx = -INFINITY, sum = 0.f, g[SPD_K_MAX];
-        for (int i = 0; i < k; ++i) mx = fmaxf(mx, st->logscore[i]);
-        for (int i = 0; i < k; ++i) { g[i] = expf(st->logscore[i] - mx); sum += g[i]; }
+        for (int i = 0; i < k; ++i) mx = fmaxf(mx, s_new[i]);
+        for (int i = 0; i < k; ++i) { g[i] = expf(s_new[i] - mx); sum += g[i]; }
         for (int i = 0; i < k; ++i) st->gamma[i] = g[i] / sum;
         st->k = k;
         st->n_gen = a.first ? 1 : st->n_gen + 1;
