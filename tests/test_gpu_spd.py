@@ -177,6 +177,22 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
 
 
 @pytest.mark.timeout(600)
+def test_7b_shape_two_layers_context_of_two_load_batches(forward_path):
+    """Llama-2-7B widths (32 heads of 128), two layers, 200 cached positions: past the 160 rows
+    a block's lanes hold per batch of loads, so the fused kernel's single attention item per
+    head walks two batches (the per-operator path cuts the context into two chunks instead)."""
+    _layer_truncated(synth.LLAMA7B, 2, 200, 3, 3, 8, forward_path)
+
+
+@pytest.mark.timeout(600)
+def test_7b_shape_two_layers_config3_context(forward_path):
+    """BASELINE config 3's context and largest k at the 7B widths, two layers: a 1030-token
+    prefix (dense prefix pass over a chunk boundary of its token arena), attention cut into
+    chunks that are merged across blocks, k = 8."""
+    _layer_truncated(synth.LLAMA7B, 2, 1030, 8, 3, 7, forward_path)
+
+
+@pytest.mark.timeout(600)
 def test_13b_shape_two_layers(forward_path):
     """BASELINE config 4's widths (d_model 5120, 40 heads, FFN 13824: rows of 1.25 and 3.375
     block passes), k = 5, two of its 40 layers."""
