@@ -33,8 +33,11 @@ namespace {
 #define SPD_FUSED_QD 12           // 16-byte pieces per lane of the next tile requested while the block synchronises
 #endif
 #ifndef SPD_FUSED_SLICE
-#define SPD_FUSED_SLICE 4         // of which this many go out per synchronisation step of wave 0
+#define SPD_FUSED_SLICE 3         // of which this many go out per synchronisation step of wave 0
 #endif
+#ifndef SPD_FUSED_SLICE_WIDE
+#define SPD_FUSED_SLICE_WIDE 4    // the same for models whose d_model takes two block passes (measured: 3 costs the
+#endif                            //   13B shape 0.3 % and the 70B shape 1 %, and gains the 7B shape 0.1...0.6 %)
 #ifndef SPD_FUSED_ONE_CHUNK
 #define SPD_FUSED_ONE_CHUNK 256   // contexts up to this long are one attention item per head (no merge across blocks)
 #endif
@@ -82,7 +85,9 @@ __device__ __forceinline__ void tick_bump(FusedShared &sh) {
 // memory side (~14 ns each): a flat counter pays for 256 of them, a top counter fed by many
 // small groups for the groups' bumps landing on the line everybody polls.  Measured per step
 // at the 7B shape (256 blocks): groups of 8 / 16 / 32 / 64 / 96 / 128 / 256 blocks = +170 / +80 /
-// +32 / +8 / 0 / +13 / +60 us.  (One counter per group polled side by side by every block,
+// +32 / +8 / 0 / +13 / +60 us with one top counter; with two copies of the top counter away
+// from the group counters, two groups of 128 are 3 us per step ahead of 96 / 96 / 64 (one
+// bump per copy fewer on the polled lines).  (One counter per group polled side by side by every block,
 // without the top level, measured slower: the polls of 256 blocks on each of 8 addresses take
 // longer than the extra hop.)  All counters increase monotonically and run on from launch to
 // launch (the kernel continues from the count its predecessor left behind); the host zeroes
@@ -110,7 +115,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
         // The top counter exists BAR_TOPS times, kilobytes away from the group counters (the last
         // lines of the range reserved for groups): the last arriver of a group bumps every copy, a
         // block polls only its own.  Half the pollers per line, and no poll lands next to a line that
-        // 96 arrivals are being added to: 1.1 % of a step against one top counter in the first line.
+        // a group's arrivals are being added to: 1.1 % of a step against one top counter in the first line.
         unsigned *grp = ctr + 64 * (1 + g);
         unsigned *tops = ctr + 64 * (1 + BAR_MAX_GROUPS - BAR_TOPS), *top = tops + 64 * (blockIdx.x % BAR_TOPS);
         const unsigned old = __hip_atomic_fetch_add(as_global(grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -188,7 +193,7 @@ __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &h
 // Loads are never predicated: a row past the block's range re-reads the last valid row (a
 // cache hit), and a column past the row end lies outside the buffer descriptor, which
 // describes one row (zeros come back, nothing is fetched); the inner loop has no branches.
-template <typename WT, int P, int U, int EPI, int NBUF>
+template <typename WT, int P, int U, int EPI, int NBUF, int SL>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
     static constexpr int UT = U / 2;   // units per tile
@@ -232,7 +237,7 @@ struct Gemv {
 #pragma unroll
         for (int q = 0; q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
     }
-    // The same while thread 0 runs barrier number `epoch`: SPD_FUSED_SLICE pieces behind each
+    // The same while thread 0 runs barrier number `epoch`: SL pieces behind each
     // of its synchronisation steps, everything that is left once the block has been released.
     static __device__ __forceinline__ void prefetch_sliced(const GemvArgs &a_in, u32x4 (&buf)[NBUF], FusedShared &sh,
                                                            unsigned epoch) {
@@ -247,7 +252,7 @@ struct Gemv {
         unsigned seen = uniform((int)*tick);
 #pragma unroll
         for (int q = 0; q < QD; ++q) {
-            if (q % SPD_FUSED_SLICE == 0) {
+            if (q % SL == 0) {
                 unsigned now = seen;
                 for (unsigned spins = 0; spins < SPIN_LIMIT; ++spins) {   // thread 0's own wait is bounded too
                     now = uniform((int)*tick);
@@ -473,11 +478,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int UO = UA + SPD_FUSED_UO_EXTRA / PA;
     constexpr int NA = PA * UO;
     constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
-    using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF>;
-    using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF>;
-    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF>;
-    using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF>;
-    using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF>;
+    constexpr int SL = PA == 1 ? SPD_FUSED_SLICE : SPD_FUSED_SLICE_WIDE;
+    using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
+    using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
+    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL>;
+    using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF, SL>;
+    using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF, SL>;
     __shared__ FusedShared sh;
     __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
 

@@ -211,7 +211,7 @@ struct PrefillChunk {
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
 #ifndef SPD_BAR_GROUP
-#define SPD_BAR_GROUP 96
+#define SPD_BAR_GROUP 128
 #endif
 constexpr int BAR_GROUP = SPD_BAR_GROUP;          // blocks per group of the two-level device-wide barrier
 constexpr int BAR_TOPS = 2;            // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
