@@ -42,8 +42,11 @@ namespace {
 #define SPD_FUSED_ONE_CHUNK 256   // contexts up to this long are one attention item per head (no merge across blocks)
 #endif
 #ifndef SPD_BAR_SLEEP
-#define SPD_BAR_SLEEP 48           // s_sleep units (64 cycles) between two polls of the barrier
+#define SPD_BAR_SLEEP 36           // s_sleep units (64 cycles) between two polls of the barrier
 #endif
+#ifndef SPD_BAR_SLEEP_WIDE
+#define SPD_BAR_SLEEP_WIDE 48      // the same where d_ffn takes more than four block passes (the 70B shape: long
+#endif                             //   phases, and 36 costs it 0.3 %; the 7B and 13B shapes gain 0.4 and 0.2 %)
 #ifndef SPD_QKV_SLEEP
 #define SPD_QKV_SLEEP 1            // the same between two polls of a head's arrival counter
 #endif
@@ -105,7 +108,7 @@ __device__ __forceinline__ void tick_bump(FusedShared &sh) {
 // a compute unit serves its memory operations in order, so an arrival or a poll issued behind
 // a whole tile of weight requests would wait for all of them, while a slice issued behind the
 // poll delays nothing and keeps the weight stream going through the barrier.
-template <bool ALL_WAVES_STORED>
+template <bool ALL_WAVES_STORED, int SLEEP>
 __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err, FusedShared &sh, unsigned seq) {
     if (ALL_WAVES_STORED) __syncthreads();
     if (threadIdx.x == 0) {
@@ -130,7 +133,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int 
             const unsigned seen = __hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             tick_bump(sh);
             if (seen >= epoch * n_groups) break;
-            __builtin_amdgcn_s_sleep(SPD_BAR_SLEEP);
+            __builtin_amdgcn_s_sleep(SLEEP);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             if (spins > SPIN_LIMIT) {
@@ -479,6 +482,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int NA = PA * UO;
     constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
     constexpr int SL = PA == 1 ? SPD_FUSED_SLICE : SPD_FUSED_SLICE_WIDE;
+    constexpr int BAR_SLEEP = PB > 4 ? SPD_BAR_SLEEP_WIDE : SPD_BAR_SLEEP;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL>;
@@ -490,7 +494,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
 #define SPD_BARRIER(ALL_WAVES_STORED)                                        \
     do {                                                                     \
         if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();      \
-        grid_barrier<ALL_WAVES_STORED>(a.barrier, ++epoch, &st->err, sh, ++seq);        \
+        grid_barrier<ALL_WAVES_STORED, BAR_SLEEP>(a.barrier, ++epoch, &st->err, sh, ++seq); \
         if (prof && threadIdx.x == 0) as_global(prof)[2 * seq - 1] = wall_clock64();  \
     } while (0)
     DevState *st = a.sup.st;
