@@ -214,7 +214,10 @@ constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phas
 #define SPD_BAR_GROUP 128
 #endif
 constexpr int BAR_GROUP = SPD_BAR_GROUP;          // blocks per group of the two-level device-wide barrier
-constexpr int BAR_TOPS = 2;            // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
+#ifndef SPD_BAR_TOPS
+#define SPD_BAR_TOPS 2
+#endif
+constexpr int BAR_TOPS = SPD_BAR_TOPS;            // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
 constexpr int BAR_LAYER_WORD = BAR_EPOCH_WORD + 16;         // layers passed by all launches since the last reset
