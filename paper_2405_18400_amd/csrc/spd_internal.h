@@ -226,7 +226,10 @@ constexpr int QKV_SYNC_MAX = 64;        // (one lane of a wave per head)
 constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS + QKV_SYNC_MAX);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
-constexpr int ATTN_CHUNK_MIN = 64;     // the fused kernel picks the chunk per step within these bounds
+#ifndef SPD_ATTN_CHUNK_MIN
+#define SPD_ATTN_CHUNK_MIN 64
+#endif
+constexpr int ATTN_CHUNK_MIN = SPD_ATTN_CHUNK_MIN;     // the fused kernel picks the chunk per step within these bounds
 constexpr int ATTN_CHUNK_MAX = 512;
 
 namespace spdk {
