@@ -183,25 +183,44 @@ __global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
     __shared__ float red[NWAVE];
     const int tid = threadIdx.x, b = blockIdx.x;
     const int lo = b * a.per_part, hi = min(a.vocab, lo + a.per_part);
-    float mx = -INFINITY;
-    for (int i = lo + tid; i < hi; i += BLOCK) mx = fmaxf(mx, __fdiv_rn(a.logits[i], a.tau));
-    mx = block_max<BLOCK>(mx, red);
-    float sm = 0.f;
-    for (int i = lo + tid; i < hi; i += BLOCK) sm += expf(__fdiv_rn(a.logits[i], a.tau) - mx);
-    sm = block_sum<BLOCK>(sm, red);
-    if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; }
+    // A thread's first NR entries of the slice stay in registers (all of them for slices of up
+    // to NR * BLOCK entries); the kernel is a chain of block-wide reductions, so it reads its
+    // logits once and takes the maximum from the first arg-best round (x -> x / tau is
+    // monotonic for tau > 0: the largest logit gives the largest z).
+    constexpr int NR = 4;
+    float rv[NR];
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        const int i = lo + tid + q * BLOCK;
+        rv[q] = i < hi ? a.logits[i] : -INFINITY;
+    }
     float pv = INFINITY;   // previous winner: everything "after" it in the total order is eligible
     int pi = -1;
     for (int r = 0; r < a.k; ++r) {
         float bv = -INFINITY;
         int bi = INT_MAX;
-        for (int i = lo + tid; i < hi; i += BLOCK) {
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            const int i = lo + tid + q * BLOCK;
+            if (i < hi && better(pv, pi, rv[q], i) && better(rv[q], i, bv, bi)) { bv = rv[q]; bi = i; }
+        }
+        for (int i = lo + tid + NR * BLOCK; i < hi; i += BLOCK) {
             const float v = a.logits[i];
             if (better(pv, pi, v, i) && better(v, i, bv, bi)) { bv = v; bi = i; }
         }
         block_best(bv, bi, sv, si);
         if (tid == 0) { a.pv[b * SPD_K_MAX + r] = bv; a.pi[b * SPD_K_MAX + r] = bi; }
         pv = bv; pi = bi;
+        if (r == 0) {
+            const float mx = lo < hi ? __fdiv_rn(bv, a.tau) : -INFINITY;
+            float sm = 0.f;
+#pragma unroll
+            for (int q = 0; q < NR; ++q)
+                if (lo + tid + q * BLOCK < hi) sm += expf(__fdiv_rn(rv[q], a.tau) - mx);
+            for (int i = lo + tid + NR * BLOCK; i < hi; i += BLOCK) sm += expf(__fdiv_rn(a.logits[i], a.tau) - mx);
+            sm = block_sum<BLOCK>(sm, red);
+            if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; }
+        }
     }
 }
 
