@@ -125,6 +125,16 @@ def test_many_attention_items(forward_path):
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=400, path=forward_path)
 
 
+def test_vocabulary_of_140k_tokens(forward_path):
+    """A vocabulary larger than 128 slices of 1024 entries: the per-slice top-k kernel then has
+    more entries per slice than its threads keep in registers and walks the rest from memory;
+    k = 5 of 140000."""
+    shape = synth.ModelShape("vocab140k-fp32", 1, 128, 2, 2, 256, 140000, "fp32")
+    w = synth.make_weights(shape, seed=14)
+    prefix = synth.make_prefix_uniform(shape.vocab, 7, seed=14)
+    run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 5, 0.0, 4, path=forward_path)
+
+
 def test_more_kv_heads_than_arrival_counters(forward_path):
     """128 key/value heads: more than the fused kernel has per-head arrival counters for, so it
     keeps the device-wide barrier after the QKV phase; small heads (d_head 16)."""
