@@ -378,6 +378,53 @@ def test_expand_prune_on_scripted_logits_with_ties(tiny):
         sess.close()
 
 
+def test_many_small_hash_tables_against_the_oracle(tiny):
+    """The n-gram probabilities of the k x k options on 150 different tiny tables (about a
+    hundred keys in about two hundred slots each): clusters of displaced keys occur all over
+    such a table, at its end too, where the probe sequence wraps round to slot 0; the oracle
+    looks the same n-grams up in plain dictionaries.  Exact comparison (counts are integers,
+    the mixture of Eq. 3 is a handful of fp32 operations in a fixed order)."""
+    shape, w, _, _ = tiny
+    pkg = P()
+    lam = synth.PAPER_LAMBDAS
+    from collections import Counter
+    sess = session(shape, w)
+    try:
+        k = 3
+        dc = pkg.SpdDecodeCfg(k, 0.54, 1.0, 0.1)
+        cfg = O.DecodeCfg(k, 0.54, 1.0, 0.1, lam)
+        hits = 0
+        for seed in range(150):
+            rng = np.random.default_rng(1000 + seed)
+            corpus = rng.integers(0, 6, size=16)
+            ctabs = {}
+            for n in range(2, 7):
+                c = Counter(tuple(corpus[i:i + n]) for i in range(len(corpus) - n + 1))
+                ctabs[n] = (np.array(list(c.keys()), np.int32).reshape(-1, n), np.array(list(c.values()), np.uint32))
+            sess.spd_load_ngrams(ctabs, lam)
+            otabs = O.NgramTables(ctabs)
+            pre = corpus[:6].astype(np.int32)
+            sess.spd_prefill(pre)
+            state = None
+            for step in range(3):
+                z = np.full(shape.vocab, -8.0, np.float32)
+                z[:6] = rng.permutation(6).astype(np.float32)   # distinct: no ties, top-k inside the corpus alphabet
+                if state is None:
+                    state, rec = O.first_step(z, pre, cfg)
+                else:
+                    state, rec = O.expand_and_prune(state, z, otabs, cfg)
+                sess.spd_expand_prune(dc, torch.from_numpy(z).cuda(), first=(step == 0))
+                ids, lp, cs, cv, cp = sess.spd_get_step_info(k)
+                assert list(ids) == list(rec.top_ids), f"table {seed} step {step}"
+                if step > 0:
+                    np.testing.assert_allclose(cp, rec.pngram, rtol=1e-6, err_msg=f"table {seed} step {step}")
+                    hits += int(np.count_nonzero(rec.pngram))
+                sess.spd_set_state(tails_of(state), state.logscores)
+        assert hits > 300   # the tables were hit, not merely missed consistently
+    finally:
+        sess.close()
+
+
 def test_error_paths(tiny):
     shape, w, tabs, prefix = tiny
     pkg = P()
