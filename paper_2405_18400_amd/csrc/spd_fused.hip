@@ -41,6 +41,7 @@ namespace {
 #ifndef SPD_FUSED_ONE_CHUNK
 #define SPD_FUSED_ONE_CHUNK 256   // contexts up to this long are one attention item per head (no merge across blocks)
 #endif
+static_assert(SPD_FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
 #ifndef SPD_BAR_SLEEP
 #define SPD_BAR_SLEEP 36           // s_sleep units (64 cycles) between two polls of the barrier
 #endif
@@ -203,7 +204,6 @@ struct Gemv {
     static constexpr int NS = U * P;
     static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U, "tile does not fit the register window");
     static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
-    static_assert(SPD_FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
 
     static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
 
