@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth
-from gpu_common import RTOL, compare_step, make_oracle, tails_of, teacher_forced
+from gpu_common import RTOL, assert_hit_paths_compared, plant_both_forms, compare_step, make_oracle, tails_of, teacher_forced
 from oracle import spd_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -19,10 +19,10 @@ def session(shape, weights, max_ctx=64, k_max=8):
     return P().Session(shape, weights, max_ctx=max_ctx, k_max=k_max)
 
 
-def planted_tables(shape, weights, base, prefix, k, n_tokens, seed=0):
+def planted_tables(shape, weights, base, prefix, k, n_tokens, seed=0, tau=1.0):
     """Insert n-grams along the paths an alpha = 0 oracle run visits, so lookups hit."""
     lm = make_oracle(shape, weights)
-    _, recs = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0), n_tokens)
+    _, recs = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0, tau), n_tokens)
     visits = []
     for rec in recs[1:]:
         for i in range(k):
@@ -92,11 +92,16 @@ def test_tiny_config_with_planted_hits(tiny, forward_path):
 
 @pytest.mark.parametrize("k", [1, 2, 5, 8])
 @pytest.mark.parametrize("alpha", [0.0, 0.54])
-def test_tiny_k_sweep_all_orders(tiny, k, alpha):
+@pytest.mark.parametrize("tau", [0.7, 0.06])
+def test_tiny_k_sweep_all_orders(tiny, k, alpha, tau):
+    """k from 1 to 8, with and without the n-gram stage, at a mild temperature and at the one the
+    paper tuned for its generation experiments (Appendix B, "Hyperparameter Choices": 0.06)."""
     shape, w, _, prefix = tiny
     base = synth.make_ngram_tables_zipf(shape.vocab, 40_000, seed=3)
-    planted = planted_tables(shape, w, base, prefix, k, 6, seed=k)
-    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, k, alpha, 6, tau=0.7)
+    planted = planted_tables(shape, w, base, prefix, k, 6, seed=k, tau=tau)
+    _, _, stats = run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, k, alpha, 6, tau=tau)
+    if alpha > 0 and k > 1:
+        assert_hit_paths_compared(stats)
 
 
 def test_bf16_small_model_gqa(forward_path):
@@ -105,7 +110,9 @@ def test_bf16_small_model_gqa(forward_path):
     prefix = synth.make_prefix_zipf(shape.vocab, 37, seed=5)
     base = synth.make_ngram_tables_zipf(shape.vocab, 30_000, seed=5)
     planted = planted_tables(shape, w, base, prefix, 3, 8)
-    run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8, path=forward_path)
+    _, _, stats = run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8, path=forward_path)
+    assert sum(bool(s.get("fully_compared")) for s in stats) == 8
+    assert_hit_paths_compared(stats, need_penalty=False)   # vocabulary of 2048: every draft finds some overlap
 
 
 def test_long_prefix_crosses_attention_chunks(forward_path):
@@ -172,8 +179,7 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
     base = synth.make_ngram_tables_zipf(shape.vocab, 100_000, seed=seed)
     lm = make_oracle(shape, host)
     _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0), n_tokens)
-    visits = [(tuple(r.state_in.history(i)), int(t)) for r in recs0[1:] for i in range(k) for t in r.top_ids]
-    tabs = synth.plant_ngrams(base, visits, shape.vocab, seed=seed + 1, frac=0.5)
+    tabs = plant_both_forms(base, recs0, k, shape.vocab, seed + 1)
     sess = pkg.Session(shape, wdev, max_ctx=prefix_len + n_tokens + 8, k_max=8)
     try:
         select_path(sess, forward_path)
@@ -182,8 +188,22 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
         cfg = O.DecodeCfg(k, alpha, 1.0, 0.1, synth.PAPER_LAMBDAS)
         _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, n_tokens, RTOL["bf16"], dc)
         print(shape.name, "scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats if "logit_err" in s])
+        report_decisions(shape.name, stats, n_tokens)
     finally:
         sess.close()
+
+
+def report_decisions(name, stats, n_steps):
+    """Every step's decision stage was compared exactly (on the GPU's own logits), and with the
+    planted tables both the interpolated and the penalty form of an option occurred."""
+    full = sum(bool(s.get("fully_compared")) for s in stats)
+    print(f"{name}: {full}/{n_steps} steps compared exactly on the GPU's own logits;",
+          "options in both distributions:", sum(s.get("own_overlap", 0) for s in stats),
+          "penalty form:", sum(s.get("own_penalty", 0) for s in stats),
+          "dropped:", sum(s.get("own_dropped", 0) for s in stats),
+          "| steps decisive against the oracle's logits:", sum(bool(s.get("vocab_decisive")) for s in stats))
+    assert full == n_steps
+    assert_hit_paths_compared(stats)
 
 
 @pytest.mark.timeout(600)
@@ -298,6 +318,11 @@ def test_generate_free_running_matches_until_first_undecided_step(tiny):
         if decided == len(recs):
             assert drafts.tolist() == state.drafts
             np.testing.assert_allclose(scores, state.logscores, atol=1e-3)
+        else:
+            # up to the first undecided step both sides hold the same set of drafts; whatever the
+            # GPU kept later descends from that set
+            upto = {tuple(d) for d in recs[decided].state_in.drafts}
+            assert {tuple(d[:decided]) for d in drafts.tolist()} <= upto
         # graph replay and plain launches agree bit for bit
         sess.spd_set_graph(False)
         drafts2, scores2 = sess.spd_generate(prefix, dc, 10)
@@ -478,8 +503,7 @@ def test_full_size_7b_shape_teacher_forced():
     base = synth.make_ngram_tables_zipf(shape.vocab, 200_000, seed=0)
     lm = make_oracle(shape, host)
     _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(3, 0.0), 3)
-    visits = [(tuple(r.state_in.history(i)), int(t)) for r in recs0[1:] for i in range(3) for t in r.top_ids]
-    tabs = synth.plant_ngrams(base, visits, shape.vocab, seed=1, frac=0.5)
+    tabs = plant_both_forms(base, recs0, 3, shape.vocab, 1)
     sess = pkg.Session(shape, wdev, max_ctx=128, k_max=8)
     try:
         assert sess.spd_get_fused()
@@ -489,5 +513,6 @@ def test_full_size_7b_shape_teacher_forced():
         _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, 3, RTOL["bf16"], dc)
         assert all("logit_err" in s for s in stats)
         print("7B scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats])
+        report_decisions("7B full size", stats, 3)
     finally:
         sess.close()

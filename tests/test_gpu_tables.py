@@ -75,7 +75,7 @@ def test_tables_replaced_between_timesteps(tiny):
         sess.spd_prefill(prefix)
         state, rec = O.first_step(lm.forward(lm.embedding_rows(prefix)), prefix, cfg)
         sess.spd_step_outputs = sess.spd_step(dc)
-        compare_step(sess, rec, dc, RTOL[shape.dtype], first=True)
+        compare_step(sess, rec, dc, RTOL[shape.dtype], first=True, cfg=cfg, otabs=O.NgramTables(tabs_a), prefix=prefix)
         seen = []
         for t in range(1, 6):
             if t == 3:
@@ -86,7 +86,7 @@ def test_tables_replaced_between_timesteps(tiny):
             sess.spd_set_state(tails_of(state), state.logscores)
             state, rec = O.expand_and_prune(state, lm.forward(x[None, :]), otabs, cfg, gamma_in=gamma)
             sess.spd_step_outputs = sess.spd_step(dc)
-            compare_step(sess, rec, dc, RTOL[shape.dtype], first=False)
+            compare_step(sess, rec, dc, RTOL[shape.dtype], first=False, cfg=cfg, otabs=otabs, prefix=prefix)
             seen.append(rec.pngram.copy())
         assert all(np.any(p > 0) for p in seen), "a timestep without any n-gram hit does not test the tables"
     finally:
