@@ -316,7 +316,7 @@ def main():
     drafts, scores = sess.spd_generate(prefix, dc, 10)
     e2e_ms = (time.perf_counter() - t2) * 1e3
 
-    # resets (Section 5.1): one of the k drafts is committed every s = 8 timesteps and its 8
+    # resets (Section 5.3): one of the k drafts is committed every s = 8 timesteps and its 8
     # tokens are passed again as ordinary prefix tokens; splice (Section 4.5): a one-draft nucleus
     # opening is committed, which passes only its newest token again
     def timed(f):

@@ -10,7 +10,7 @@
  *   their probabilities (Section 3, Eq. for D and P).
  * Around it: the pass over the prefix (Section 3, "First Timestep"; spd_prefill), one pass of
  * nucleus sampling on the same forward (the comparison decoder of Section 4.3;
- * spd_nucleus_step), and committing one draft to restart from it (resets, Section 5.1; a
+ * spd_nucleus_step), and committing one draft to restart from it (resets, Section 5.3; a
  * nucleus-sampled opening in front of Superposed Decoding, Section 4.5; spd_commit).
  *
  * Conventions
@@ -180,9 +180,9 @@ int spd_get_step_info(spd_ctx *ctx, int32_t *out_top_ids, float *out_top_logp,
  * not touch the KV cache or the position.  Does not synchronise. */
 int spd_expand_prune(spd_ctx *ctx, const spd_decode_cfg *dc, const float *dev_logits, int32_t first);
 
-/* Commit one draft and restart (Section 5.1, "Superposed Decoding Resets": every s timesteps
+/* Commit one draft and restart (Section 5.3, "Superposed Decoding Resets": every s timesteps
  * one of the k drafts is sampled and draft generation restarts; Section 4.5: a nucleus-sampled
- * generation serves as the prefix of a Superposed Decoding run, "spliced in at any timestep").
+ * generation of any length serves as the prefix of a Superposed Decoding run).
  * Draft i is sampled with its superposition weight gamma_i (Eq. 2) by inverse CDF over the
  * drafts in rank order with the caller's draw u in [0, 1); its tokens since the last
  * spd_prefill / spd_commit are appended to the text, the cache positions they occupy are
@@ -288,6 +288,20 @@ size_t spd_op_attention_scratch_bytes(int32_t n_heads, int32_t d_head, int32_t c
 int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V, float *out,
                      void *partials, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,
                      int32_t n_ctx, int32_t cap_ctx, void *hip_stream);
+
+/* ---- test hooks for the error path of the persistent kernel's bounded waits ----
+ * A wait of the persistent forward kernel that gives up (its grid was not co-resident) sets an
+ * error word in the device-side draft state; every entry point that copies that state back
+ * (spd_step, spd_generate, spd_commit, spd_nucleus_step, spd_get_state, spd_get_step_info,
+ * spd_get_nucleus_info) then returns SPD_EHIP.  spd_test_state_layout gives the size of that
+ * state in 32-bit words and the index of the error word; spd_test_state_status applies the
+ * library's check to a HOST copy of the state filled by the caller (host only, no GPU);
+ * spd_test_poke_err writes the device-side error word (a fill kernel on the ctx's stream, no
+ * synchronisation) so that the getters' mapping can be seen without any wait ever failing:
+ * spd_prefill clears it again. */
+int spd_test_state_layout(size_t *out_words, size_t *out_err_word);
+int spd_test_state_status(const int32_t *state_words, size_t n_words);
+int spd_test_poke_err(spd_ctx *ctx, int32_t value);
 
 const char *spd_last_error(const spd_ctx *ctx);
 const char *spd_strerror(int status);

@@ -388,9 +388,9 @@ def nucleus_generate(lm, prefix, top_p: float, tau: float, us, keep_logits: bool
 
 
 # ================================================================ resets and the splice
-# Section 5.1 ("Superposed Decoding Resets"): every s timesteps one of the k drafts is
+# Section 5.3 ("Superposed Decoding Resets"): every s timesteps one of the k drafts is
 # sampled and draft generation restarts from the text extended by it.  Section 4.5: a
-# nucleus-sampled generation can serve as the prefix at any timestep ("splice").  Both are
+# nucleus-sampled generation can serve as the prefix, whatever timestep it ends at.  Both are
 # "commit one draft, restart from the longer prefix".  Reading: the draft is sampled with its
 # superposition weight gamma_i = p_i / sum_j p_j (Eq. 2) -- the paper only says "sample" --
 # by inverse CDF over the drafts in rank order with a draw u in [0, 1) supplied by the caller.

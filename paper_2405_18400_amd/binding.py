@@ -89,6 +89,9 @@ def lib():
             "spd_set_fused": [vp, i32],
             "spd_get_fused": [vp, C.POINTER(i32)],
             "spd_get_kernel_timing": [vp, i32, C.POINTER(C.c_char_p), C.POINTER(f32), C.POINTER(C.c_int64), C.POINTER(i32)],
+            "spd_test_state_layout": [C.POINTER(sz), C.POINTER(sz)],
+            "spd_test_state_status": [vp, sz],
+            "spd_test_poke_err": [vp, i32],
             "spd_op_gemv": [i32, vp, vp, f32, vp, vp, vp, i32, i32, vp],
             "spd_op_swiglu": [i32, vp, vp, vp, f32, vp, vp, i32, i32, vp],
             "spd_op_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
@@ -314,6 +317,9 @@ class Session:
         assert dev_logits.is_cuda and dev_logits.dtype == _torch().float32 and dev_logits.numel() == self.shape.vocab
         self._chk(self.L.spd_expand_prune(self.ctx, C.byref(dc), dev_logits.data_ptr(), int(first)), "spd_expand_prune")
 
+    def spd_test_poke_err(self, value: int):
+        self._chk(self.L.spd_test_poke_err(self.ctx, int(value)), "spd_test_poke_err")
+
     def spd_position(self) -> int:
         out = C.c_int32(0)
         self._chk(self.L.spd_position(self.ctx, C.byref(out)), "spd_position")
@@ -384,3 +390,16 @@ def spd_op_attention(dtype: str, q, K, V, out, n_ctx: int):
     if rc:
         raise SpdError(rc, "spd_op_attention")
     torch.cuda.current_stream().synchronize()   # scratch must outlive the kernel
+
+
+def spd_test_state_layout():
+    words, err_word = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().spd_test_state_layout(C.byref(words), C.byref(err_word))
+    if rc:
+        raise SpdError(rc, "spd_test_state_layout")
+    return words.value, err_word.value
+
+
+def spd_test_state_status(state_words) -> int:
+    a = np.ascontiguousarray(state_words, dtype=np.int32)
+    return lib().spd_test_state_status(_np_ptr(a), a.size)

@@ -4,6 +4,8 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -20,22 +22,30 @@ def hipcc() -> str:
 
 
 def build_library(verbose: bool = False, out: str = LIB) -> str:
-    """Always recompiles.  -ffp-contract=off: the kernels spell out every fused
-    multiply-add they want; packed-fp32 instruction selection is disabled."""
-    cmd = [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
-    cmd += os.environ.get("SPD_EXTRA_DEFS", "").split()      # experiments only, e.g. -DSPD_FUSED_NT=512
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", out]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    """Always recompiles: every source to an object file (in parallel), then one link.
+    -ffp-contract=off: the kernels spell out every fused multiply-add they want;
+    packed-fp32 instruction selection is disabled."""
+    flags = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     noise = "is not a recognized feature for this target"
-    log = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if noise not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + log)
-    if verbose and log.strip():
-        print(log)
+    logs = []
+
+    def run(cmd):
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        log = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if noise not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + log)
+        logs.append(log)
+
+    with tempfile.TemporaryDirectory(prefix="spd_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            list(pool.map(lambda so: run([hipcc(), *flags, "-x", "hip", "-c", os.path.join(CSRC, so[0]), "-o", so[1]]),
+                          zip(SOURCES, objs)))
+        run([hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", *objs, "-o", out])
+    if verbose and any(l.strip() for l in logs):
+        print("\n".join(l for l in logs if l.strip()))
     return out
 
 

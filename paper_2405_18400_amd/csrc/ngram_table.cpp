@@ -1,5 +1,5 @@
 // Host-side construction of the device n-gram store: one exact-key open-addressing table
-// holding every n-gram's count (Section 4: "each unique n-gram and its corresponding count")
+// holding every n-gram's count (the frequency tables of Section 4: one entry per distinct n-gram)
 // plus, per distinct context, the sum of the counts of its continuations -- the denominator of
 // p_{n-gram}(x | context) = count(context, x) / sum_x' count(context, x').
 #include "spd_internal.h"

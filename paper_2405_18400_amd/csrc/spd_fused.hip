@@ -20,39 +20,20 @@ namespace {
 // One block per CU (few barrier participants).  With 512 threads: 8 waves that read one matrix
 // row side by side and have 256 vector registers each, i.e. room for a 16 KB weight tile in
 // flight per wave.  (1024 threads = two such row groups with half the registers.)
-#ifndef SPD_FUSED_NT
-#define SPD_FUSED_NT 512
-#endif
-#ifndef SPD_FUSED_UA
-#define SPD_FUSED_UA 16           // rows per tile where one pass covers a row
-#endif
-#ifndef SPD_FUSED_UO_EXTRA
-#define SPD_FUSED_UO_EXTRA 4      // extra rows per tile of the O projection
-#endif
-#ifndef SPD_FUSED_QD
-#define SPD_FUSED_QD 12           // 16-byte pieces per lane of the next tile requested while the block synchronises
-#endif
-#ifndef SPD_FUSED_SLICE
-#define SPD_FUSED_SLICE 3         // of which this many go out per synchronisation step of wave 0
-#endif
-#ifndef SPD_FUSED_SLICE_WIDE
-#define SPD_FUSED_SLICE_WIDE 4    // the same for models whose d_model takes two block passes (measured: 3 costs the
-#endif                            //   13B shape 0.3 % and the 70B shape 1 %, and gains the 7B shape 0.1...0.6 %)
-#ifndef SPD_FUSED_ONE_CHUNK
-#define SPD_FUSED_ONE_CHUNK 256   // contexts up to this long are one attention item per head (no merge across blocks)
-#endif
-static_assert(SPD_FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
-#ifndef SPD_BAR_SLEEP
-#define SPD_BAR_SLEEP 36           // s_sleep units (64 cycles) between two polls of the barrier
-#endif
-#ifndef SPD_BAR_SLEEP_WIDE
-#define SPD_BAR_SLEEP_WIDE 48      // the same where d_ffn takes more than four block passes (the 70B shape: long
-#endif                             //   phases, and 36 costs it 0.3 %; the 7B and 13B shapes gain 0.4 and 0.2 %)
-#ifndef SPD_QKV_SLEEP
-#define SPD_QKV_SLEEP 1            // the same between two polls of a head's arrival counter
-#endif
-constexpr int NT = SPD_FUSED_NT;  // threads per block
-constexpr int NW = 8;             // waves side by side on one row
+constexpr int FUSED_UA = 16;          // rows per tile where one pass covers a row
+constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
+constexpr int FUSED_QD = 12;          // 16-byte pieces per lane of the next tile requested while the block synchronises
+constexpr int FUSED_SLICE = 3;        // of which this many go out per synchronisation step of wave 0
+constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes (measured: 3 costs the
+                                      //   13B shape 0.3 % and the 70B shape 1 %, and gains the 7B shape 0.1...0.6 %)
+constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
+static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
+constexpr int BAR_SLEEP_7B = 36;      // s_sleep units (64 cycles) between two polls of the barrier
+constexpr int BAR_SLEEP_WIDE = 48;    // the same where d_ffn takes more than four block passes (the 70B shape: long
+                                      //   phases, and 36 costs it 0.3 %; the 7B and 13B shapes gain 0.4 and 0.2 %)
+constexpr int QKV_SLEEP = 1;          // the same between two polls of a head's arrival counter
+constexpr int NT = 512;               // threads per block
+constexpr int NW = 8;                 // waves side by side on one row
 constexpr int MAX_U = 32;
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
@@ -228,7 +209,7 @@ struct Gemv {
 
     // The head of this block's first tile, pieces [0, QD), is requested before the phase
     // starts; the rest follows the load of x.
-    static constexpr int QD = NS < SPD_FUSED_QD ? NS : SPD_FUSED_QD;
+    static constexpr int QD = NS < FUSED_QD ? NS : FUSED_QD;
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
@@ -450,7 +431,7 @@ __device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned t
     if (threadIdx.x == 0) {
         unsigned spins = 0;
         while (__hip_atomic_load(as_global(sync) + 64 * kv_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(SPD_QKV_SLEEP);
+            __builtin_amdgcn_s_sleep(QKV_SLEEP);
             ++spins;
             if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             if (spins > SPIN_LIMIT) {
@@ -471,18 +452,18 @@ __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
 
 // PA / PB: passes a block needs to cover d_model / d_ffn columns.  Rows per tile follow from
 // them so that a tile stays at about 16 pieces (16 bytes each) per lane.
-constexpr int tile_rows(int passes) { return passes == 1 ? SPD_FUSED_UA : passes == 2 ? SPD_FUSED_UA / 2 : passes <= 4 ? 4 : 2; }
+constexpr int tile_rows(int passes) { return passes == 1 ? FUSED_UA : passes == 2 ? FUSED_UA / 2 : passes <= 4 ? 4 : 2; }
 
 template <typename WT, int PA, int PB>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int UA = tile_rows(PA), UB = tile_rows(PB);
     // The O projection is one tile per block; its tile is a little taller so that it still is
     // when the blocks busy with attention items leave their rows to the others.
-    constexpr int UO = UA + SPD_FUSED_UO_EXTRA / PA;
+    constexpr int UO = UA + FUSED_UO_EXTRA / PA;
     constexpr int NA = PA * UO;
     constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
-    constexpr int SL = PA == 1 ? SPD_FUSED_SLICE : SPD_FUSED_SLICE_WIDE;
-    constexpr int BAR_SLEEP = PB > 4 ? SPD_BAR_SLEEP_WIDE : SPD_BAR_SLEEP;
+    constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
+    constexpr int BAR_SLEEP = PB > 4 ? BAR_SLEEP_WIDE : BAR_SLEEP_7B;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL>;
@@ -541,7 +522,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
         // Attention items: one per (query head, chunk of cached positions).  Up to
-        // SPD_FUSED_ONE_CHUNK positions a head is ONE item (one or two batches of loads in one
+        // FUSED_ONE_CHUNK positions a head is ONE item (one or two batches of loads in one
         // block): a second batch costs about 2 us, merging chunks across blocks about 4 us (an
         // acknowledged store, an atomic and two dependent loads), but one compute unit's share
         // of the bandwidth makes a single block the slower choice past some 270 positions.
@@ -549,8 +530,8 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         // While few blocks have an item those take no rows of the O projection: they would hold
         // everybody up fetching their tile after the attention.
         const int n_ctx = pos + 1;
-        int chunk = SPD_FUSED_ONE_CHUNK;
-        if (n_ctx > SPD_FUSED_ONE_CHUNK) {
+        int chunk = FUSED_ONE_CHUNK;
+        if (n_ctx > FUSED_ONE_CHUNK) {
             const int per_head = max(1, (int)gridDim.x / a.n_heads);
             chunk = ((n_ctx + per_head - 1) / per_head + 15) & ~15;
             chunk = min(ATTN_CHUNK_MAX, max(ATTN_CHUNK_MIN, chunk));

@@ -186,10 +186,7 @@ struct FusedArgsHost {
 
 // One chunk of the dense prefix pass (bf16 weights): T <= PREFILL_CHUNK prefix tokens at
 // positions p0 .. p0 + T - 1.  Arena buffers are DEVICE, sized for PREFILL_CHUNK rows.
-#ifndef SPD_PREFILL_CHUNK
-#define SPD_PREFILL_CHUNK 1024
-#endif
-constexpr int PREFILL_CHUNK = SPD_PREFILL_CHUNK;
+constexpr int PREFILL_CHUNK = 1024;
 struct PrefillChunk {
     const void *embed;
     const int32_t *prefix;             // DEVICE token ids of the whole prefix
@@ -210,14 +207,8 @@ struct PrefillChunk {
 
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
-#ifndef SPD_BAR_GROUP
-#define SPD_BAR_GROUP 128
-#endif
-constexpr int BAR_GROUP = SPD_BAR_GROUP;          // blocks per group of the two-level device-wide barrier
-#ifndef SPD_BAR_TOPS
-#define SPD_BAR_TOPS 2
-#endif
-constexpr int BAR_TOPS = SPD_BAR_TOPS;            // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
+constexpr int BAR_GROUP = 128;         // blocks per group of the two-level device-wide barrier
+constexpr int BAR_TOPS = 2;           // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
 constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
 constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
 constexpr int BAR_LAYER_WORD = BAR_EPOCH_WORD + 16;         // layers passed by all launches since the last reset
@@ -226,10 +217,7 @@ constexpr int QKV_SYNC_MAX = 64;        // (one lane of a wave per head)
 constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS + QKV_SYNC_MAX);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
-#ifndef SPD_ATTN_CHUNK_MIN
-#define SPD_ATTN_CHUNK_MIN 64
-#endif
-constexpr int ATTN_CHUNK_MIN = SPD_ATTN_CHUNK_MIN;     // the fused kernel picks the chunk per step within these bounds
+constexpr int ATTN_CHUNK_MIN = 64;    // the fused kernel picks the chunk per step within these bounds
 constexpr int ATTN_CHUNK_MAX = 512;
 
 namespace spdk {
@@ -249,6 +237,11 @@ hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);
 int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn);
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &a, int blocks);
 hipError_t init();  // raise the dynamic-LDS limit of the kernels that need it
+// stand-alone attention: argument check (an spd_status) and the launch on a given scratch buffer
+int attention_args_status(int dtype, const float *q, const void *K, const void *V, const float *out, int n_heads,
+                          int n_kv_heads, int d_head, int n_ctx, int cap_ctx);
+int attention_on_scratch(hipStream_t s, int dtype, const float *q, const void *K, const void *V, float *out,
+                         void *scratch, int n_heads, int n_kv_heads, int d_head, int n_ctx, int cap_ctx);
 }  // namespace spdk
 
 // ---------------------------------------------------------------- host-side table builder

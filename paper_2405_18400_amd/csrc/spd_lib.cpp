@@ -3,6 +3,7 @@
 #include "spd_internal.h"
 
 #include <cmath>
+#include <cstddef>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -50,6 +51,15 @@ const char *check_cfg(const spd_model_cfg *c) {
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return "rms_eps and rope_theta must be positive";
     const int widest = c->d_model > c->d_ffn ? c->d_model : c->d_ffn;
     if (spdk::gemv_lds_bytes(c->dtype, widest) > 160 * 1024 - 1024) return "d_model / d_ffn too large for the LDS staging";
+    // The persistent kernel's arrival counters are 32-bit and count on from launch to launch
+    // until the next prefix pass zeroes them; at most max_ctx launches lie between two prefix
+    // passes.  Barrier groups count BAR_GROUP arrivals per barrier (at most 5 per layer + 2),
+    // the per-head counters one per row pair of a head's q, k and v rows per layer.
+    const uint64_t launches = (uint64_t)c->max_ctx;
+    const uint64_t per_head = (uint64_t)(c->n_heads / c->n_kv_heads + 2) * (uint64_t)(dh / 2);
+    if (launches * (uint64_t)(5 * c->n_layers + 2) * BAR_GROUP >= (1ull << 32) ||
+        launches * (uint64_t)c->n_layers * per_head >= (1ull << 32))
+        return "max_ctx too large for the 32-bit arrival counters of the persistent kernel";
     return nullptr;
 }
 
@@ -158,6 +168,19 @@ int hipfail(spd_ctx *c, hipError_t e, const char *what) {
     do {                                                        \
         hipError_t e_ = (call);                                 \
         if (e_ != hipSuccess) return hipfail((c), e_, #call);   \
+    } while (0)
+
+// Every entry point that copies the draft state back from the device passes the copy through
+// here: a bounded wait of the persistent kernel that gave up (the grid was not co-resident)
+// leaves `err` set, and whatever the launch produced after that is not a result.
+int device_state_status(spd_ctx *c, const DevState *hs) {
+    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    return SPD_OK;
+}
+#define STATECHK(c, hs)                                          \
+    do {                                                         \
+        const int rc_ = device_state_status((c), (hs));          \
+        if (rc_ != SPD_OK) return rc_;                           \
     } while (0)
 
 // Launch helper: plain, or bracketed by an event pair when per-kernel timing is on.
@@ -319,6 +342,33 @@ bool graphs_usable(const spd_ctx *c) { return c->use_graph && !c->timing && c->s
 
 }  // namespace
 
+// Shared by spd_op_attention and its variant on the library's static scratch.
+namespace spdk {
+int attention_args_status(int dtype, const float *q, const void *K, const void *V, const float *out, int n_heads,
+                          int n_kv_heads, int d_head, int n_ctx, int cap_ctx) {
+    if (!q || !K || !V || !out) return SPD_EINVAL;
+    if (dtype != SPD_DTYPE_FP32 && dtype != SPD_DTYPE_BF16) return SPD_EINVAL;
+    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    if (n_heads <= 0 || n_kv_heads <= 0 || n_heads % n_kv_heads || d_head <= 0 || d_head % vec || d_head > 256) return SPD_EINVAL;
+    const int lpp = d_head / vec;
+    if (lpp > 64 || (lpp & (lpp - 1))) return SPD_EINVAL;
+    if (n_ctx < 1 || n_ctx > cap_ctx) return SPD_EINVAL;
+    return SPD_OK;
+}
+
+// `scratch`: DEVICE, 256-byte aligned, spd_op_attention_scratch_bytes() bytes: the heads'
+// arrival counters (cleared here, by a fill kernel) followed by the chunks' partial results.
+int attention_on_scratch(hipStream_t s, int dtype, const float *q, const void *K, const void *V, float *out,
+                         void *scratch, int n_heads, int n_kv_heads, int d_head, int n_ctx, int cap_ctx) {
+    int32_t *counters = (int32_t *)scratch;
+    float *part = (float *)((char *)scratch + up((size_t)n_heads * ATTN_COUNTER_STRIDE * 4));
+    if (fill_i32(s, counters, 0, n_heads * ATTN_COUNTER_STRIDE) != hipSuccess) return SPD_EHIP;
+    AttnArgs a{q, K, V, out, part, counters, nullptr, n_ctx, n_heads, n_kv_heads, d_head, cap_ctx, ATTN_CHUNK,
+               (cap_ctx + ATTN_CHUNK - 1) / ATTN_CHUNK};
+    return attention(s, dtype, a) == hipSuccess ? SPD_OK : SPD_EHIP;
+}
+}  // namespace spdk
+
 // =============================================================================== C ABI
 extern "C" {
 
@@ -475,6 +525,9 @@ static int run_prefix_pass(spd_ctx *c, int p0, int m) {
     HIPCHK(c, hipMemcpyAsync(c->st(), hs, sizeof(DevState), hipMemcpyHostToDevice, c->stream));
     // the persistent kernel's barrier counters run on from launch to launch within a generation
     HIPCHK(c, spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, BAR_WORDS));
+    // (and the chunk-arrival counters of the attention merge: a launch that gave up on a wait
+    // may have left some of them short of the count that resets them)
+    HIPCHK(c, spdk::fill_i32(c->stream, c->at<int32_t>(c->L.counters), 0, c->cfg.n_heads * ATTN_COUNTER_STRIDE));
     HIPCHK(c, hipMemcpyAsync(c->ws + c->L.prefix + (size_t)p0 * 4, hp, (size_t)(m - p0) * 4, hipMemcpyHostToDevice, c->stream));
     c->state = ST_CREATED;
     c->pos = p0; c->n_gen = 0; c->k = 0;
@@ -546,7 +599,7 @@ static int copy_step_outputs(spd_ctx *c, int k, int32_t *out_tok, int32_t *out_p
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    STATECHK(c, hs);
     for (int i = 0; i < k; ++i) {
         if (out_tok) out_tok[i] = hs->new_tok[i];
         if (out_par) out_par[i] = hs->new_parent[i];
@@ -606,7 +659,7 @@ int spd_commit(spd_ctx *c, float u, int32_t *out_chosen, int32_t *out_tokens, in
     HIPCHK(c, hipMemcpyAsync(hp, c->ws + c->L.hist_par, hist_bytes, hipMemcpyDeviceToHost, c->stream));
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    STATECHK(c, hs);
     // sample draft i with its superposition weight (Eq. 2): inverse CDF over the rank order
     double total = 0.0;
     for (int i = 0; i < k; ++i) total += (double)hs->gamma[i];
@@ -678,7 +731,7 @@ int spd_nucleus_step(spd_ctx *c, const spd_sample_cfg *sc, float u, int32_t *out
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (hs->err) return fail(c, SPD_EHIP, "device-wide barrier timed out (grid not co-resident)");
+    STATECHK(c, hs);
     if (out_tok) *out_tok = hs->new_tok[0];
     if (out_logprob) *out_logprob = hs->top_logp[0];
     return SPD_OK;
@@ -714,6 +767,7 @@ int spd_get_nucleus_info(spd_ctx *c, int32_t *out_size, float *out_mass, float *
     DevState *hs = (DevState *)c->pinned;
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    STATECHK(c, hs);
     if (out_size) *out_size = hs->nucleus_size;
     if (out_mass) *out_mass = hs->nucleus_mass;
     if (out_sum_logprob) *out_sum_logprob = hs->logscore[0];
@@ -743,6 +797,7 @@ int spd_generate(spd_ctx *c, const int32_t *prefix, int32_t m, const spd_decode_
     HIPCHK(c, hipMemcpyAsync(hp, c->ws + c->L.hist_par, hist_bytes, hipMemcpyDeviceToHost, c->stream));
     if (c->timing) HIPCHK(c, drain_timing(c));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    STATECHK(c, hs);
     for (int r = 0; r < k; ++r) {   // walk the parent indices back from the last timestep
         int slot = r;
         for (int t = n_tokens - 1; t >= 0; --t) {
@@ -762,6 +817,7 @@ int spd_get_state(spd_ctx *c, int32_t *out_k, int32_t *out_tails, float *out_sc,
     DevState *hs = (DevState *)c->pinned;
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    STATECHK(c, hs);
     if (out_k) *out_k = c->k;
     for (int i = 0; i < c->k; ++i) {
         if (out_tails) std::memcpy(out_tails + i * SPD_TAIL, hs->tails[i], SPD_TAIL * 4);
@@ -812,6 +868,7 @@ int spd_get_step_info(spd_ctx *c, int32_t *top_ids, float *top_logp, float *cs, 
     DevState *hs = (DevState *)c->pinned;
     HIPCHK(c, hipMemcpyAsync(hs, c->st(), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    STATECHK(c, hs);
     const int k = c->k;
     for (int i = 0; i < k; ++i) {
         if (top_ids) top_ids[i] = hs->top_ids[i];
@@ -840,6 +897,26 @@ int spd_expand_prune(spd_ctx *c, const spd_decode_cfg *dc, const float *dev_logi
     if (c->n_gen >= c->cfg.max_ctx) return fail(c, SPD_ECTX_OVERFLOW, "token history is full");
     HIPCHK(c, enqueue_decide(c, *dc, dev_logits, 0, 0));
     c->n_gen += 1;
+    return SPD_OK;
+}
+
+int spd_test_state_status(const int32_t *state_words, size_t n_words) {
+    if (!state_words || n_words * 4 < sizeof(DevState)) return SPD_EINVAL;
+    DevState hs;
+    std::memcpy(&hs, state_words, sizeof(DevState));
+    return device_state_status(nullptr, &hs);
+}
+
+int spd_test_state_layout(size_t *out_words, size_t *out_err_word) {
+    if (!out_words || !out_err_word) return SPD_EINVAL;
+    *out_words = (sizeof(DevState) + 3) / 4;
+    *out_err_word = offsetof(DevState, err) / 4;
+    return SPD_OK;
+}
+
+int spd_test_poke_err(spd_ctx *c, int32_t value) {
+    if (!c) return SPD_EINVAL;
+    HIPCHK(c, spdk::fill_i32(c->stream, &c->st()->err, value, 1));
     return SPD_OK;
 }
 
@@ -966,20 +1043,11 @@ size_t spd_op_attention_scratch_bytes(int32_t n_heads, int32_t d_head, int32_t c
 int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V, float *out, void *scratch,
                      int32_t n_heads, int32_t n_kv_heads, int32_t d_head, int32_t n_ctx, int32_t cap_ctx,
                      void *hip_stream) {
-    if (!q || !K || !V || !out || !scratch) return SPD_EINVAL;
-    if (dtype != SPD_DTYPE_FP32 && dtype != SPD_DTYPE_BF16) return SPD_EINVAL;
-    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
-    if (n_heads <= 0 || n_kv_heads <= 0 || n_heads % n_kv_heads || d_head <= 0 || d_head % vec || d_head > 256) return SPD_EINVAL;
-    const int lpp = d_head / vec;
-    if (lpp > 64 || (lpp & (lpp - 1))) return SPD_EINVAL;
-    if (n_ctx < 1 || n_ctx > cap_ctx || ((uintptr_t)scratch & (ALIGN - 1))) return SPD_EINVAL;
-    hipStream_t s = (hipStream_t)hip_stream;
-    int32_t *counters = (int32_t *)scratch;
-    float *part = (float *)((char *)scratch + up((size_t)n_heads * ATTN_COUNTER_STRIDE * 4));
-    if (spdk::fill_i32(s, counters, 0, n_heads * ATTN_COUNTER_STRIDE) != hipSuccess) return SPD_EHIP;
-    AttnArgs a{q, K, V, out, part, counters, nullptr, n_ctx, n_heads, n_kv_heads, d_head, cap_ctx, ATTN_CHUNK,
-               (cap_ctx + ATTN_CHUNK - 1) / ATTN_CHUNK};
-    return spdk::attention(s, dtype, a) == hipSuccess ? SPD_OK : SPD_EHIP;
+    const int rc = spdk::attention_args_status(dtype, q, K, V, out, n_heads, n_kv_heads, d_head, n_ctx, cap_ctx);
+    if (rc != SPD_OK) return rc;
+    if (!scratch || ((uintptr_t)scratch & (ALIGN - 1))) return SPD_EINVAL;
+    return spdk::attention_on_scratch((hipStream_t)hip_stream, dtype, q, K, V, out, scratch, n_heads, n_kv_heads,
+                                      d_head, n_ctx, cap_ctx);
 }
 
 }  // extern "C"

@@ -765,23 +765,14 @@ namespace spdk {
 size_t prefill_attn_lds(int d_head) { return (size_t)(AQ * (d_head + 4) + AK * (d_head + 4) + AK * d_head + AQ * (AK + 1)) * sizeof(float); }
 
 // Launch with the widest column tile that still gives every compute unit a block.
-#ifndef SPD_GEMM_TT
-#define SPD_GEMM_TT 2
-#endif
-constexpr int GEMM_TT = SPD_GEMM_TT;
-#ifndef SPD_SWIGLU_TT
-#define SPD_SWIGLU_TT 2
-#endif
-constexpr int SWIGLU_TT = SPD_SWIGLU_TT;  // the same for gate and up side by side
+constexpr int GEMM_TT = 2;
+constexpr int SWIGLU_TT = 2;  // the same for gate and up side by side
 
 static size_t skinny_lds(int nmat, int nwv) {
     const size_t tiles = (size_t)nwv * nmat * 32 * W_ROW, red = (size_t)nwv * nmat * 16 * 64 * sizeof(float);
     return tiles > red ? tiles : red;
 }
-#ifndef SPD_SKINNY_MAX_T
-#define SPD_SKINNY_MAX_T 96
-#endif
-constexpr int SKINNY_MAX_T = SPD_SKINNY_MAX_T;      // up to here the split-k kernel is the faster one
+constexpr int SKINNY_MAX_T = 96;      // up to here the split-k kernel is the faster one
 
 template <int EPI, int TT>
 static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {

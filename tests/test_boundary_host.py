@@ -99,3 +99,36 @@ def test_entry_points_exist():
     import importlib
     ge = importlib.import_module("__graft_entry__")
     assert callable(ge.build) and callable(ge.smoke)
+
+
+def test_device_error_word_maps_to_ehip(pkg):
+    """A bounded wait of the persistent kernel that gives up leaves an error word in the
+    device-side draft state; the one function every entry point passes its host copy of that
+    state through turns it into SPD_EHIP.  Host only: the state is filled by hand here."""
+    words, err_word = pkg.spd_test_state_layout()
+    assert words > 100 and 0 <= err_word < 8
+    state = np.zeros(words, np.int32)
+    assert pkg.spd_test_state_status(state) == 0
+    state[:] = np.arange(words) % 7                   # whatever the other fields hold ...
+    state[err_word] = 0
+    assert pkg.spd_test_state_status(state) == 0      # ... only the error word decides
+    for bad in (1, -1, 12345):
+        state[err_word] = bad
+        assert pkg.spd_test_state_status(state) == -6
+        assert "HIP" in pkg.spd_strerror(-6)
+    assert pkg.spd_test_state_status(state[: words - 1]) == -1    # too short a copy is refused
+    assert pkg.lib().spd_test_state_status(None, words) == -1
+
+
+def test_max_ctx_is_bounded_by_the_32_bit_arrival_counters(pkg):
+    """The persistent kernel's arrival counters count on from launch to launch between two
+    prefix passes: a context so long that they could wrap is refused when the context is
+    sized, not found out at run time."""
+    ok = pkg.binding.model_cfg(synth.LLAMA7B, 200_000, 8)
+    assert pkg.spd_workspace_bytes(ok) > 0
+    with pytest.raises(pkg.SpdError) as e:
+        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA7B, 210_000, 8))     # 162 barriers x 128 arrivals x 210k launches > 2^32
+    assert e.value.code == -1
+    with pytest.raises(pkg.SpdError):
+        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 84_000, 8))
+    assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 83_000, 8)) > 0

@@ -1,4 +1,4 @@
-"""Committing a draft and restarting (resets, Section 5.1; nucleus pass spliced in front of
+"""Committing a draft and restarting (resets, Section 5.3; nucleus pass spliced in front of
 Superposed Decoding, Section 4.5) on the GPU against the oracle, through the C ABI."""
 import numpy as np
 import pytest

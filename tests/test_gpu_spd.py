@@ -516,3 +516,29 @@ def test_full_size_7b_shape_teacher_forced():
         report_decisions("7B full size", stats, 3)
     finally:
         sess.close()
+
+
+def test_device_error_word_reaches_the_caller(tiny):
+    """The getters (and every call that fetches results) report SPD_EHIP once the device-side
+    error word is set; here it is written by a fill kernel after the work has finished -- no
+    wait fails, no kernel runs while it is set -- and the next prefix pass clears it."""
+    shape, w, _, prefix = tiny
+    pkg = P()
+    sess = session(shape, w)
+    try:
+        dc = pkg.SpdDecodeCfg(3, 0.0, 1.0, 0.1)
+        sess.spd_prefill(prefix)
+        sess.spd_step(dc)
+        sess.spd_step(dc)
+        sess.spd_get_state()
+        sess.spd_test_poke_err(1)
+        for call in (sess.spd_get_state, lambda: sess.spd_get_step_info(3)):
+            with pytest.raises(pkg.SpdError) as e:
+                call()
+            assert e.value.code == -6 and "barrier" in str(e.value)
+        sess.spd_prefill(prefix)
+        tok, par, sc = sess.spd_step(dc)
+        assert len(tok) == 3
+        sess.spd_get_state()
+    finally:
+        sess.close()

@@ -14,7 +14,7 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden", "hyperparameters.txt")
 
 
 def corpus_tables(corpus, orders=range(2, 7)):
-    """Frequency tables built the way Section 4 describes: each unique n-gram and its count."""
+    """Frequency tables built the way Section 4 describes: one entry per distinct n-gram, holding how often it occurs."""
     tabs = {}
     for n in orders:
         c = Counter(tuple(corpus[i:i + n]) for i in range(len(corpus) - n + 1))

@@ -1,4 +1,4 @@
-"""Pins for the oracle's reset / splice operations (Sections 5.1 and 4.5)."""
+"""Pins for the oracle's reset / splice operations (Sections 5.3 and 4.5)."""
 import numpy as np
 
 import synth
