@@ -289,6 +289,20 @@ int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V
                      void *partials, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,
                      int32_t n_ctx, int32_t cap_ctx, void *hip_stream);
 
+/* spd_op_attention for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same computation with
+ * the scratch in a static device array of SPD_STATIC_SCRATCH_BYTES inside the library instead
+ * of a caller-supplied buffer.  The call allocates nothing.  Shapes whose
+ * spd_op_attention_scratch_bytes(n_heads, d_head, cap_ctx) exceeds SPD_STATIC_SCRATCH_BYTES are
+ * refused with SPD_EWORKSPACE before any GPU work.  Each GPU holds one such array for the life
+ * of the process and every call on that GPU uses it: calls on one stream are ordered (each
+ * clears the counters it needs with a fill kernel), calls that overlap on one GPU (other
+ * streams, other threads) race and must be serialised by the caller.  Does not synchronise. */
+#define SPD_STATIC_SCRATCH_BYTES (4u << 20)
+int spd_op_attention_static(int32_t dtype, const float *q, const void *K, const void *V, float *out,
+                            int32_t n_heads, int32_t n_kv_heads, int32_t d_head, int32_t n_ctx,
+                            int32_t cap_ctx, void *hip_stream);
+
 /* ---- test hooks for the error path of the persistent kernel's bounded waits ----
  * A wait of the persistent forward kernel that gives up (its grid was not co-resident) sets an
  * error word in the device-side draft state; every entry point that copies that state back

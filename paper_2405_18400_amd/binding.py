@@ -95,6 +95,7 @@ def lib():
             "spd_op_gemv": [i32, vp, vp, f32, vp, vp, vp, i32, i32, vp],
             "spd_op_swiglu": [i32, vp, vp, vp, f32, vp, vp, i32, i32, vp],
             "spd_op_attention": [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+            "spd_op_attention_static": [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -390,6 +391,16 @@ def spd_op_attention(dtype: str, q, K, V, out, n_ctx: int):
     if rc:
         raise SpdError(rc, "spd_op_attention")
     torch.cuda.current_stream().synchronize()   # scratch must outlive the kernel
+
+
+def spd_op_attention_static(dtype: str, q, K, V, out, n_ctx: int):
+    """The same on the library's static scratch: no allocation here or in the library."""
+    n_heads, d_head = q.shape
+    n_kv, cap_ctx, _ = K.shape
+    rc = lib().spd_op_attention_static(SPD_DTYPE[dtype], q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+                                       n_heads, n_kv, d_head, n_ctx, cap_ctx, _stream_ptr())
+    if rc:
+        raise SpdError(rc, "spd_op_attention_static")
 
 
 def spd_test_state_layout():

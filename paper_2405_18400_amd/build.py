@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspd.so")
-SOURCES = ["spd_kernels.hip", "spd_fused.hip", "spd_sampler.hip", "spd_prefill.hip", "spd_lib.cpp", "ngram_table.cpp"]
+SOURCES = ["spd_kernels.hip", "spd_fused.hip", "spd_sampler.hip", "spd_prefill.hip", "spd_noalloc.hip", "spd_lib.cpp", "ngram_table.cpp"]
 
 
 def hipcc() -> str:

@@ -132,3 +132,18 @@ def test_max_ctx_is_bounded_by_the_32_bit_arrival_counters(pkg):
     with pytest.raises(pkg.SpdError):
         pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 84_000, 8))
     assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 83_000, 8)) > 0
+
+
+def test_static_scratch_variant_refuses_oversized_shapes_before_any_gpu_work(pkg):
+    """spd_op_attention_static: argument errors and a scratch need beyond the static array are
+    refused on the host (no GPU is touched: this runs without one)."""
+    L = pkg.lib()
+    dummy = C.c_void_p(256)
+    need = L.spd_op_attention_scratch_bytes(64, 128, 8192)
+    assert need <= 4 << 20
+    assert L.spd_op_attention_scratch_bytes(64, 128, 32768) > 4 << 20
+    assert L.spd_op_attention_static(1, dummy, dummy, dummy, dummy, 64, 8, 128, 100, 32768, None) == -4
+    assert L.spd_op_attention_static(1, None, dummy, dummy, dummy, 8, 8, 128, 10, 64, None) == -1
+    assert L.spd_op_attention_static(1, dummy, dummy, dummy, dummy, 8, 3, 128, 10, 64, None) == -1
+    assert L.spd_op_attention_static(1, dummy, dummy, dummy, dummy, 8, 8, 128, 65, 64, None) == -1
+    assert L.spd_op_attention_static(5, dummy, dummy, dummy, dummy, 8, 8, 128, 10, 64, None) == -1
