@@ -40,68 +40,90 @@ def algorithmic_bytes(shape, ctx_positions: float) -> dict:
             "step": shape.n_layers * (qkv + o + gateup + down) + head + kv_pos * ctx_positions}
 
 
-def recorded_traffic(workload: str, k: int):
+def recorded_traffic(workload: str, k: int, prefix: int):
     """HBM bytes per launch of the fused forward kernel as counted by rocprofv3 (FETCH_SIZE +
     WRITE_SIZE, scaled by a plain copy): taken from the committed counter summary of this
-    workload, since counters cannot be read from inside the benchmark.  None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"spd_step_{workload}_k{k}_hbm_counters.txt")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
-    except OSError:
-        pass
-    return None
+    workload, since counters cannot be read from inside the benchmark.  Returns (bytes, the
+    file it came from), or (None, None) if there is no summary for this workload."""
+    names = [f"spd_step_{workload}_prefix{prefix}_k{k}_hbm_counters.txt", f"spd_step_{workload}_k{k}_hbm_counters.txt"]
+    defaults = {"7b": 64, "13b": 256, "70b": 512, "tiny": 16}
+    if prefix != defaults.get(workload):
+        names = names[:1]
+    for name in names:
+        try:
+            for line in open(os.path.join(ROOT, "profiles", name)):
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split("=")[1]), "profiles/" + name
+        except OSError:
+            pass
+    return None, None
 
 
 def cpu_baseline(shape, weights, tables, lambdas, prefix, k, alpha, tau, delta):
-    """The CPU oracle, as it stands, timed on this host.  A full 7B-shaped step would take
-    minutes in numpy, so the sample is the same step on depth-truncated copies of the model
-    (1 and 3 layers, same tensors): per-layer cost = (t3 - t1) / 2, the rest (embedding mix,
-    final norm, LM head, decision stage with n-gram scans) = t1 - per-layer; a full step is
-    rest + n_layers * per-layer."""
+    """The CPU oracle, as it stands, timed on this host, in two legs.
+    All cores: the whole model at full depth on the workload's real prefix -- the prefix pass
+    (untimed), the first timestep, then 2 timed SPD timesteps (each a few seconds at the 7B
+    shape).  Models too large for that (more than 40 GB of weights) are timed on 1- and 3-layer
+    truncations and extrapolated per layer, and the sample says so.
+    One thread: the same timestep on 1- and 3-layer truncations with every numerical library
+    limited to one thread, extrapolated per layer (per-layer = (t3 - t1) / 2, rest = t1 -
+    per-layer, step = rest + n_layers * per-layer)."""
     import synth
     from oracle import spd_oracle as O
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     def host(name):
         return synth.host_view(weights[name]) if not isinstance(weights[name], np.ndarray) else weights[name]
 
     otabs = O.NgramTables(tables)
     cfg = O.DecodeCfg(k, alpha, tau, delta, tuple(lambdas))
-    short = list(map(int, prefix[:8]))
-    times = {}
-    depths = (1, 3) if shape.n_layers > 3 else (shape.n_layers,)
-    for nl in depths:
-        names = [n for n, _, _ in synth.weight_names(shape.truncated(nl))]
+    full_prefix = list(map(int, prefix))
+
+    def timed_steps(n_layers, pre, n_steps):
+        names = [n for n, _, _ in synth.weight_names(shape.truncated(n_layers))]
         w = {n: host(n) for n in names}
-        lm = O.OracleLM(w, nl, shape.n_heads, shape.n_kv_heads, shape.rms_eps, shape.rope_theta)
+        lm = O.OracleLM(w, n_layers, shape.n_heads, shape.n_kv_heads, shape.rms_eps, shape.rope_theta)
         lm.reset()
-        logits = lm.forward(lm.embedding_rows(short))
-        state, _ = O.first_step(logits, short, cfg, keep_logits=False)
+        logits = lm.forward(lm.embedding_rows(pre))
+        state, _ = O.first_step(logits, pre, cfg, keep_logits=False)
         t0 = time.perf_counter()
-        n_steps = 2
         for _ in range(n_steps):
             gamma = O.superposition_weights(state.logscores)
             x = O.superposed_embedding(lm.embedding_rows([d[-1] for d in state.drafts]), gamma.astype(np.float32))
             logits = lm.forward(x[None, :])
             state, _ = O.expand_and_prune(state, logits, otabs, cfg, keep_logits=False)
-        times[nl] = (time.perf_counter() - t0) / n_steps
-    if len(depths) == 2:
-        per_layer = max((times[3] - times[1]) / 2, 0.0)
-        rest = max(times[1] - per_layer, 0.0)
-        step_s = rest + shape.n_layers * per_layer
+        return (time.perf_counter() - t0) / n_steps
+
+    def extrapolated(pre, n_steps):
+        if shape.n_layers <= 3:
+            t = timed_steps(shape.n_layers, pre, n_steps)
+            return t, 0.0, t
+        t1, t3 = timed_steps(1, pre, n_steps), timed_steps(3, pre, n_steps)
+        per_layer = max((t3 - t1) / 2, 0.0)
+        rest = max(t1 - per_layer, 0.0)
+        return rest + shape.n_layers * per_layer, per_layer, rest
+
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    weight_gb = shape.streamed_params() * (2 if shape.dtype == "bf16" else 4) / 1e9
+    if weight_gb <= 40.0:
+        step_s = timed_steps(shape.n_layers, full_prefix, 2)
+        sample = (f"2 timed oracle timesteps of the whole {shape.name} model ({shape.n_layers} layers) after its "
+                  f"{len(full_prefix)}-token prefix pass and first timestep, same tensors and n-gram tables as the GPU run, "
+                  f"all {cores} threads")
     else:
-        per_layer, rest, step_s = 0.0, times[depths[0]], times[depths[0]]
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+        step_s, per_layer, rest = extrapolated(full_prefix[:8], 2)
+        sample = (f"{weight_gb:.0f} GB of weights: 2 timed oracle timesteps each on 1- and 3-layer truncations of the "
+                  f"{shape.name} model (8-token prefix), all {cores} threads; per-layer {per_layer * 1e3:.1f} ms, rest "
+                  f"{rest * 1e3:.1f} ms, extrapolated to {shape.n_layers} layers")
+    with threadpool_limits(limits=1):
+        single_s, per_layer1, rest1 = extrapolated(full_prefix[:8], 1)
     return {"value": k / step_s, "unit": "draft-tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"2 timed oracle steps each on 1- and 3-layer truncations of the {shape.name} model "
-                      f"(same tensors, same n-gram tables, 8-token prefix); per-layer {per_layer * 1e3:.1f} ms, "
-                      f"rest {rest * 1e3:.1f} ms, extrapolated to {shape.n_layers} layers = {step_s * 1e3:.0f} ms/step",
-            "ms_per_step": step_s * 1e3}
+            "sample": sample, "ms_per_step": step_s * 1e3,
+            "single_thread_ms_per_step": single_s * 1e3,
+            "single_thread_value": k / single_s,
+            "single_thread_sample": f"1 timed oracle timestep each on 1- and 3-layer truncations (8-token prefix), one thread; "
+                                    f"per-layer {per_layer1 * 1e3:.0f} ms, rest {rest1 * 1e3:.0f} ms, extrapolated to "
+                                    f"{shape.n_layers} layers"}
 
 
 def probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args):
@@ -249,10 +271,10 @@ def main():
         # dominant kernel: the fused forward (the whole model in one launch) where it runs,
         # else the largest matrix-vector product
         fwd_bytes = ab["step"]
-        traffic = None
+        traffic, traffic_source = None, None
         if "fused_forward" in kernels:
             dom, dom_bytes = "fused_forward", fwd_bytes
-            traffic = recorded_traffic(args.workload, k)
+            traffic, traffic_source = recorded_traffic(args.workload, k, m)
         else:
             dom, dom_bytes = "gemv_gateup", ab["gemv_gateup"]
         if dom in kernels:
@@ -260,6 +282,8 @@ def main():
             kernels[dom]["GBps"] = gbs
             roofline = {"bound": "hbm", "kernel": dom, "achieved": gbs, "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
+                        "traffic_source": (traffic_source + " (rocprofv3 counters of an earlier run of this command, not of this run)")
+                        if traffic_source else None,
                         "bytes_per_launch": dom_bytes, "avg_launch_us": kernels[dom]["avg_us"],
                         "step_achieved": step_gbs, "step_frac": step_gbs / HBM_PEAK_GBS,
                         "step_bytes": ab["step"]}

@@ -193,15 +193,31 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
         sess.close()
 
 
+REPORT = []   # one line per large-shape test, printed once past pytest's capture when the module ends
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _print_report(request):
+    yield
+    if REPORT:
+        capman = request.config.pluginmanager.getplugin("capturemanager")
+        with capman.global_and_fixture_disabled():
+            print()
+            for line in REPORT:
+                print("  " + line)
+
+
 def report_decisions(name, stats, n_steps):
     """Every step's decision stage was compared exactly (on the GPU's own logits), and with the
     planted tables both the interpolated and the penalty form of an option occurred."""
     full = sum(bool(s.get("fully_compared")) for s in stats)
-    print(f"{name}: {full}/{n_steps} steps compared exactly on the GPU's own logits;",
-          "options in both distributions:", sum(s.get("own_overlap", 0) for s in stats),
-          "penalty form:", sum(s.get("own_penalty", 0) for s in stats),
-          "dropped:", sum(s.get("own_dropped", 0) for s in stats),
-          "| steps decisive against the oracle's logits:", sum(bool(s.get("vocab_decisive")) for s in stats))
+    line = (f"{name}: {full}/{n_steps} steps compared exactly on the GPU's own logits; options in both distributions: "
+            f"{sum(s.get('own_overlap', 0) for s in stats)}, penalty form: {sum(s.get('own_penalty', 0) for s in stats)}, "
+            f"dropped: {sum(s.get('own_dropped', 0) for s in stats)}; steps decisive against the oracle's logits: "
+            f"{sum(bool(s.get('vocab_decisive')) for s in stats)}; worst scaled logit error "
+            f"{max(s['logit_err'] for s in stats):.1e}")
+    print(line)
+    REPORT.append(line)
     assert full == n_steps
     assert_hit_paths_compared(stats)
 
