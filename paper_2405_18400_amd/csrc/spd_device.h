@@ -118,6 +118,19 @@ template <bool COH> __device__ __forceinline__ void act_store(float *p, float v)
     else *as_global(p) = v;
 }
 
+// 16 bytes of another workgroup's output, read coherently at device scope (the form a
+// device-scope atomic load takes, four words wide).  The compiler barrier keeps it where it is
+// written: a look at memory that another workgroup is writing must not be hoisted or merged.
+__device__ __forceinline__ u32x4 coherent_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset) {
+    asm volatile("" ::: "memory");
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 16);   // 16 = sc1: device scope
+}
+// The twin of an activation element in the other arena (see ACT_UNSET).
+__device__ __forceinline__ float *twin_of(float *p, long long twin) { return (float *)((char *)p + twin); }
+__device__ __forceinline__ void twin_unset(float *p, long long twin) {
+    __hip_atomic_store((global_ptr<uint32_t>)twin_of(p, twin), ACT_UNSET, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
@@ -355,7 +368,10 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
             for (int r = 0; r < PPB; ++r) o += dyn[(size_t)r * dh + tid];
         }
         if (n_splits == 1) {
-            if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, o / l);
+            if (tid < dh) {
+                act_store<COH>(a.out + (size_t)h * dh + tid, o / l);
+                if (COH && a.out_twin) twin_unset(a.out + (size_t)h * dh + tid, a.out_twin);
+            }
         } else {
             float *pp = a.part + ((size_t)h * a.max_splits + s) * (dh + 2);
             if (tid < dh) act_store<COH>(pp + 2 + tid, o);
@@ -409,7 +425,10 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                         if (tid < dh) O += w * coherent_load(pq + 2 + tid);
                     }
                 }
-                if (tid < dh) act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
+                if (tid < dh) {
+                    act_store<COH>(a.out + (size_t)h * dh + tid, O / L);
+                    if (COH && a.out_twin) twin_unset(a.out + (size_t)h * dh + tid, a.out_twin);
+                }
                 // (written through: the next user of this counter may sit behind another L2)
                 if (tid == 0) __hip_atomic_store(as_global(a.counters) + (size_t)h * ATTN_COUNTER_STRIDE, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -423,6 +442,7 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 // mode 0 feeds a prefix token's own embedding (gamma = 1) during the prefix pass.
 template <typename WT, bool COH = false>
 __device__ __forceinline__ void superpose_element(const SuperposeArgs &a, int c, int pos) {
+    if (COH && a.twin && c < a.d_model) twin_unset(a.h + c, a.twin);
     if (a.mode == 0) {
         const int tok = as_global(a.prefix)[pos];
         if (c < a.d_model) act_store<COH>(a.h + c, Store<WT>::load1(a.embed, (size_t)tok * a.d_model + c));

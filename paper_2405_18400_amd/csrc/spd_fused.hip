@@ -3,10 +3,21 @@
 // Batch-1 decode is a chain of ~160 small matrix-vector products (7B shape: 33-180 MB each,
 // 6-30 us at HBM speed), every one of which needs the complete output of its predecessor.
 // Launching them one by one leaves HBM idle at every boundary, so here a grid that exactly
-// fills the chip walks through all phases itself and meets at a device-wide barrier between
-// phases.  The weights a block needs for its first tile of the NEXT phase do not depend on
-// any activation, so they are requested before the barrier and are in flight while the block
-// waits: the weight stream from HBM does not stop at phase boundaries.
+// fills the chip walks through all phases itself.  There is no device-wide barrier between
+// phases: the activation vectors themselves say whether they are complete.  Every element of
+// a vector holds ACT_UNSET (a NaN bit pattern no arithmetic produces) until its producer has
+// stored it; a consumer loads the slice of the vector it needs, coherently, and loads again
+// whatever still reads ACT_UNSET.  So between "the last producer stored" and "every consumer
+// computes" lies one trip to memory, not the chain store acknowledged -> arrival counted ->
+// release polled -> vector loaded, each link of which queues behind the compute unit's own
+// outstanding weight requests (a compute unit serves its memory operations in order).
+// Two activation arenas alternate from launch to launch: whoever stores an element of this
+// launch's arena stores ACT_UNSET to the same element of the other one, which the next launch
+// finds unset throughout (the host sets both when a prefix pass begins).
+//
+// The weights a block needs for its first tile of the NEXT phase do not depend on any
+// activation, so they are requested while the block waits for its input, a slice at a time
+// between two looks at the input: the weight stream from HBM does not stop at phase boundaries.
 //
 // Phase GEMV ("row-contiguous"): the NW waves of a block read one matrix row side by side
 // (wave w takes columns [(p*NW + w)*64*VEC, +64*VEC) of pass p), so the slice of x a lane
@@ -22,15 +33,12 @@ namespace {
 // flight per wave.  (1024 threads = two such row groups with half the registers.)
 constexpr int FUSED_UA = 16;          // rows per tile where one pass covers a row
 constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
-constexpr int FUSED_QD = 12;          // 16-byte pieces per lane of the next tile requested while the block synchronises
-constexpr int FUSED_SLICE = 3;        // of which this many go out per synchronisation step of wave 0
-constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes (measured: 3 costs the
-                                      //   13B shape 0.3 % and the 70B shape 1 %, and gains the 7B shape 0.1...0.6 %)
+constexpr int FUSED_QD = 12;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
+constexpr int FUSED_SLICE = 3;        // of which this many go out between two looks at the input
+constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
 static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
-constexpr int BAR_SLEEP_7B = 36;      // s_sleep units (64 cycles) between two polls of the barrier
-constexpr int BAR_SLEEP_WIDE = 48;    // the same where d_ffn takes more than four block passes (the 70B shape: long
-                                      //   phases, and 36 costs it 0.3 %; the 7B and 13B shapes gain 0.4 and 0.2 %)
+constexpr int INPUT_SLEEP = 2;        // s_sleep units (64 cycles) between two looks at an input that is not complete yet
 constexpr int QKV_SLEEP = 1;          // the same between two polls of a head's arrival counter
 constexpr int NT = 512;               // threads per block
 constexpr int NW = 8;                 // waves side by side on one row
@@ -47,86 +55,7 @@ struct FusedShared {
     float red[NT / WAVE];
     float sc[ATTN_CHUNK_MAX];
     int s_last;
-    unsigned tick;                // bumped by thread 0 whenever it has issued a synchronisation step
-    unsigned released;            // number of synchronisation points this block has been released from
 };
-
-// (volatile accesses must name the LDS address space, or they become generic-address
-// instructions, which hold up the weight stream: see spd_device.h)
-typedef volatile unsigned __attribute__((address_space(3))) *lds_flag_ptr;
-__device__ __forceinline__ lds_flag_ptr lds_flag(unsigned *p) { return (lds_flag_ptr)p; }
-
-// Thread 0 tells the other waves that one more of its memory operations is on its way.
-__device__ __forceinline__ void tick_bump(FusedShared &sh) {
-    asm volatile("" ::: "memory");
-    lds_flag_ptr t = lds_flag(&sh.tick);
-    *t = *t + 1;
-    asm volatile("" ::: "memory");
-}
-
-// Device-wide barrier, two levels: blocks arrive on their group's counter (BAR_GROUP
-// consecutive blocks per group, counters 256 bytes apart), the last arriver of a group bumps
-// the top counter, everyone polls the top counter.  Same-address atomics serialise at the
-// memory side (~14 ns each): a flat counter pays for 256 of them, a top counter fed by many
-// small groups for the groups' bumps landing on the line everybody polls.  Measured per step
-// at the 7B shape (256 blocks): groups of 8 / 16 / 32 / 64 / 96 / 128 / 256 blocks = +170 / +80 /
-// +32 / +8 / 0 / +13 / +60 us with one top counter; with two copies of the top counter away
-// from the group counters, two groups of 128 are 3 us per step ahead of 96 / 96 / 64 (one
-// bump per copy fewer on the polled lines).  (One counter per group polled side by side by every block,
-// without the top level, measured slower: the polls of 256 blocks on each of 8 addresses take
-// longer than the extra hop.)  All counters increase monotonically and run on from launch to
-// launch (the kernel continues from the count its predecessor left behind); the host zeroes
-// them when a prefix pass begins.  Bounded: if the grid is not co-resident the wait gives up,
-// raises *err, and every later wait returns at once, so the kernel always drains.
-//
-// Everything other blocks will read was stored with write-through (device-scope) stores and
-// every storing wave has waited for its own stores (wait_stores) before getting here.
-// ALL_WAVES_STORED: waves other than wave 0 stored too, so the block meets before it arrives.
-// Wave 0 should have no weight loads outstanding when it gets here: memory operations of a
-// wave return in order, so the arrival count and every poll would queue behind them.
-//
-// While thread 0 works through the barrier the other waves request the next phase's first
-// tile a slice at a time, one slice behind each memory operation thread 0 issues (tick_bump):
-// a compute unit serves its memory operations in order, so an arrival or a poll issued behind
-// a whole tile of weight requests would wait for all of them, while a slice issued behind the
-// poll delays nothing and keeps the weight stream going through the barrier.
-template <bool ALL_WAVES_STORED, int SLEEP>
-__device__ __forceinline__ void grid_barrier(unsigned *ctr, unsigned epoch, int *err, FusedShared &sh, unsigned seq) {
-    if (ALL_WAVES_STORED) __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned g = blockIdx.x / BAR_GROUP;
-        const unsigned n_groups = (gridDim.x + BAR_GROUP - 1) / BAR_GROUP;
-        const unsigned my_size = min((unsigned)BAR_GROUP, gridDim.x - g * BAR_GROUP);
-        // The top counter exists BAR_TOPS times, kilobytes away from the group counters (the last
-        // lines of the range reserved for groups): the last arriver of a group bumps every copy, a
-        // block polls only its own.  Half the pollers per line, and no poll lands next to a line that
-        // a group's arrivals are being added to: 1.1 % of a step against one top counter in the first line.
-        unsigned *grp = ctr + 64 * (1 + g);
-        unsigned *tops = ctr + 64 * (1 + BAR_MAX_GROUPS - BAR_TOPS), *top = tops + 64 * (blockIdx.x % BAR_TOPS);
-        const unsigned old = __hip_atomic_fetch_add(as_global(grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        tick_bump(sh);
-        if (old + 1 == epoch * my_size) {
-#pragma unroll
-            for (int r = 0; r < BAR_TOPS; ++r)
-                __hip_atomic_fetch_add(as_global(tops) + 64 * r, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        unsigned spins = 0;
-        while (true) {
-            const unsigned seen = __hip_atomic_load(as_global(top), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            tick_bump(sh);
-            if (seen >= epoch * n_groups) break;
-            __builtin_amdgcn_s_sleep(SLEEP);
-            ++spins;
-            if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
-            if (spins > SPIN_LIMIT) {
-                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-        }
-        *lds_flag(&sh.released) = seq;
-    }
-    __syncthreads();
-}
 
 // Values that are the same in every lane but were loaded from global memory would occupy
 // vector registers; these move them to scalar registers.
@@ -156,10 +85,6 @@ __device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
 
 __device__ __forceinline__ bool is_wave0() { return __builtin_amdgcn_readfirstlane((int)threadIdx.x) < WAVE; }
 
-// Wait until this wave's stores have been acknowledged.  Called before the next phase's
-// weights are requested, so it never waits for those.
-__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // Units [lo, hi) of n that block b of G owns (contiguous, balanced to within one unit); the
 // first `skip` blocks own nothing.
 __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &hi, int skip = 0) {
@@ -171,20 +96,29 @@ __device__ __forceinline__ void block_range(int n, int b, int G, int &lo, int &h
     hi = __builtin_amdgcn_readfirstlane((int)(((unsigned)n * (unsigned)(b + 1)) / (unsigned)G));
 }
 
+// What a phase leaves in the profile: stamp[2i] = the block has finished everything before
+// synchronisation point i (its outputs are stored), stamp[2i+1] = it has what it needs to go on.
+struct Prof {
+    long long *p;
+    __device__ __forceinline__ void done(unsigned point) const { if (p && threadIdx.x == 0) as_global(p)[2 * point] = wall_clock64(); }
+    __device__ __forceinline__ void go(unsigned point) const { if (p && threadIdx.x == 0) as_global(p)[2 * point + 1] = wall_clock64(); }
+};
+
 // A phase keeps ONE tile of U rows x P passes (NS = U * P 16-byte pieces per lane) in
 // registers.  The moment a piece has been multiplied in, its register is re-used for the same
-// piece of the block's next tile, so a wave always has about NS loads in flight; after the
-// last tile the first tile of the NEXT phase is requested, before the device-wide barrier.
+// piece of the block's next tile, so a wave always has about NS loads in flight.
 // Loads are never predicated: a row past the block's range re-reads the last valid row (a
 // cache hit), and a column past the row end lies outside the buffer descriptor, which
 // describes one row (zeros come back, nothing is fetched); the inner loop has no branches.
 template <typename WT, int P, int U, int EPI, int NBUF, int SL>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
-    static constexpr int UT = U / 2;   // units per tile
+    static constexpr int XP = VEC / 4;   // 16-byte pieces of x per pass and lane
+    static constexpr int UT = U / 2;     // units per tile
     static constexpr int NS = U * P;
     static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U, "tile does not fit the register window");
     static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
+    static_assert(P * XP <= 32, "one bit per piece of x");
 
     static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
 
@@ -207,9 +141,12 @@ struct Gemv {
         return stream_load16(row_resource(W + (size_t)row * row_bytes, row_bytes), coff[p]);
     }
 
-    // The head of this block's first tile, pieces [0, QD), is requested before the phase
-    // starts; the rest follows the load of x.
+    // The head of a block's first tile, pieces [0, QD), goes out while the input is awaited;
+    // the rest follows once the input is there.
     static constexpr int QD = NS < FUSED_QD ? NS : FUSED_QD;
+
+    // Requests pieces [0, QD) at once.  For a block that has other work to do (an attention
+    // item) before it can look at this phase's input: run() is then told they are on their way.
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
         int lo, hi;
@@ -220,33 +157,6 @@ struct Gemv {
         for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
 #pragma unroll
         for (int q = 0; q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
-    }
-    // The same while thread 0 runs barrier number `epoch`: SL pieces behind each
-    // of its synchronisation steps, everything that is left once the block has been released.
-    static __device__ __forceinline__ void prefetch_sliced(const GemvArgs &a_in, u32x4 (&buf)[NBUF], FusedShared &sh,
-                                                           unsigned epoch) {
-        const GemvArgs a = uniform(a_in);
-        int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
-        if (lo >= hi) return;
-        uint32_t coff[P];
-#pragma unroll
-        for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
-        lds_flag_ptr tick = lds_flag(&sh.tick), released = lds_flag(&sh.released);
-        unsigned seen = uniform((int)*tick);
-#pragma unroll
-        for (int q = 0; q < QD; ++q) {
-            if (q % SL == 0) {
-                unsigned now = seen;
-                for (unsigned spins = 0; spins < SPIN_LIMIT; ++spins) {   // thread 0's own wait is bounded too
-                    now = uniform((int)*tick);
-                    if (now != seen || (unsigned)uniform((int)*released) >= epoch) break;
-                    __builtin_amdgcn_s_sleep(1);
-                }
-                seen = now;
-            }
-            buf[q] = piece(a, lo, hi, q, coff);
-        }
     }
 
     // One tile: U rows of this wave's row group against x, partial sums to LDS, the block
@@ -285,82 +195,144 @@ struct Gemv {
             if (EPI == EPI_RESID) {
                 act_store<true>(a.y + 2 * eu, sh.epi[2 * (eu - lo)] + r0);
                 act_store<true>(a.y + 2 * eu + 1, sh.epi[2 * (eu - lo) + 1] + r1);
+                if (a.twin) { twin_unset(a.y + 2 * eu, a.twin); twin_unset(a.y + 2 * eu + 1, a.twin); }
             } else {
                 const float2 cs = EPI == EPI_QKV ? sh.rope[((2 * eu) % a.d_head) / 2] : make_float2(1.f, 0.f);
                 gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, cs);
+                if (EPI == EPI_SWIGLU && a.twin) twin_unset(a.y + eu, a.twin);
             }
         }
-        if (!REFILL && tid == 0) tick_bump(sh);   // the phase's last stores are on their way
     }
 
-    // Runs the phase.  On entry `buf` holds this block's first tile; on return it holds the
-    // block's first tile of phase Next (arguments `na`).
-    template <typename Next>
-    static __device__ __forceinline__ void run(const GemvArgs &a_in, const GemvArgs &na, int pos,
-                                               FusedShared &sh, u32x4 (&buf)[NBUF], unsigned seq) {
+    // Runs the phase.  `ahead`: pieces [0, QD) of the block's first tile are in `buf` already
+    // (prefetch); otherwise they are requested here, a slice of SL between two looks at x.
+    // `pb` (which of the two partial-sum buffers the next tile uses) runs on from phase to
+    // phase: wave 0 may still be finishing the previous phase's last tile from the other one.
+    static __device__ __forceinline__ void run(const GemvArgs &a_in, int pos, FusedShared &sh, u32x4 (&buf)[NBUF],
+                                               int &pb, bool ahead, int *err, const Prof &prof, unsigned point) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         int lo, hi;
         block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
-        if (lo < hi) {
-            // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
-            // depend on any activation, so its load goes out first
-            float xr[P][VEC];
-            uint32_t coff[P];
-            u32x4 graw[P];
-            float ss = 0.f;
+        if (lo >= hi) { prof.go(point); return; }
+        // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
+        // depend on any activation, so its load goes out first
+        uint32_t coff[P];
+        u32x4 graw[P];
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-                coff[p] = col_offset(a, p);
-                if (a.gain != nullptr)   // clamped: lanes past the row end must stay inside the gain vector
-                    graw[p] = global_load16((const char *)a.gain + min(coff[p], (uint32_t)((a.cols - VEC) * sizeof(WT))));
+        for (int p = 0; p < P; ++p) {
+            coff[p] = col_offset(a, p);
+            if (a.gain != nullptr)   // clamped: lanes past the row end must stay inside the gain vector
+                graw[p] = global_load16((const char *)a.gain + min(coff[p], (uint32_t)((a.cols - VEC) * sizeof(WT))));
+        }
+        // x: every 16-byte piece is loaded until none of its four words reads ACT_UNSET
+        const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.cols * 4, 0x00020000);
+        u32x4 xv[P][XP];
+        unsigned pend = 0;   // bit p * XP + j: that piece is still missing
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int c = ((p * NW + w) * WAVE + lane) * VEC;
+#pragma unroll
+            for (int j = 0; j < XP; ++j) {
+                xv[p][j] = u32x4{0u, 0u, 0u, 0u};   // past the row end: x is 0, nothing to wait for
+                if (c < a.cols) pend |= 1u << (p * XP + j);
             }
+        }
+        auto look = [&]() {
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 const int c = ((p * NW + w) * WAVE + lane) * VEC;
 #pragma unroll
-                for (int v = 0; v < VEC; v += 4) {
-                    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (c < a.cols) t = global_load_float4(a.x + c + v);   // first read of a fresh address
-                    xr[p][v] = t.x; xr[p][v + 1] = t.y; xr[p][v + 2] = t.z; xr[p][v + 3] = t.w;
-                }
+                for (int j = 0; j < XP; ++j)
+                    if (pend & (1u << (p * XP + j))) xv[p][j] = coherent_load16(xres, (uint32_t)(c + 4 * j) * 4u);
             }
-            if (EPI == EPI_RESID) {   // this block's slice of the residual: 2 (hi - lo) <= MAX_EPI values
-                for (int i = tid; i < 2 * (hi - lo); i += NT) sh.epi[i] = as_global(a.resid)[2 * lo + i];
-            }
-            if (QD < NS) {   // the rest of the first tile goes out behind x, which everything waits for
-                asm volatile("" ::: "memory");
-#pragma unroll
-                for (int q = QD; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
-            }
+        };
+        auto judge = [&]() {
 #pragma unroll
             for (int p = 0; p < P; ++p)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) ss += xr[p][v] * xr[p][v];
-            if (a.gain != nullptr) {
-                const float tot = block_sum<NT>(g == 0 ? ss : 0.f, sh.red);   // every group holds all of x
-                const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
+                for (int j = 0; j < XP; ++j) {
+                    const u32x4 v = xv[p][j];
+                    if (v.x != ACT_UNSET && v.y != ACT_UNSET && v.z != ACT_UNSET && v.w != ACT_UNSET) pend &= ~(1u << (p * XP + j));
+                }
+        };
+        look();
+        if (!ahead) {
 #pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    float gf[VEC];
-                    Store<WT>::unpack(graw[p], gf);
+            for (int q0 = 0; q0 < QD; q0 += SL) {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) xr[p][v] = xr[p][v] * rs * gf[v];   // x is 0 past the row end
+                for (int q = q0; q < q0 + SL && q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
+                if (__any(pend != 0)) {      // the look before this slice has come back: whatever is
+                    judge();                 // still missing is asked for again, behind the slice
+                    if (__any(pend != 0)) look();
                 }
             }
-            // All tiles but the last refill their registers unconditionally; the last one has
-            // its own copy of the loop body.  (A refill under a branch makes the compiler wait
-            // for every outstanding load at the loop's back edge: the stream would stop once
-            // per tile.)
-            int pb = 0, u0 = lo;
-            for (; u0 + NG * UT < hi; u0 += NG * UT, pb ^= 1) tile<true>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
-            tile<false>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
         }
-        // Only wave 0 stored anything; the others request the next phase's first tile at once.
-        // Wave 0 runs the device-wide barrier next and asks for its share after the release
-        // (see grid_barrier).
-        if (is_wave0()) wait_stores();
-        else Next::prefetch_sliced(na, buf, sh, seq + 1);   // `seq` synchronisation points have been passed so far
+        for (unsigned spins = 0; __any(pend != 0); ++spins) {
+            judge();
+            if (!__any(pend != 0)) break;
+            if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                // bounded: the grid is not co-resident (or a producer gave up): raise the flag and go on
+                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(INPUT_SLEEP);
+            look();
+        }
+        prof.go(point);
+        if (QD < NS) {   // the rest of the first tile
+#pragma unroll
+            for (int q = QD; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
+        }
+        float xr[P][VEC];
+        float ss = 0.f;
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < XP; ++j) {
+                xr[p][4 * j] = __uint_as_float(xv[p][j].x); xr[p][4 * j + 1] = __uint_as_float(xv[p][j].y);
+                xr[p][4 * j + 2] = __uint_as_float(xv[p][j].z); xr[p][4 * j + 3] = __uint_as_float(xv[p][j].w);
+            }
+        if (EPI == EPI_RESID) {
+            // this block's slice of the residual: 2 (hi - lo) <= MAX_EPI values.  It has been
+            // complete for a whole phase; read coherently all the same, and never taken unset.
+            __syncthreads();   // wave 0 may still be in the epilogue of the last phase that staged a slice
+            for (int i = tid; i < 2 * (hi - lo); i += NT) {
+                float r = coherent_load(a.resid + 2 * lo + i);
+                for (unsigned spins = 0; __float_as_uint(r) == ACT_UNSET; ++spins) {
+                    if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                        __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(INPUT_SLEEP);
+                    r = coherent_load(a.resid + 2 * lo + i);
+                }
+                sh.epi[i] = r;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) ss += xr[p][v] * xr[p][v];
+        if (a.gain != nullptr) {
+            const float tot = block_sum<NT>(g == 0 ? ss : 0.f, sh.red);   // every group holds all of x
+            const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                float gf[VEC];
+                Store<WT>::unpack(graw[p], gf);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) xr[p][v] = xr[p][v] * rs * gf[v];   // x is 0 past the row end
+            }
+        }
+        // All tiles but the last refill their registers unconditionally; the last one has
+        // its own copy of the loop body.  (A refill under a branch makes the compiler wait
+        // for every outstanding load at the loop's back edge: the stream would stop once
+        // per tile.)
+        int u0 = lo;
+        for (; u0 + NG * UT < hi; u0 += NG * UT, pb ^= 1) tile<true>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
+        tile<false>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
+        pb ^= 1;
     }
 };
 
@@ -368,7 +340,8 @@ struct FusedArgs {
     SuperposeArgs sup;
     const spd_layer_weights *layers;   // device array [n_layers]
     const void *final_norm, *lm_head;
-    char *act;
+    char *act;                         // arena 0; arena 1 starts arena_bytes later
+    size_t arena_bytes;
     ActLayout al;
     float *logits;
     void *kv;                          // layer l: K at kv + 2 l kv_layer_bytes, V one kv_layer_bytes later
@@ -376,24 +349,18 @@ struct FusedArgs {
     float *part;
     int32_t *counters;
     const double *inv_freq;
-    long long *prof;                   // optional: every block stamps wall_clock64() around every barrier
-    unsigned *barrier;
+    long long *prof;                   // optional: every block stamps wall_clock64() around every synchronisation point
+    unsigned *sync;
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
 };
 
-template <int NBUF>
-struct NoNext {
-    static __device__ __forceinline__ void prefetch(const GemvArgs &, u32x4 (&)[NBUF]) {}
-    static __device__ __forceinline__ void prefetch_sliced(const GemvArgs &, u32x4 (&)[NBUF], FusedShared &, unsigned) {}
-};
-
-__device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
+__device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, char *act, int l) {
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh, nkv = a.n_kv_heads * dh;
     GemvArgs g{};
     const spd_layer_weights w = uniform(a.layers[l]);
-    g.W = w.wqkv; g.gain = w.attn_norm; g.eps = a.eps; g.x = a.al.h_in(a.act, l); g.y = a.al.vec(a.act, l, a.al.q);
+    g.W = w.wqkv; g.gain = w.attn_norm; g.eps = a.eps; g.x = a.al.h_in(act, l); g.y = a.al.vec(act, l, a.al.q);
     g.rows = nq + 2 * nkv; g.cols = a.d_model;
     g.kcache = (char *)a.kv + (size_t)(2 * l) * a.kv_layer_bytes;
     g.vcache = (char *)a.kv + (size_t)(2 * l + 1) * a.kv_layer_bytes;
@@ -403,29 +370,27 @@ __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, int l) {
 }
 
 // After the QKV phase nothing but attention needs the new q, k and v, and attention for one
-// head needs only that head's rows.  So instead of a device-wide barrier there is an arrival
-// counter per key/value head that counts finished row pairs: a block adds, for every head, how
-// many of its row pairs belong to the head's query, key or value rows (one lane of wave 0 per
-// head, one atomic instruction), and a block about to run an attention item waits until the
-// head's counter shows all of its row pairs.  Blocks without an item do not wait at all.  The
-// counters run on from layer to layer and launch to launch like the barrier's.  Same rules as
-// grid_barrier: the arriving wave has waited for its write-through stores; the wait is bounded.
-__device__ __forceinline__ void qkv_arrive(unsigned *sync, const GemvArgs &q, FusedShared &sh, unsigned seq) {
+// head needs only that head's rows: an arrival counter per key/value head counts finished row
+// pairs.  A block adds, for every head, how many of its row pairs belong to the head's query,
+// key or value rows (one lane of wave 0 per head, one atomic instruction per 64 heads), and a
+// block about to run an attention item waits until the head's counter shows all of its row
+// pairs.  Blocks without an item do not wait at all.  The counters run on from layer to layer
+// and launch to launch; the host zeroes them when a prefix pass begins.  The arriving wave has
+// waited for its write-through stores (only wave 0 stores in a phase); the wait is bounded.
+__device__ __forceinline__ void qkv_arrive(unsigned *sync, const GemvArgs &q) {
     if (is_wave0()) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's stores of q, k, v have been acknowledged
         int lo, hi;
         block_range(q.rows / 2, blockIdx.x, gridDim.x, lo, hi, q.first_block);
-        const int g = threadIdx.x, dh2 = q.d_head / 2, n_kv = q.n_kv_rows / q.d_head;
+        const int dh2 = q.d_head / 2, n_kv = q.n_kv_rows / q.d_head;
         const int tq = (q.n_q_rows / q.n_kv_rows) * dh2, kb = q.n_q_rows / 2, vb = (q.n_q_rows + q.n_kv_rows) / 2;
         auto overlap = [&](int a0, int a1) { return max(0, min(hi, a1) - max(lo, a0)); };
-        const int mine = overlap(g * tq, (g + 1) * tq) + overlap(kb + g * dh2, kb + (g + 1) * dh2) + overlap(vb + g * dh2, vb + (g + 1) * dh2);
-        if (g < n_kv && mine > 0)
-            __hip_atomic_fetch_add(as_global(sync) + 64 * g, (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (threadIdx.x == 0) {
-            tick_bump(sh);
-            *lds_flag(&sh.released) = seq;
+        for (int g = threadIdx.x; g < n_kv; g += WAVE) {
+            const int mine = overlap(g * tq, (g + 1) * tq) + overlap(kb + g * dh2, kb + (g + 1) * dh2) + overlap(vb + g * dh2, vb + (g + 1) * dh2);
+            if (mine > 0)
+                __hip_atomic_fetch_add(as_global(sync) + 64 * g, (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    __syncthreads();
 }
 __device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned target, int *err) {
     if (threadIdx.x == 0) {
@@ -443,9 +408,9 @@ __device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned t
     __syncthreads();
 }
 
-__device__ __forceinline__ GemvArgs head_args(const FusedArgs &a) {
+__device__ __forceinline__ GemvArgs head_args(const FusedArgs &a, char *act) {
     GemvArgs g{};
-    g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.al.h_in(a.act, a.n_layers); g.y = a.logits;
+    g.W = a.lm_head; g.gain = a.final_norm; g.eps = a.eps; g.x = a.al.h_in(act, a.n_layers); g.y = a.logits;
     g.rows = a.vocab; g.cols = a.d_model;
     return g;
 }
@@ -463,7 +428,6 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int NA = PA * UO;
     constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
     constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
-    constexpr int BAR_SLEEP = PB > 4 ? BAR_SLEEP_WIDE : BAR_SLEEP_7B;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL>;
@@ -472,55 +436,46 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     __shared__ FusedShared sh;
     __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
 
-#define SPD_BARRIER(ALL_WAVES_STORED)                                        \
-    do {                                                                     \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();      \
-        grid_barrier<ALL_WAVES_STORED, BAR_SLEEP>(a.barrier, ++epoch, &st->err, sh, ++seq); \
-        if (prof && threadIdx.x == 0) as_global(prof)[2 * seq - 1] = wall_clock64();  \
-    } while (0)
     DevState *st = a.sup.st;
-    long long *prof = (a.prof && blockIdx.x < FUSED_PROF_BLOCKS) ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr;
+    int *err = &st->err;
+    const Prof prof{(a.prof && blockIdx.x < FUSED_PROF_BLOCKS) ? a.prof + (size_t)blockIdx.x * (size_t)(2 * (5 * a.n_layers + 2)) : nullptr};
     const int pos = uniform(as_global(st)->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;
-    // The barrier counters run on from launch to launch (the host zeroes them only when a prefix
-    // pass begins): `epoch` continues from the number of barriers all earlier launches passed,
-    // which block 0 leaves behind when it ends.  Every block has read it before it arrives at
-    // this launch's first barrier, and block 0 cannot get past that barrier without them.
-    const unsigned epoch0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.barrier) + BAR_EPOCH_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    unsigned epoch = epoch0;
-    unsigned seq = 0;   // synchronisation points passed in this launch (device-wide barriers and per-head arrivals)
-    const unsigned layers0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.barrier) + BAR_LAYER_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    unsigned *qkv_sync = a.barrier + QKV_SYNC_WORD0;
-    const bool per_head = a.n_kv_heads <= QKV_SYNC_MAX;
+    // The arenas alternate from launch to launch and the per-head counters run on: block 0 leaves
+    // the number of launches and of layers passed behind when it ends.
+    const unsigned launch0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.sync) + SYNC_LAUNCH_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const unsigned layers0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.sync) + SYNC_LAYER_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    char *act = a.act + (size_t)(launch0 & 1u) * a.arena_bytes;
+    const long long twin = (launch0 & 1u) ? -(long long)a.arena_bytes : (long long)a.arena_bytes;
+    unsigned *qkv_sync = a.sync + QKV_SYNC_WORD0;
     const unsigned head_units = (unsigned)((a.n_heads / a.n_kv_heads + 2) * (dh / 2));   // row pairs of one key/value head's q, k, v
+    unsigned point = 0;   // synchronisation points passed: one after the input phase, five per layer
+    int pb = 0;
 
     // phase 0: the input vector (Section 3.1, Eq. 1 and 2); every block keeps this position's
     // rotary table in LDS
-    for (int c = blockIdx.x * NT + threadIdx.x; c < a.d_model; c += gridDim.x * NT)
-        superpose_element<WT, true>(a.sup, c, pos);
+    {
+        SuperposeArgs sup = a.sup;
+        sup.h = a.al.h_in(act, 0);
+        sup.twin = twin;
+        for (int c = blockIdx.x * NT + threadIdx.x; c < a.d_model; c += gridDim.x * NT)
+            superpose_element<WT, true>(sup, c, pos);
+    }
     if (threadIdx.x < dh / 2) sh.rope[threadIdx.x] = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
-    wait_stores();
     u32x4 buf[NBUF];
-    GemvArgs cur = a.n_layers > 0 ? qkv_args(a, 0) : head_args(a);
-    if (threadIdx.x == 0) { sh.tick = 0; sh.released = 0; }
-    __syncthreads();
-    if (!is_wave0()) {   // (not sliced: before this barrier the whole block meets first)
-        if (a.n_layers > 0) Qkv::prefetch(cur, buf);
-        else if (a.head) Head::prefetch(cur, buf);
-    }
-    SPD_BARRIER(true);
-    if (is_wave0()) {
-        if (a.n_layers > 0) Qkv::prefetch(cur, buf);
-        else if (a.head) Head::prefetch(cur, buf);
-    }
+    prof.done(point);
 
     for (int l = 0; l < a.n_layers; ++l) {
         const spd_layer_weights w = uniform(a.layers[l]);
-        GemvArgs o{};
-        float *att = a.al.vec(a.act, l, a.al.att), *h1 = a.al.vec(a.act, l, a.al.h1);
-        float *u = a.al.vec(a.act, l, a.al.u), *h2 = a.al.vec(a.act, l, a.al.h2);
-        o.W = w.wo; o.x = att; o.resid = a.al.h_in(a.act, l); o.y = h1; o.rows = a.d_model; o.cols = nq;
+        float *q = a.al.vec(act, l, a.al.q), *att = a.al.vec(act, l, a.al.att), *h1 = a.al.vec(act, l, a.al.h1);
+        float *u = a.al.vec(act, l, a.al.u), *h2 = a.al.vec(act, l, a.al.h2);
+        const GemvArgs cur = qkv_args(a, act, l);
+        Qkv::run(cur, pos, sh, buf, pb, false, err, prof, point++);
+        prof.done(point);
+        qkv_arrive(qkv_sync, cur);
+        prof.go(point++);
+
         // Attention items: one per (query head, chunk of cached positions).  Up to
         // FUSED_ONE_CHUNK positions a head is ONE item (one or two batches of loads in one
         // block): a second batch costs about 2 us, merging chunks across blocks about 4 us (an
@@ -529,6 +484,8 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         // Longer contexts are cut so that every block gets an item if the chunk bounds allow.
         // While few blocks have an item those take no rows of the O projection: they would hold
         // everybody up fetching their tile after the attention.
+        GemvArgs o{};
+        o.W = w.wo; o.x = att; o.resid = a.al.h_in(act, l); o.y = h1; o.rows = a.d_model; o.cols = nq; o.twin = twin;
         const int n_ctx = pos + 1;
         int chunk = FUSED_ONE_CHUNK;
         if (n_ctx > FUSED_ONE_CHUNK) {
@@ -539,65 +496,40 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         const int n_splits = (n_ctx + chunk - 1) / chunk;
         const int n_items = a.n_heads * n_splits;
         o.first_block = 4 * n_items <= (int)gridDim.x ? n_items : 0;
-        Qkv::template run<Oproj>(cur, o, pos, sh, buf, seq);
-        if (per_head) {   // no device-wide barrier here: see qkv_arrive
-            if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();
-            qkv_arrive(qkv_sync, cur, sh, ++seq);
-            if (prof && threadIdx.x == 0) as_global(prof)[2 * seq - 1] = wall_clock64();
-        } else {
-            SPD_BARRIER(false);
-        }
-        if (is_wave0()) Oproj::prefetch(o, buf);
-
-        {   // attention over pos + 1 cached positions; the O-projection tile stays in flight
-            AttnArgs t{cur.y, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, n_ctx,
-                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, chunk, a.max_splits};
+        const bool has_item = (int)blockIdx.x < n_items;
+        if (has_item) {   // attention over pos + 1 cached positions with the head of the O-projection tile in flight
+            Oproj::prefetch(o, buf);
+            AttnArgs t{q, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, n_ctx,
+                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, chunk, a.max_splits, twin};
             const int group = a.n_heads / a.n_kv_heads;
             for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
-                if (per_head) qkv_wait(qkv_sync, h / group, (layers0 + l + 1) * head_units, &st->err);
+                qkv_wait(qkv_sync, h / group, (layers0 + l + 1) * head_units, err);
                 attn_item<KvT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
                                          h % group, h % group + 1);
             }
-            wait_stores();
         }
-        SPD_BARRIER(true);
+        prof.done(point);
+        Oproj::run(o, pos, sh, buf, pb, has_item, err, prof, point++);
+        prof.done(point);
 
         GemvArgs f{};
         f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
-        f.rows = a.d_ffn; f.cols = a.d_model;
-        Oproj::template run<GateUp>(o, f, pos, sh, buf, seq);
-        SPD_BARRIER(false);
-        if (is_wave0()) GateUp::prefetch(f, buf);
+        f.rows = a.d_ffn; f.cols = a.d_model; f.twin = twin;
+        GateUp::run(f, pos, sh, buf, pb, false, err, prof, point++);
+        prof.done(point);
 
         GemvArgs d{};
-        d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn;
-        GateUp::template run<Down>(f, d, pos, sh, buf, seq);
-        SPD_BARRIER(false);
-        if (is_wave0()) Down::prefetch(d, buf);
-
-        if (l + 1 < a.n_layers) {
-            cur = qkv_args(a, l + 1);
-            Down::template run<Qkv>(d, cur, pos, sh, buf, seq);
-        } else if (a.head) {
-            cur = head_args(a);
-            Down::template run<Head>(d, cur, pos, sh, buf, seq);
-        } else {
-            Down::template run<NoNext<NBUF>>(d, d, pos, sh, buf, seq);
-        }
-        if (l + 1 < a.n_layers || a.head) SPD_BARRIER(false);
-        if (is_wave0()) {
-            if (l + 1 < a.n_layers) Qkv::prefetch(cur, buf);
-            else if (a.head) Head::prefetch(cur, buf);
-        }
+        d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn; d.twin = twin;
+        Down::run(d, pos, sh, buf, pb, false, err, prof, point++);
+        prof.done(point);
     }
-    if (a.head) Head::template run<NoNext<NBUF>>(cur, cur, pos, sh, buf, seq);
-    if (prof && threadIdx.x == 0) as_global(prof)[2 * seq] = wall_clock64();
+    if (a.head) Head::run(head_args(a, act), pos, sh, buf, pb, false, err, prof, point);
+    if (prof.p && threadIdx.x == 0) as_global(prof.p)[2 * (point + 1)] = wall_clock64();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        __hip_atomic_store(as_global(a.barrier) + BAR_EPOCH_WORD, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(as_global(a.barrier) + BAR_LAYER_WORD, layers0 + (unsigned)a.n_layers, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(a.sync) + SYNC_LAUNCH_WORD, launch0 + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(a.sync) + SYNC_LAYER_WORD, layers0 + (unsigned)a.n_layers, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-#undef SPD_BARRIER
 }
 
 template <typename WT, int PA, int PB> struct Variant {
@@ -650,9 +582,9 @@ int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int blocks) {
     FusedArgs a{};
     a.sup = h.sup; a.layers = h.layers; a.final_norm = h.final_norm; a.lm_head = h.lm_head;
-    a.act = h.act; a.al = h.al; a.logits = h.logits;
+    a.act = h.act; a.arena_bytes = h.arena_bytes; a.al = h.al; a.logits = h.logits;
     a.kv = h.kv; a.kv_layer_bytes = h.kv_layer_bytes; a.part = h.part; a.counters = h.counters;
-    a.inv_freq = h.inv_freq; a.prof = h.prof; a.barrier = h.barrier;
+    a.inv_freq = h.inv_freq; a.prof = h.prof; a.sync = h.sync;
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
     a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
     a.eps = h.eps;

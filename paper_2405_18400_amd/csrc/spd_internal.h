@@ -93,6 +93,8 @@ struct GemvArgs {
     const double *inv_freq;     // [d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
     int32_t first_block;        // fused kernel: blocks below this index take no rows of this phase
+    long long twin;             // fused kernel: byte offset from y to the same vector in the other activation arena
+                                // (every element stored to y is accompanied by ACT_UNSET stored there); 0 = none
 };
 
 constexpr int ATTN_COUNTER_STRIDE = 64;
@@ -107,6 +109,7 @@ struct AttnArgs {
     const DevState *st;  // n_ctx = st->pos + 1 when non-null
     int32_t n_ctx;       // used when st is null
     int32_t n_heads, n_kv_heads, d_head, cap_ctx, chunk, max_splits;
+    long long out_twin;  // fused kernel: byte offset from out to its twin in the other activation arena; 0 = none
 };
 
 struct SuperposeArgs {
@@ -115,6 +118,7 @@ struct SuperposeArgs {
     const int32_t *prefix;  // mode 0: token = prefix[st->pos]
     float *h;
     int32_t d_model, mode, k;
+    long long twin;         // fused kernel: byte offset from h to its twin in the other activation arena; 0 = none
 };
 
 struct TopkArgs {
@@ -165,12 +169,19 @@ struct ActLayout {
     __host__ __device__ __forceinline__ float *vec(char *base, int l, size_t which) const { return at(base, layer0 + (size_t)l * stride + which); }
 };
 
+// The fused forward kernel synchronises through the activation vectors themselves: a vector
+// element holds this bit pattern (a NaN no arithmetic produces) until its producer has stored
+// it.  There are two activation arenas; a launch works in one (they alternate from launch to
+// launch) and leaves every element of the other at ACT_UNSET for its successor.
+constexpr uint32_t ACT_UNSET = 0xFFFFFFFFu;
+
 // Arguments of the fused forward kernel (one persistent launch for the whole model).
 struct FusedArgsHost {
     SuperposeArgs sup;
     const spd_layer_weights *layers;   // DEVICE array [n_layers]
     const void *final_norm, *lm_head;
-    char *act;
+    char *act;                         // arena 0; arena 1 starts arena_bytes later
+    size_t arena_bytes;
     ActLayout al;
     float *logits;
     void *kv;
@@ -179,7 +190,7 @@ struct FusedArgsHost {
     int32_t *counters;
     const double *inv_freq;
     long long *prof;                   // optional [blocks][2 * (5 n_layers + 2)] clock stamps
-    unsigned *barrier;                 // zero at launch
+    unsigned *sync;                    // SYNC_WORDS words: launch and layer counts, per-head arrival counters
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
 };
@@ -207,14 +218,12 @@ struct PrefillChunk {
 
 constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused kernel stages per phase
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
-constexpr int BAR_GROUP = 128;         // blocks per group of the two-level device-wide barrier
-constexpr int BAR_TOPS = 2;           // copies of the top counter (the last lines of the group range): a block polls copy blockIdx % BAR_TOPS
-constexpr int BAR_MAX_GROUPS = 63;     // counters: 1 top + one per group, 256 bytes apart
-constexpr int BAR_EPOCH_WORD = 64 * (1 + BAR_MAX_GROUPS);   // barriers passed by all launches since the last reset
-constexpr int BAR_LAYER_WORD = BAR_EPOCH_WORD + 16;         // layers passed by all launches since the last reset
-constexpr int QKV_SYNC_WORD0 = 64 * (2 + BAR_MAX_GROUPS);  // one arrival counter per key/value head, 256 bytes apart
-constexpr int QKV_SYNC_MAX = 64;        // (one lane of a wave per head)
-constexpr int BAR_WORDS = 64 * (2 + BAR_MAX_GROUPS + QKV_SYNC_MAX);
+constexpr int FUSED_MAX_BLOCKS = 1024;                      // largest grid of the fused kernel
+constexpr int SYNC_LAUNCH_WORD = 0;                         // launches of the fused kernel since the last reset (its parity picks the arena)
+constexpr int SYNC_LAYER_WORD = 16;                         // layers passed by all launches since the last reset
+constexpr int QKV_SYNC_WORD0 = 64;                          // one arrival counter per key/value head, 256 bytes apart
+constexpr int QKV_SYNC_MAX = 256;                           // key/value heads the fused kernel has counters for
+constexpr int SYNC_WORDS = 64 * (1 + QKV_SYNC_MAX);
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
 constexpr int ATTN_CHUNK_MIN = 64;    // the fused kernel picks the chunk per step within these bounds

@@ -24,8 +24,9 @@ struct Layout {
     size_t pf_h, pf_h1, pf_q, pf_xhi, pf_xlo, pf_uhi, pf_ulo, pf_rope;   // dense prefix pass arena (0 = none)
     size_t pf_ks_part, pf_ks_count, pf_ks_tiles;
     bool dense;
-    size_t state, barrier, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
+    size_t state, sync, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
+    size_t arena_bytes;      // one activation arena
     int max_splits, n_part, per_part;
     ActLayout al;
 };
@@ -51,14 +52,11 @@ const char *check_cfg(const spd_model_cfg *c) {
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return "rms_eps and rope_theta must be positive";
     const int widest = c->d_model > c->d_ffn ? c->d_model : c->d_ffn;
     if (spdk::gemv_lds_bytes(c->dtype, widest) > 160 * 1024 - 1024) return "d_model / d_ffn too large for the LDS staging";
-    // The persistent kernel's arrival counters are 32-bit and count on from launch to launch
-    // until the next prefix pass zeroes them; at most max_ctx launches lie between two prefix
-    // passes.  Barrier groups count BAR_GROUP arrivals per barrier (at most 5 per layer + 2),
-    // the per-head counters one per row pair of a head's q, k and v rows per layer.
-    const uint64_t launches = (uint64_t)c->max_ctx;
+    // The persistent kernel's per-head arrival counters are 32-bit and count on from launch to
+    // launch until the next prefix pass zeroes them (one per row pair of a head's q, k and v
+    // rows per layer); at most max_ctx launches lie between two prefix passes.
     const uint64_t per_head = (uint64_t)(c->n_heads / c->n_kv_heads + 2) * (uint64_t)(dh / 2);
-    if (launches * (uint64_t)(5 * c->n_layers + 2) * BAR_GROUP >= (1ull << 32) ||
-        launches * (uint64_t)c->n_layers * per_head >= (1ull << 32))
+    if ((uint64_t)c->max_ctx * (uint64_t)(c->n_layers > 0 ? c->n_layers : 1) * per_head >= (1ull << 32))
         return "max_ctx too large for the 32-bit arrival counters of the persistent kernel";
     return nullptr;
 }
@@ -73,7 +71,7 @@ Layout make_layout(const spd_model_cfg &c) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
     L.state = take(sizeof(DevState));
-    L.barrier = take((size_t)BAR_WORDS * 4);
+    L.sync = take((size_t)SYNC_WORDS * 4);
     L.layers_dev = take((size_t)(c.n_layers > 0 ? c.n_layers : 1) * sizeof(spd_layer_weights));
     L.prof = take((size_t)FUSED_PROF_BLOCKS * (size_t)(2 * (5 * c.n_layers + 2)) * 8);   // phase clocks per block
     {   // one address per produced vector (see ActLayout)
@@ -82,7 +80,8 @@ Layout make_layout(const spd_model_cfg &c) {
         L.al.layer0 = vd;
         L.al.q = 0; L.al.att = vq; L.al.h1 = 2 * vq; L.al.u = 2 * vq + vd; L.al.h2 = 2 * vq + vd + vu;
         L.al.stride = 2 * vq + 2 * vd + vu;
-        L.act = take(vd + (size_t)c.n_layers * L.al.stride);
+        L.arena_bytes = up(vd + (size_t)c.n_layers * L.al.stride);
+        L.act = take(2 * L.arena_bytes);   // the fused kernel alternates between two arenas (see ACT_UNSET)
     }
     L.logits = take((size_t)c.vocab * 4);
     L.part = take((size_t)c.n_heads * L.max_splits * (dh + 2) * 4);
@@ -226,11 +225,11 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.sup = sa;
         f.layers = c->at<spd_layer_weights>(c->L.layers_dev);
         f.final_norm = c->final_norm; f.lm_head = c->lm_head;
-        f.act = act; f.al = al; f.logits = c->at<float>(c->L.logits);
+        f.act = act; f.arena_bytes = c->L.arena_bytes; f.al = al; f.logits = c->at<float>(c->L.logits);
         f.kv = c->ws + c->L.kv; f.kv_layer_bytes = c->L.kv_layer_bytes;
         f.part = c->at<float>(c->L.part); f.counters = c->at<int32_t>(c->L.counters);
         f.inv_freq = c->at<double>(c->L.inv_freq); f.prof = c->timing ? c->at<long long>(c->L.prof) : nullptr;
-        f.barrier = c->at<unsigned>(c->L.barrier);
+        f.sync = c->at<unsigned>(c->L.sync);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
         f.head = head ? 1 : 0; f.eps = m.rms_eps;
@@ -306,6 +305,17 @@ hipError_t enqueue_sample(spd_ctx *c, const spd_sample_cfg &sc, const float *log
     n.hist_tok = c->at<int32_t>(c->L.hist_tok); n.hist_par = c->at<int32_t>(c->L.hist_par);
     n.max_gen = c->cfg.max_ctx;
     return launch(c, KC_NUCLEUS, [&] { return spdk::nucleus(c->stream, n); });
+}
+
+// What the persistent forward kernel carries from launch to launch, back to its initial state:
+// counters zero, every element of both activation arenas ACT_UNSET (and the chunk-arrival
+// counters of the attention merge, which a launch that gave up on a wait may have left short
+// of the count that resets them).
+hipError_t reset_fused_state(spd_ctx *c) {
+    hipError_t e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.sync), 0, SYNC_WORDS);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.counters), 0, c->cfg.n_heads * ATTN_COUNTER_STRIDE);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(c->L.act), (int32_t)ACT_UNSET, (int)(2 * c->L.arena_bytes / 4));
+    return e;
 }
 
 void drop_graph(hipGraphExec_t &g) {
@@ -443,7 +453,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
         int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
         if (per_cu > 1) per_cu = 1;
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
-        if (c->fused_blocks > BAR_GROUP * (BAR_MAX_GROUPS - BAR_TOPS)) c->fused_blocks = 0;
+        if (c->fused_blocks > FUSED_MAX_BLOCKS || cfg->n_kv_heads > QKV_SYNC_MAX) c->fused_blocks = 0;
         if (c->fused_blocks > 0 && (4 * cfg->d_model) / (3 * c->fused_blocks) + 4 > FUSED_MAX_EPI) c->fused_blocks = 0;   // residual slice per block (a quarter of the blocks may sit a phase out)
     }
 
@@ -523,11 +533,9 @@ static int run_prefix_pass(spd_ctx *c, int p0, int m) {
     int32_t *hp = (int32_t *)(c->pinned + up(sizeof(DevState)));
     std::memcpy(hp, c->text.data() + p0, (size_t)(m - p0) * 4);
     HIPCHK(c, hipMemcpyAsync(c->st(), hs, sizeof(DevState), hipMemcpyHostToDevice, c->stream));
-    // the persistent kernel's barrier counters run on from launch to launch within a generation
-    HIPCHK(c, spdk::fill_i32(c->stream, c->at<int32_t>(c->L.barrier), 0, BAR_WORDS));
-    // (and the chunk-arrival counters of the attention merge: a launch that gave up on a wait
-    // may have left some of them short of the count that resets them)
-    HIPCHK(c, spdk::fill_i32(c->stream, c->at<int32_t>(c->L.counters), 0, c->cfg.n_heads * ATTN_COUNTER_STRIDE));
+    // the persistent kernel's launch / layer counts and per-head counters run on from launch to
+    // launch within a generation, and it expects both activation arenas unset
+    HIPCHK(c, reset_fused_state(c));
     HIPCHK(c, hipMemcpyAsync(c->ws + c->L.prefix + (size_t)p0 * 4, hp, (size_t)(m - p0) * 4, hipMemcpyHostToDevice, c->stream));
     c->state = ST_CREATED;
     c->pos = p0; c->n_gen = 0; c->k = 0;
@@ -935,7 +943,11 @@ int spd_set_graph(spd_ctx *c, int32_t enable) {
 int spd_set_fused(spd_ctx *c, int32_t enable) {
     if (!c) return SPD_EINVAL;
     if (enable && c->fused_blocks == 0) return fail(c, SPD_EINVAL, "no fused forward kernel for this model shape");
-    if ((enable != 0) != c->use_fused) { drop_graph(c->step_exec); drop_graph(c->prefill_exec); drop_graph(c->nucleus_exec); }
+    if ((enable != 0) != c->use_fused) {
+        drop_graph(c->step_exec); drop_graph(c->prefill_exec); drop_graph(c->nucleus_exec);
+        // the per-operator kernels leave plain values in the first arena: unset both again
+        if (enable) HIPCHK(c, reset_fused_state(c));
+    }
     c->use_fused = enable != 0;
     return SPD_OK;
 }

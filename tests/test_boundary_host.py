@@ -44,7 +44,8 @@ def test_workspace_bytes_and_config_validation(pkg):
     arena = 1024 * (3 * 4096 * 4 + 2 * 4096 * 2 + 2 * 11008 * 2 + 64 * 8)
     # partial tiles of the split-k products: two per 32-row tile of the widest product (QKV, 12288 rows), gate + up
     arena += (12288 // 32) * 2 * 2 * 16 * 64 * 4
-    assert kv + arena <= need < kv + arena + 8 * 2 ** 20
+    # the rest: two arenas of per-layer activation vectors (3.6 MB each), logits, history, counters
+    assert kv + arena <= need < kv + arena + 12 * 2 ** 20
     for field, bad in [("dtype", 7), ("n_heads", 3), ("n_kv_heads", 5), ("k_max", 17), ("k_max", 0), ("max_ctx", 1),
                        ("vocab", 31999), ("d_ffn", 11004), ("d_model", 0)]:
         c = pkg.binding.model_cfg(synth.LLAMA7B, 128, 8)
@@ -121,13 +122,13 @@ def test_device_error_word_maps_to_ehip(pkg):
 
 
 def test_max_ctx_is_bounded_by_the_32_bit_arrival_counters(pkg):
-    """The persistent kernel's arrival counters count on from launch to launch between two
-    prefix passes: a context so long that they could wrap is refused when the context is
+    """The persistent kernel's per-head arrival counters count on from launch to launch between
+    two prefix passes: a context so long that they could wrap is refused when the context is
     sized, not found out at run time."""
-    ok = pkg.binding.model_cfg(synth.LLAMA7B, 200_000, 8)
+    ok = pkg.binding.model_cfg(synth.LLAMA7B, 690_000, 8)
     assert pkg.spd_workspace_bytes(ok) > 0
-    with pytest.raises(pkg.SpdError) as e:
-        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA7B, 210_000, 8))     # 162 barriers x 128 arrivals x 210k launches > 2^32
+    with pytest.raises(pkg.SpdError) as e:     # 32 layers x 192 row pairs per head x 700k launches > 2^32
+        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA7B, 700_000, 8))
     assert e.value.code == -1
     with pytest.raises(pkg.SpdError):
         pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 84_000, 8))
