@@ -125,6 +125,11 @@ __device__ __forceinline__ u32x4 coherent_load16(__amdgpu_buffer_rsrc_t rsrc, ui
     asm volatile("" ::: "memory");
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 16);   // 16 = sc1: device scope
 }
+// The same look through the L2 (no scope bits): for data whose producer finished long ago.
+__device__ __forceinline__ u32x4 cached_look16(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset) {
+    asm volatile("" ::: "memory");
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_offset, 0, 0);
+}
 // The twin of an activation element in the other arena (see ACT_UNSET).
 __device__ __forceinline__ float *twin_of(float *p, long long twin) { return (float *)((char *)p + twin); }
 __device__ __forceinline__ void twin_unset(float *p, long long twin) {

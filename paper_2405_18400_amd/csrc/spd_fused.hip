@@ -33,8 +33,9 @@ namespace {
 // flight per wave.  (1024 threads = two such row groups with half the registers.)
 constexpr int FUSED_UA = 16;          // rows per tile where one pass covers a row
 constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
-constexpr int FUSED_QD = 12;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
-constexpr int FUSED_SLICE = 3;        // of which this many go out between two looks at the input
+constexpr int FUSED_QD = 20;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
+constexpr int FUSED_QD_ITEM = 12;     // of which this many are requested before an attention item (they stay in registers through it)
+constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
 static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
@@ -43,13 +44,16 @@ constexpr int QKV_SLEEP = 1;          // the same between two polls of a head's 
 constexpr int NT = 512;               // threads per block
 constexpr int NW = 8;                 // waves side by side on one row
 constexpr int MAX_U = 32;
+constexpr int MAX_SLOTS = 128;       // partial sums (rows x passes) a tile may leave in LDS per row group
+constexpr int FUSED_UPM = 16;        // rows per tile (= pieces per lane in flight) of a pass-major phase
+constexpr bool FUSED_PM_CACHED = false;   // a pass-major phase reads all passes of its input but the last through the L2
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
 constexpr int MAX_EPI = FUSED_MAX_EPI;   // residual values a block may need in one phase
 
 struct FusedShared {
-    float part[2][NG][MAX_U][NW]; // [buffer][row group][tile slot][wave]
+    float part[2][NG][MAX_SLOTS][NW]; // [buffer][row group][tile slot][wave]
     float epi[MAX_EPI];           // this block's slice of the residual, staged when the phase starts
     float2 rope[128];             // (cos, sin) of this step's position, all d_head / 2 <= 128 pairs
     float red[NT / WAVE];
@@ -79,7 +83,7 @@ __device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
     r.resid = uniform(a.resid); r.y = uniform(a.y); r.rows = uniform(a.rows); r.cols = uniform(a.cols);
     r.kcache = uniform(a.kcache); r.vcache = uniform(a.vcache);
     r.n_q_rows = uniform(a.n_q_rows); r.n_kv_rows = uniform(a.n_kv_rows); r.d_head = uniform(a.d_head);
-    r.cap_ctx = uniform(a.cap_ctx); r.first_block = uniform(a.first_block);
+    r.cap_ctx = uniform(a.cap_ctx); r.first_block = uniform(a.first_block); r.chunk_span = uniform(a.chunk_span);
     return r;
 }
 
@@ -104,21 +108,41 @@ struct Prof {
     __device__ __forceinline__ void go(unsigned point) const { if (p && threadIdx.x == 0) as_global(p)[2 * point + 1] = wall_clock64(); }
 };
 
+// Where a block stands in its walk through a phase: chunk j, of which it owns units [lo, hi),
+// tile at unit u0.
+struct Cursor { int j, lo, hi, u0; };
+
 // A phase keeps ONE tile of U rows x P passes (NS = U * P 16-byte pieces per lane) in
 // registers.  The moment a piece has been multiplied in, its register is re-used for the same
 // piece of the block's next tile, so a wave always has about NS loads in flight.
 // Loads are never predicated: a row past the block's range re-reads the last valid row (a
 // cache hit), and a column past the row end lies outside the buffer descriptor, which
 // describes one row (zeros come back, nothing is fetched); the inner loop has no branches.
-template <typename WT, int P, int U, int EPI, int NBUF, int SL>
+//
+// Chunks (a.chunk_span > 0): the phase's units are cut into chunks of chunk_span units, every
+// block owns a balanced range of EVERY chunk and walks chunk after chunk.  All blocks together
+// therefore complete the output vector front to back, a chunk at a time, and a consumer that
+// needs the vector a column pass at a time (below) finds its first passes long before the
+// phase ends.
+//
+// PM ("pass-major", for a phase whose rows take P >= 2 column passes): a tile is U rows, walked
+// pass by pass -- all U rows against pass 0 of x, then against pass 1, ... -- with U pieces per
+// lane in flight (piece (p, s) is re-requested as (p + 1, s), the last pass as the next tile's
+// pass 0).  Pass p of x is needed only when the walk gets there: the phase starts as soon as
+// pass 0 is complete and looks at the later passes, a tile's pass ahead each, while it streams.
+// With a producer that works in chunks of one pass width, only the last pass's chunk is still
+// being written when the phase starts, and it is needed a tile's (P - 1) / P later.
+template <typename WT, int P, int U, int EPI, int NBUF, int SL, bool PM = false, bool CHUNKS = false>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
     static constexpr int XP = VEC / 4;   // 16-byte pieces of x per pass and lane
     static constexpr int UT = U / 2;     // units per tile
-    static constexpr int NS = U * P;
-    static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U, "tile does not fit the register window");
+    static constexpr int NS = PM ? U : U * P;   // pieces per lane in flight
+    static constexpr int PASS_COLS = NW * WAVE * VEC;   // columns of a row the block covers per pass
+    static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U && U * P <= MAX_SLOTS, "tile does not fit the register window");
     static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
     static_assert(P * XP <= 32, "one bit per piece of x");
+    static_assert(!PM || (P >= 2 && EPI == EPI_RESID), "pass-major tiles: several passes, no normalisation of x");
 
     static __device__ __forceinline__ int n_units(const GemvArgs &a) { return EPI == EPI_SWIGLU ? a.rows : a.rows / 2; }
 
@@ -129,10 +153,42 @@ struct Gemv {
         return (uint32_t)c * (uint32_t)sizeof(WT);   // past the row end: the load returns zero
     }
 
-    // Piece q = s * P + p of this wave's row group within the block tile starting at unit u0
-    // (a block tile is NG * UT units) of a block whose range ends at u_end.
-    static __device__ __forceinline__ u32x4 piece(const GemvArgs &a, int u0, int u_end, int q, const uint32_t (&coff)[P]) {
-        const int s = q / P, p = q % P;
+    static __device__ __forceinline__ int n_chunks(const GemvArgs &a) {
+        return CHUNKS ? (n_units(a) + a.chunk_span - 1) / a.chunk_span : 1;
+    }
+    static __device__ __forceinline__ void chunk_range(const GemvArgs &a, int j, int &lo, int &hi) {
+        const int n = n_units(a);
+        const int base = CHUNKS ? j * a.chunk_span : 0;
+        const int len = CHUNKS ? min(a.chunk_span, n - base) : n;
+        block_range(len, blockIdx.x, gridDim.x, lo, hi, a.first_block);
+        lo += base; hi += base;
+    }
+    // The block's first tile; false: the block owns no unit of this phase.
+    static __device__ __forceinline__ bool first_tile(const GemvArgs &a, Cursor &c) {
+        const int nc = n_chunks(a);
+        for (c.j = 0; c.j < nc; ++c.j) {
+            chunk_range(a, c.j, c.lo, c.hi);
+            if (c.lo < c.hi) { c.u0 = c.lo; return true; }
+        }
+        return false;
+    }
+    // The tile after c; false: c is the block's last tile.
+    static __device__ __forceinline__ bool next_tile(const GemvArgs &a, const Cursor &c, Cursor &n) {
+        n = c;
+        n.u0 += NG * UT;
+        if (n.u0 < n.hi) return true;
+        if (!CHUNKS) return false;
+        const int nc = n_chunks(a);
+        while (++n.j < nc) {
+            chunk_range(a, n.j, n.lo, n.hi);
+            if (n.lo < n.hi) { n.u0 = n.lo; return true; }
+        }
+        return false;
+    }
+
+    // Row slot s, pass p of this wave's row group within the block tile starting at unit u0
+    // (a block tile is NG * UT units) of a chunk range that ends at u_end.
+    static __device__ __forceinline__ u32x4 piece_sp(const GemvArgs &a, int u0, int u_end, int s, int p, const uint32_t (&coff)[P]) {
         const int g = __builtin_amdgcn_readfirstlane(threadIdx.x / (WAVE * NW));
         const int unit = min(u0 + g * UT + (EPI == EPI_SWIGLU ? (s % UT) : (s / 2)), u_end - 1);
         const uint32_t row_bytes = (uint32_t)a.cols * (uint32_t)sizeof(WT);
@@ -140,56 +196,55 @@ struct Gemv {
         const int row = EPI == EPI_SWIGLU ? unit : 2 * unit + (s & 1);
         return stream_load16(row_resource(W + (size_t)row * row_bytes, row_bytes), coff[p]);
     }
+    // Piece q of the tile in the order the registers hold it: row-major q = s * P + p; pass-major:
+    // the U rows of pass 0.
+    static __device__ __forceinline__ u32x4 piece(const GemvArgs &a, int u0, int u_end, int q, const uint32_t (&coff)[P]) {
+        return PM ? piece_sp(a, u0, u_end, q, 0, coff) : piece_sp(a, u0, u_end, q / P, q % P, coff);
+    }
+
+    // Piece q of a pass-major tile for a predecessor phase that requests it (see tile, MODE 2):
+    // the lane's column offset of pass 0 is the same in every phase.
+    static __device__ __forceinline__ u32x4 piece0(const GemvArgs &a, int u0, int u_end, int q, uint32_t coff0) {
+        static_assert(PM, "only a pass-major phase is requested by its predecessor");
+        uint32_t coff[P];
+        coff[0] = coff0;
+        return piece_sp(a, u0, u_end, q, 0, coff);
+    }
 
     // The head of a block's first tile, pieces [0, QD), goes out while the input is awaited;
     // the rest follows once the input is there.
     static constexpr int QD = NS < FUSED_QD ? NS : FUSED_QD;
 
-    // Requests pieces [0, QD) at once.  For a block that has other work to do (an attention
+    // Requests pieces [0, QI) at once.  For a block that has other work to do (an attention
     // item) before it can look at this phase's input: run() is then told they are on their way.
+    static constexpr int QI = NS < FUSED_QD_ITEM ? NS : FUSED_QD_ITEM;
     static __device__ __forceinline__ void prefetch(const GemvArgs &a_in, u32x4 (&buf)[NBUF]) {
         const GemvArgs a = uniform(a_in);
-        int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
-        if (lo >= hi) return;
+        Cursor c;
+        if (!first_tile(a, c)) return;
         uint32_t coff[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) coff[p] = col_offset(a, p);
 #pragma unroll
-        for (int q = 0; q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
+        for (int q = 0; q < QI; ++q) buf[q] = piece(a, c.u0, c.hi, q, coff);
     }
 
-    // One tile: U rows of this wave's row group against x, partial sums to LDS, the block
-    // meets, the first NG * UT threads finish their units.  REFILL: every consumed register is
-    // re-requested at once with the same piece of the block's next tile.
-    template <bool REFILL>
-    static __device__ __forceinline__ void tile(const GemvArgs &a, int u0, int lo, int hi, int pos,
-                                                FusedShared &sh, u32x4 (&buf)[NBUF], const float (&xr)[P][VEC],
-                                                const uint32_t (&coff)[P], int pb) {
-        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
+    // The block has met after a tile: the first NG * UT threads finish their units of the tile
+    // at unit u0 (chunk range [lo, hi)); a unit's two sums are spread over NPART slots each.
+    template <int NPART>
+    static __device__ __forceinline__ void finish(const GemvArgs &a, int u0, int lo, int hi, int pos, FusedShared &sh, int pb) {
+        const int tid = threadIdx.x;
         const int eu = min(u0 + tid, hi - 1);
-#pragma unroll
-        for (int s = 0; s < U; ++s) {
-            float acc = 0.f;
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                float f[VEC];
-                Store<WT>::unpack(buf[s * P + p], f);
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
-                if (REFILL) buf[s * P + p] = piece(a, u0 + NG * UT, hi, s * P + p, coff);
-            }
-            acc = wave_sum_last(acc);
-            if (lane == WAVE - 1) sh.part[pb][g][s][w] = acc;
-        }
-        __syncthreads();
         if (tid < NG * UT && u0 + tid < hi) {   // unit u0 + tid: row group tid / UT, pair tid % UT
             const int eg = tid / UT, t = tid % UT;
             const int s0 = EPI == EPI_SWIGLU ? t : 2 * t;
             const int s1 = EPI == EPI_SWIGLU ? t + UT : 2 * t + 1;
             float r0 = 0.f, r1 = 0.f;
 #pragma unroll
-            for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][s0][q]; r1 += sh.part[pb][eg][s1][q]; }
+            for (int p = 0; p < NPART; ++p) {
+#pragma unroll
+                for (int q = 0; q < NW; ++q) { r0 += sh.part[pb][eg][p * U + s0][q]; r1 += sh.part[pb][eg][p * U + s1][q]; }
+            }
             // what the epilogue needs beyond the sums sits in LDS: the tile loop holds no load
             // from global memory but the weights'
             if (EPI == EPI_RESID) {
@@ -204,17 +259,205 @@ struct Gemv {
         }
     }
 
-    // Runs the phase.  `ahead`: pieces [0, QD) of the block's first tile are in `buf` already
-    // (prefetch); otherwise they are requested here, a slice of SL between two looks at x.
+    // One tile: U rows of this wave's row group against x, partial sums to LDS, the block
+    // meets, the first NG * UT threads finish their units.  Every consumed register is
+    // re-requested at once -- MODE 1: with the same piece of the block's next tile (cursor n);
+    // MODE 2 (the phase's last tile): with the same piece of the block's first tile of the NEXT
+    // phase Nx (arguments na, cursor n), whose first pass of input is complete long before this
+    // phase ends -- weights do not depend on activations, and so the stream from HBM does not
+    // run dry at that phase boundary; MODE 0: not at all.
+    template <int MODE, typename Nx>
+    static __device__ __forceinline__ void tile(const GemvArgs &a, const Cursor &c, const Cursor &n, int pos,
+                                                FusedShared &sh, u32x4 (&buf)[NBUF], const float (&xr)[P][VEC],
+                                                const uint32_t (&coff)[P], int pb, const GemvArgs &na) {
+        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
+        if constexpr (MODE == 2) {   // registers the next phase's tile has beyond this one's
+#pragma unroll
+            for (int q = NS; q < Nx::NS; ++q) buf[q] = Nx::piece0(na, n.u0, n.hi, q, coff[0]);
+        }
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            float acc = 0.f;
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                float f[VEC];
+                Store<WT>::unpack(buf[s * P + p], f);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
+                if (MODE == 1) buf[s * P + p] = piece(a, n.u0, n.hi, s * P + p, coff);
+                if constexpr (MODE == 2) { if (s * P + p < Nx::NS) buf[s * P + p] = Nx::piece0(na, n.u0, n.hi, s * P + p, coff[0]); }
+            }
+            acc = wave_sum_last(acc);
+            if (lane == WAVE - 1) sh.part[pb][g][s][w] = acc;
+        }
+        __syncthreads();
+        finish<1>(a, c.u0, c.lo, c.hi, pos, sh, pb);
+    }
+
+    // The lazily awaited input of a pass-major phase: raw pieces, which of them are still unset.
+    struct LazyX {
+        __amdgpu_buffer_rsrc_t xres;
+        int c0;                 // this lane's first column of pass 0
+        u32x4 xv[P][XP];
+        unsigned pend;          // bit p * XP + j: that piece is still missing
+        static constexpr unsigned pass_mask(int p) { return ((1u << XP) - 1u) << (p * XP); }
+        // Passes below CACHED_BELOW are read through the L2 (a producer finished them long ago:
+        // a hit costs no trip across the chip; should a word still read unset, the line is stale
+        // in this L2 from then on, which costs later looks a coherent retry and nothing else:
+        // retries are always coherent).
+        template <int CACHED_BELOW = 0>
+        __device__ __forceinline__ void look(unsigned mask) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+#pragma unroll
+                for (int j = 0; j < XP; ++j)
+                    if (pend & mask & (1u << (p * XP + j)))
+                        xv[p][j] = p < CACHED_BELOW ? cached_look16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u)
+                                                    : coherent_load16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u);
+            }
+        }
+        __device__ __forceinline__ void judge(unsigned mask) {
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < XP; ++j) {
+                    const u32x4 v = xv[p][j];
+                    if ((mask & (1u << (p * XP + j))) && v.x != ACT_UNSET && v.y != ACT_UNSET && v.z != ACT_UNSET && v.w != ACT_UNSET)
+                        pend &= ~(1u << (p * XP + j));
+                }
+        }
+        // Waits (bounded) until none of the pieces in `mask` is missing.  The answer to the last
+        // look is judged outside the loop: inside it the compiler has to assume the look at the
+        // loop's end and waits for EVERY outstanding load, the weight requests behind it included.
+        __device__ __forceinline__ void await(unsigned mask, int *err) {
+            if (__any((pend & mask) != 0)) judge(mask);
+            for (unsigned spins = 0; __any((pend & mask) != 0); ++spins) {
+                if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                    // bounded: the grid is not co-resident (or a producer gave up): raise the flag and go on
+                    __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(INPUT_SLEEP);
+                look(mask);
+                judge(mask);
+            }
+        }
+        __device__ __forceinline__ void take(int p, float (&xr)[P][VEC]) const {
+#pragma unroll
+            for (int j = 0; j < XP; ++j) {
+                xr[p][4 * j] = __uint_as_float(xv[p][j].x); xr[p][4 * j + 1] = __uint_as_float(xv[p][j].y);
+                xr[p][4 * j + 2] = __uint_as_float(xv[p][j].z); xr[p][4 * j + 3] = __uint_as_float(xv[p][j].w);
+            }
+        }
+    };
+
+    // What the predecessor phase sets up of this phase before its own last tile (see tile, MODE
+    // 2): where the block starts and the look at the first pass of its input.
+    struct Pre {
+        Cursor cur;
+        LazyX lx;
+        float resid;  // this thread's element of the block's residual slice
+        bool valid;   // the block owns units of this phase
+    };
+    // Element threadIdx.x of the block's slice of the residual: 2 (hi - lo) <= MAX_EPI = NT values.
+    // It has been complete for a whole phase; read coherently all the same.  (Phases with a
+    // residual are not cut into chunks.)  Requested before anything else of the phase, so that
+    // it does not come back behind the weight stream.
+    static __device__ __forceinline__ float load_resid(const GemvArgs &a, const Cursor &c) {
+        static_assert(MAX_EPI <= NT, "one residual element per thread");
+        const int i = threadIdx.x;
+        return (EPI == EPI_RESID && i < 2 * (c.hi - c.lo)) ? coherent_load(a.resid + 2 * c.lo + i) : 0.f;
+    }
+    static __device__ __forceinline__ void lazy_init(const GemvArgs &a, LazyX &lx) {
+        const int lane = threadIdx.x & (WAVE - 1), w = (threadIdx.x / WAVE) % NW;
+        lx.xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.cols * 4, 0x00020000);
+        lx.c0 = (w * WAVE + lane) * VEC;
+        lx.pend = 0;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+#pragma unroll
+            for (int j = 0; j < XP; ++j) {
+                lx.xv[p][j] = u32x4{0u, 0u, 0u, 0u};   // past the row end: x is 0, nothing to wait for
+                if (lx.c0 + p * PASS_COLS < a.cols) lx.pend |= 1u << (p * XP + j);
+            }
+        }
+    }
+    // (a: scalar copies of the arguments)
+    static __device__ __forceinline__ void early(const GemvArgs &a, Pre &pre) {
+        pre.valid = first_tile(a, pre.cur);
+        if (!pre.valid) return;
+        lazy_init(a, pre.lx);
+        pre.lx.template look<FUSED_PM_CACHED ? P - 1 : 0>(LazyX::pass_mask(0));
+        pre.resid = load_resid(a, pre.cur);
+    }
+
+    // One pass-major tile.  `first`: the block's first tile of the phase, where passes 1 .. P-1 of
+    // x are still to be taken: each is looked at when the pass before it begins, so the answer
+    // comes back behind that pass's weight requests and is there when the pass is reached; only
+    // a pass that is still incomplete then is waited for.
+    template <bool REFILL>
+    static __device__ __forceinline__ void tile_pm(const GemvArgs &a, const Cursor &c, const Cursor &n, int pos,
+                                                   FusedShared &sh, u32x4 (&buf)[NBUF], float (&xr)[P][VEC], LazyX &lx, bool first,
+                                                   int *err, const uint32_t (&coff)[P], int pb) {
+        const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if (first) {
+                if (p > 0) {
+                    lx.await(LazyX::pass_mask(p), err);
+                    lx.take(p, xr);
+                }
+                if (p + 1 < P) lx.template look<FUSED_PM_CACHED ? P - 1 : 0>(LazyX::pass_mask(p + 1));
+            }
+#pragma unroll
+            for (int s = 0; s < U; ++s) {
+                float f[VEC];
+                Store<WT>::unpack(buf[s], f);
+                float acc = 0.f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
+                if (p + 1 < P) buf[s] = piece_sp(a, c.u0, c.hi, s, p + 1, coff);
+                else if (REFILL) buf[s] = piece_sp(a, n.u0, n.hi, s, 0, coff);
+                acc = wave_sum_last(acc);
+                if (lane == WAVE - 1) sh.part[pb][g][p * U + s][w] = acc;
+            }
+        }
+        __syncthreads();
+        finish<P>(a, c.u0, c.lo, c.hi, pos, sh, pb);
+    }
+
+    // Runs the phase.  `ahead`: pieces [0, QI) of the block's first tile are in `buf` already
+    // (prefetch); the others up to QD are requested here, a slice of SL between two looks at x.
     // `pb` (which of the two partial-sum buffers the next tile uses) runs on from phase to
     // phase: wave 0 may still be finishing the previous phase's last tile from the other one.
+    // Nx, na_in: the phase that follows if its first tile is to be requested by this phase's
+    // last tile (HANDOVER; Nx is pass-major), with `npre` left for its run(); PRE: this phase was
+    // set up that way by its predecessor (`pre`), all of its first tile is on its way.
+    template <typename Nx, bool HANDOVER, bool PRE>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, int pos, FusedShared &sh, u32x4 (&buf)[NBUF],
-                                               int &pb, bool ahead, int *err, const Prof &prof, unsigned point) {
+                                               int &pb, bool ahead, int *err, const Prof &prof, unsigned point,
+                                               const GemvArgs &na_in, typename Nx::Pre *npre, Pre *pre) {
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
-        int lo, hi;
-        block_range(n_units(a), blockIdx.x, gridDim.x, lo, hi, a.first_block);
-        if (lo >= hi) { prof.go(point); return; }
+        Cursor cur;
+        if (PRE) {
+            if (!pre->valid) { prof.go(point); return; }
+            cur = pre->cur;
+        } else if (!first_tile(a, cur)) {
+            if constexpr (HANDOVER) {   // no unit of this phase: the next phase's first tile is requested at once
+                const GemvArgs na = uniform(na_in);
+                Nx::early(na, *npre);
+                if (npre->valid) {
+                    const uint32_t coff0 = col_offset(a, 0);
+#pragma unroll
+                    for (int q = 0; q < Nx::NS; ++q) buf[q] = Nx::piece0(na, npre->cur.u0, npre->cur.hi, q, coff0);
+                }
+            }
+            prof.go(point);
+            return;
+        }
+        float rres = 0.f;
+        if (EPI == EPI_RESID) rres = PRE ? pre->resid : load_resid(a, cur);
         // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
         // depend on any activation, so its load goes out first
         uint32_t coff[P];
@@ -226,95 +469,57 @@ struct Gemv {
                 graw[p] = global_load16((const char *)a.gain + min(coff[p], (uint32_t)((a.cols - VEC) * sizeof(WT))));
         }
         // x: every 16-byte piece is loaded until none of its four words reads ACT_UNSET
-        const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.cols * 4, 0x00020000);
-        u32x4 xv[P][XP];
-        unsigned pend = 0;   // bit p * XP + j: that piece is still missing
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int c = ((p * NW + w) * WAVE + lane) * VEC;
-#pragma unroll
-            for (int j = 0; j < XP; ++j) {
-                xv[p][j] = u32x4{0u, 0u, 0u, 0u};   // past the row end: x is 0, nothing to wait for
-                if (c < a.cols) pend |= 1u << (p * XP + j);
-            }
-        }
-        auto look = [&]() {
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                const int c = ((p * NW + w) * WAVE + lane) * VEC;
-#pragma unroll
-                for (int j = 0; j < XP; ++j)
-                    if (pend & (1u << (p * XP + j))) xv[p][j] = coherent_load16(xres, (uint32_t)(c + 4 * j) * 4u);
-            }
-        };
-        auto judge = [&]() {
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-#pragma unroll
-                for (int j = 0; j < XP; ++j) {
-                    const u32x4 v = xv[p][j];
-                    if (v.x != ACT_UNSET && v.y != ACT_UNSET && v.z != ACT_UNSET && v.w != ACT_UNSET) pend &= ~(1u << (p * XP + j));
-                }
-        };
-        look();
-        if (!ahead) {
+        LazyX lx;
+        if (PRE) lx = pre->lx;
+        else lazy_init(a, lx);
+        // what must be complete before the first tile can start: all of x, or its first pass
+        constexpr unsigned NEED = PM ? LazyX::pass_mask(0) : ~0u;
+        if (!PRE) {
+            lx.template look<PM && FUSED_PM_CACHED ? P - 1 : 0>(NEED);
 #pragma unroll
             for (int q0 = 0; q0 < QD; q0 += SL) {
 #pragma unroll
-                for (int q = q0; q < q0 + SL && q < QD; ++q) buf[q] = piece(a, lo, hi, q, coff);
-                if (__any(pend != 0)) {      // the look before this slice has come back: whatever is
-                    judge();                 // still missing is asked for again, behind the slice
-                    if (__any(pend != 0)) look();
+                for (int q = q0; q < q0 + SL && q < QD; ++q)
+                    if (q >= QI || !ahead) buf[q] = piece(a, cur.u0, cur.hi, q, coff);
+                if (__any((lx.pend & NEED) != 0)) {   // the look before this slice has come back: whatever is
+                    lx.judge(NEED);          // still missing is asked for again, behind the slice
+                    if (__any((lx.pend & NEED) != 0)) lx.look(NEED);
                 }
             }
         }
-        for (unsigned spins = 0; __any(pend != 0); ++spins) {
-            judge();
-            if (!__any(pend != 0)) break;
-            if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                // bounded: the grid is not co-resident (or a producer gave up): raise the flag and go on
-                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(INPUT_SLEEP);
-            look();
-        }
+        lx.await(NEED, err);
         prof.go(point);
-        if (QD < NS) {   // the rest of the first tile
+        if (!PRE && QD < NS) {   // the rest of the first tile
 #pragma unroll
-            for (int q = QD; q < NS; ++q) buf[q] = piece(a, lo, hi, q, coff);
+            for (int q = QD; q < NS; ++q) buf[q] = piece(a, cur.u0, cur.hi, q, coff);
         }
         float xr[P][VEC];
-        float ss = 0.f;
+        if (PM) {
+            lx.take(0, xr);
+        } else {
 #pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < XP; ++j) {
-                xr[p][4 * j] = __uint_as_float(xv[p][j].x); xr[p][4 * j + 1] = __uint_as_float(xv[p][j].y);
-                xr[p][4 * j + 2] = __uint_as_float(xv[p][j].z); xr[p][4 * j + 3] = __uint_as_float(xv[p][j].w);
-            }
-        if (EPI == EPI_RESID) {
-            // this block's slice of the residual: 2 (hi - lo) <= MAX_EPI values.  It has been
-            // complete for a whole phase; read coherently all the same, and never taken unset.
+            for (int p = 0; p < P; ++p) lx.take(p, xr);
+        }
+        if (EPI == EPI_RESID) {   // the block's slice of the residual goes to LDS for the epilogues
             __syncthreads();   // wave 0 may still be in the epilogue of the last phase that staged a slice
-            for (int i = tid; i < 2 * (hi - lo); i += NT) {
-                float r = coherent_load(a.resid + 2 * lo + i);
-                for (unsigned spins = 0; __float_as_uint(r) == ACT_UNSET; ++spins) {
+            if (tid < 2 * (cur.hi - cur.lo)) {
+                for (unsigned spins = 0; __float_as_uint(rres) == ACT_UNSET; ++spins) {   // (never taken unset)
                     if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
                         __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         break;
                     }
                     __builtin_amdgcn_s_sleep(INPUT_SLEEP);
-                    r = coherent_load(a.resid + 2 * lo + i);
+                    rres = coherent_load(a.resid + 2 * cur.lo + tid);
                 }
-                sh.epi[i] = r;
+                sh.epi[tid] = rres;
             }
         }
+        if (!PM && a.gain != nullptr) {
+            float ss = 0.f;
 #pragma unroll
-        for (int p = 0; p < P; ++p)
+            for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) ss += xr[p][v] * xr[p][v];
-        if (a.gain != nullptr) {
+                for (int v = 0; v < VEC; ++v) ss += xr[p][v] * xr[p][v];
             const float tot = block_sum<NT>(g == 0 ? ss : 0.f, sh.red);   // every group holds all of x
             const float rs = 1.0f / sqrtf(tot / (float)a.cols + a.eps);
 #pragma unroll
@@ -329,9 +534,23 @@ struct Gemv {
         // its own copy of the loop body.  (A refill under a branch makes the compiler wait
         // for every outstanding load at the loop's back edge: the stream would stop once
         // per tile.)
-        int u0 = lo;
-        for (; u0 + NG * UT < hi; u0 += NG * UT, pb ^= 1) tile<true>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
-        tile<false>(a, u0, lo, hi, pos, sh, buf, xr, coff, pb);
+        Cursor nxt;
+        if (PM) {
+            static_assert(!PM || !HANDOVER, "a pass-major phase hands nothing over");
+            bool first = true;
+            for (; next_tile(a, cur, nxt); cur = nxt, pb ^= 1, first = false) tile_pm<true>(a, cur, nxt, pos, sh, buf, xr, lx, first, err, coff, pb);
+            tile_pm<false>(a, cur, cur, pos, sh, buf, xr, lx, first, err, coff, pb);
+        } else {
+            for (; next_tile(a, cur, nxt); cur = nxt, pb ^= 1) tile<1, Nx>(a, cur, nxt, pos, sh, buf, xr, coff, pb, a);
+            if constexpr (HANDOVER) {
+                const GemvArgs na = uniform(na_in);
+                Nx::early(na, *npre);
+                if (npre->valid) tile<2, Nx>(a, cur, npre->cur, pos, sh, buf, xr, coff, pb, na);
+                else tile<0, Nx>(a, cur, cur, pos, sh, buf, xr, coff, pb, a);
+            } else {
+                tile<0, Nx>(a, cur, cur, pos, sh, buf, xr, coff, pb, a);
+            }
+        }
         pb ^= 1;
     }
 };
@@ -426,12 +645,16 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     // when the blocks busy with attention items leave their rows to the others.
     constexpr int UO = UA + FUSED_UO_EXTRA / PA;
     constexpr int NA = PA * UO;
-    constexpr int NBUF = (NA > PB * UB) ? NA : PB * UB;
+    // The down projection walks its tiles pass by pass, and the gate/up phase before it works in
+    // chunks of one such pass, where d_model is one block pass wide and d_ffn several.
+    constexpr bool PMD = PA == 1 && PB >= 2;
+    constexpr int ND = PMD ? FUSED_UPM : PB * UB;
+    constexpr int NBUF = (NA > ND) ? NA : ND;
     constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
-    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL>;
-    using Down = Gemv<WT, PB, UB, EPI_RESID, NBUF, SL>;
+    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL, false, PMD>;
+    using Down = Gemv<WT, PB, PMD ? FUSED_UPM : UB, EPI_RESID, NBUF, SL, PMD>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF, SL>;
     __shared__ FusedShared sh;
     __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
@@ -471,7 +694,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *q = a.al.vec(act, l, a.al.q), *att = a.al.vec(act, l, a.al.att), *h1 = a.al.vec(act, l, a.al.h1);
         float *u = a.al.vec(act, l, a.al.u), *h2 = a.al.vec(act, l, a.al.h2);
         const GemvArgs cur = qkv_args(a, act, l);
-        Qkv::run(cur, pos, sh, buf, pb, false, err, prof, point++);
+        Qkv::template run<Qkv, false, false>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, nullptr, nullptr);
         prof.done(point);
         qkv_arrive(qkv_sync, cur);
         prof.go(point++);
@@ -510,21 +733,30 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             }
         }
         prof.done(point);
-        Oproj::run(o, pos, sh, buf, pb, has_item, err, prof, point++);
+        Oproj::template run<Oproj, false, false>(o, pos, sh, buf, pb, has_item, err, prof, point++, o, nullptr, nullptr);
         prof.done(point);
 
         GemvArgs f{};
         f.W = w.w_gate; f.W2 = w.w_up; f.gain = w.ffn_norm; f.eps = a.eps; f.x = h1; f.y = u;
         f.rows = a.d_ffn; f.cols = a.d_model; f.twin = twin;
-        GateUp::run(f, pos, sh, buf, pb, false, err, prof, point++);
-        prof.done(point);
-
+        f.chunk_span = PMD ? Down::PASS_COLS : 0;   // the chunks of u are the column passes of the down projection
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn; d.twin = twin;
-        Down::run(d, pos, sh, buf, pb, false, err, prof, point++);
+        if constexpr (PMD) {
+            // the last gate/up tile requests the first tile of the down projection, whose first
+            // pass of input (the first chunk of u) has been complete since early in this phase
+            typename Down::Pre dpre;
+            GateUp::template run<Down, true, false>(f, pos, sh, buf, pb, false, err, prof, point++, d, &dpre, nullptr);
+            prof.done(point);
+            Down::template run<Down, false, true>(d, pos, sh, buf, pb, false, err, prof, point++, d, nullptr, &dpre);
+        } else {
+            GateUp::template run<GateUp, false, false>(f, pos, sh, buf, pb, false, err, prof, point++, f, nullptr, nullptr);
+            prof.done(point);
+            Down::template run<Down, false, false>(d, pos, sh, buf, pb, false, err, prof, point++, d, nullptr, nullptr);
+        }
         prof.done(point);
     }
-    if (a.head) Head::run(head_args(a, act), pos, sh, buf, pb, false, err, prof, point);
+    if (a.head) Head::template run<Head, false, false>(head_args(a, act), pos, sh, buf, pb, false, err, prof, point, head_args(a, act), nullptr, nullptr);
     if (prof.p && threadIdx.x == 0) as_global(prof.p)[2 * (point + 1)] = wall_clock64();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         __hip_atomic_store(as_global(a.sync) + SYNC_LAUNCH_WORD, launch0 + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -93,6 +93,8 @@ struct GemvArgs {
     const double *inv_freq;     // [d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
     int32_t first_block;        // fused kernel: blocks below this index take no rows of this phase
+    int32_t chunk_span;         // fused kernel: the phase's units are cut into chunks of this many, every block owns a
+                                // share of each chunk and walks them in order; 0 = one chunk
     long long twin;             // fused kernel: byte offset from y to the same vector in the other activation arena
                                 // (every element stored to y is accompanied by ACT_UNSET stored there); 0 = none
 };
