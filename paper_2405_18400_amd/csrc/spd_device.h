@@ -274,7 +274,12 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                                           float *dyn, int *s_last, int hq0 = 0, int hq1 = INT_MAX) {
     constexpr int VEC = Store<KT>::VEC;
     constexpr int NWAVE = NT / WAVE;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wid = tid / WAVE;
+    int tid = threadIdx.x;
+    // (the persistent kernel calls this once per layer: without this the compiler computes every
+    // thread-dependent address below once, before the layer loop, and keeps some thirty vector
+    // registers occupied through all the other phases)
+    if (COH) asm volatile("" : "+v"(tid));
+    const int lane = tid & (WAVE - 1), wid = tid / WAVE;
     const int dh = a.d_head;
     const int LPP = dh / VEC;             // lanes per cached position
     const int PPW = WAVE / LPP;           // positions per wave per iteration

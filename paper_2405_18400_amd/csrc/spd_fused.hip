@@ -36,6 +36,8 @@ constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
 constexpr int FUSED_QD = 20;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
 constexpr int FUSED_QD_ITEM = 12;     // of which this many are requested before an attention item (they stay in registers through it)
 constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
+constexpr int FUSED_HAND_QKV = 0;     // pieces of the QKV phase's (LM head's) first tile that the phase before it requests
+constexpr int FUSED_SLICE_GATE = 4;   // the first slice of the gate/up phase (its input follows the attention within a microsecond or two)
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
 static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
@@ -46,7 +48,7 @@ constexpr int NW = 8;                 // waves side by side on one row
 constexpr int MAX_U = 32;
 constexpr int MAX_SLOTS = 128;       // partial sums (rows x passes) a tile may leave in LDS per row group
 constexpr int FUSED_UPM = 16;        // rows per tile (= pieces per lane in flight) of a pass-major phase
-constexpr bool FUSED_PM_CACHED = false;   // a pass-major phase reads all passes of its input but the last through the L2
+constexpr bool FUSED_PM_CACHED = true;    // a pass-major phase reads all passes of its input but the last through the L2
 constexpr int NG = NT / WAVE / NW;   // row groups per block
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
@@ -112,6 +114,78 @@ struct Prof {
 // tile at unit u0.
 struct Cursor { int j, lo, hi, u0; };
 
+// The input vector of a phase as its lanes await it: raw 16-byte pieces (XP per column pass),
+// which of them still read unset.
+template <int P, int VEC>
+struct LazyXT {
+    static constexpr int XP = VEC / 4;
+    static constexpr int PASS_COLS = NW * WAVE * VEC;
+    __amdgpu_buffer_rsrc_t xres;
+    int c0;                 // this lane's first column of pass 0
+    u32x4 xv[P][XP];
+    unsigned pend;          // bit p * XP + j: that piece is still missing
+    static constexpr unsigned pass_mask(int p) { return ((1u << XP) - 1u) << (p * XP); }
+    // Passes below CACHED_BELOW are read through the L2 (a producer finished them long ago:
+    // a hit costs no trip across the chip; should a word still read unset, the line is stale
+    // in this L2 from then on, which costs later looks a coherent retry and nothing else:
+    // retries are always coherent).
+    template <int CACHED_BELOW = 0>
+    __device__ __forceinline__ void look(unsigned mask) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+#pragma unroll
+            for (int j = 0; j < XP; ++j)
+                if (pend & mask & (1u << (p * XP + j)))
+                    xv[p][j] = p < CACHED_BELOW ? cached_look16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u)
+                                                : coherent_load16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u);
+        }
+    }
+    __device__ __forceinline__ void judge(unsigned mask) {
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < XP; ++j) {
+                const u32x4 v = xv[p][j];
+                if ((mask & (1u << (p * XP + j))) && v.x != ACT_UNSET && v.y != ACT_UNSET && v.z != ACT_UNSET && v.w != ACT_UNSET)
+                    pend &= ~(1u << (p * XP + j));
+            }
+    }
+    // Waits (bounded) until none of the pieces in `mask` is missing.  The answer to the last
+    // look is judged outside the loop: inside it the compiler has to assume the look at the
+    // loop's end and waits for EVERY outstanding load, the weight requests behind it included.
+    __device__ __forceinline__ void await(unsigned mask, int *err) {
+        if (__any((pend & mask) != 0)) judge(mask);
+        for (unsigned spins = 0; __any((pend & mask) != 0); ++spins) {
+            if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                // bounded: the grid is not co-resident (or a producer gave up): raise the flag and go on
+                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(INPUT_SLEEP);
+            look(mask);
+            judge(mask);
+        }
+    }
+    __device__ __forceinline__ void take(int p, float (&xr)[P][VEC]) const {
+#pragma unroll
+        for (int j = 0; j < XP; ++j) {
+            xr[p][4 * j] = __uint_as_float(xv[p][j].x); xr[p][4 * j + 1] = __uint_as_float(xv[p][j].y);
+            xr[p][4 * j + 2] = __uint_as_float(xv[p][j].z); xr[p][4 * j + 3] = __uint_as_float(xv[p][j].w);
+        }
+    }
+};
+
+// What the predecessor phase sets up of a phase before its own last tile (see Gemv::tile, MODE
+// 2): where the block starts and, for a pass-major phase, the look at the first pass of its
+// input and the residual.
+template <int P, int VEC>
+struct PreT {
+    Cursor cur;
+    LazyXT<P, VEC> lx;
+    float resid;  // this thread's element of the block's residual slice
+    bool valid;   // the block owns units of this phase
+};
+
 // A phase keeps ONE tile of U rows x P passes (NS = U * P 16-byte pieces per lane) in
 // registers.  The moment a piece has been multiplied in, its register is re-used for the same
 // piece of the block's next tile, so a wave always has about NS loads in flight.
@@ -132,13 +206,15 @@ struct Cursor { int j, lo, hi, u0; };
 // pass 0 is complete and looks at the later passes, a tile's pass ahead each, while it streams.
 // With a producer that works in chunks of one pass width, only the last pass's chunk is still
 // being written when the phase starts, and it is needed a tile's (P - 1) / P later.
-template <typename WT, int P, int U, int EPI, int NBUF, int SL, bool PM = false, bool CHUNKS = false>
+template <typename WT, int P, int U, int EPI, int NBUF, int SL, bool PM = false, bool CHUNKS = false, int SL0 = SL>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
     static constexpr int XP = VEC / 4;   // 16-byte pieces of x per pass and lane
     static constexpr int UT = U / 2;     // units per tile
     static constexpr int NS = PM ? U : U * P;   // pieces per lane in flight
     static constexpr int PASS_COLS = NW * WAVE * VEC;   // columns of a row the block covers per pass
+    using LazyX = LazyXT<P, VEC>;
+    using Pre = PreT<P, VEC>;
     static_assert(U % 2 == 0 && NS <= NBUF && U <= MAX_U && U * P <= MAX_SLOTS, "tile does not fit the register window");
     static_assert(NG * UT <= WAVE, "the epilogue threads must all sit in wave 0");
     static_assert(P * XP <= 32, "one bit per piece of x");
@@ -202,13 +278,13 @@ struct Gemv {
         return PM ? piece_sp(a, u0, u_end, q, 0, coff) : piece_sp(a, u0, u_end, q / P, q % P, coff);
     }
 
-    // Piece q of a pass-major tile for a predecessor phase that requests it (see tile, MODE 2):
-    // the lane's column offset of pass 0 is the same in every phase.
-    static __device__ __forceinline__ u32x4 piece0(const GemvArgs &a, int u0, int u_end, int q, uint32_t coff0) {
-        static_assert(PM, "only a pass-major phase is requested by its predecessor");
+    // Piece q of a tile for a predecessor phase that requests it (see tile, MODE 2): the lane's
+    // column offset of pass 0 is the same in every phase, the other passes follow from it.
+    static __device__ __forceinline__ u32x4 piece_for(const GemvArgs &a, int u0, int u_end, int q, uint32_t coff0) {
         uint32_t coff[P];
-        coff[0] = coff0;
-        return piece_sp(a, u0, u_end, q, 0, coff);
+#pragma unroll
+        for (int p = 0; p < P; ++p) coff[p] = coff0 + (uint32_t)p * (uint32_t)(PASS_COLS * sizeof(WT));
+        return piece(a, u0, u_end, q, coff);
     }
 
     // The head of a block's first tile, pieces [0, QD), goes out while the input is awaited;
@@ -262,18 +338,21 @@ struct Gemv {
     // One tile: U rows of this wave's row group against x, partial sums to LDS, the block
     // meets, the first NG * UT threads finish their units.  Every consumed register is
     // re-requested at once -- MODE 1: with the same piece of the block's next tile (cursor n);
-    // MODE 2 (the phase's last tile): with the same piece of the block's first tile of the NEXT
-    // phase Nx (arguments na, cursor n), whose first pass of input is complete long before this
-    // phase ends -- weights do not depend on activations, and so the stream from HBM does not
-    // run dry at that phase boundary; MODE 0: not at all.
-    template <int MODE, typename Nx>
+    // MODE 2 (the phase's last tile): the first NXQ registers with the same piece of the block's
+    // first tile of the NEXT phase Nx (arguments na, cursor n) -- weights do not depend on
+    // activations, and so the stream from HBM does not run dry at the phase boundary.  All of
+    // the tile where Nx finds its input complete (gate/up -> down); elsewhere only its head:
+    // whatever is requested here is in the compute unit's queue AHEAD of this tile's own stores
+    // and of the next phase's look at its input, and the head is the part that has come back
+    // by then.  MODE 0: not at all.
+    template <int MODE, typename Nx, int NXQ = 0>
     static __device__ __forceinline__ void tile(const GemvArgs &a, const Cursor &c, const Cursor &n, int pos,
                                                 FusedShared &sh, u32x4 (&buf)[NBUF], const float (&xr)[P][VEC],
                                                 const uint32_t (&coff)[P], int pb, const GemvArgs &na) {
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         if constexpr (MODE == 2) {   // registers the next phase's tile has beyond this one's
 #pragma unroll
-            for (int q = NS; q < Nx::NS; ++q) buf[q] = Nx::piece0(na, n.u0, n.hi, q, coff[0]);
+            for (int q = NS; q < NXQ; ++q) buf[q] = Nx::piece_for(na, n.u0, n.hi, q, coff[0]);
         }
 #pragma unroll
         for (int s = 0; s < U; ++s) {
@@ -285,7 +364,7 @@ struct Gemv {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
                 if (MODE == 1) buf[s * P + p] = piece(a, n.u0, n.hi, s * P + p, coff);
-                if constexpr (MODE == 2) { if (s * P + p < Nx::NS) buf[s * P + p] = Nx::piece0(na, n.u0, n.hi, s * P + p, coff[0]); }
+                if constexpr (MODE == 2) { if (s * P + p < NXQ) buf[s * P + p] = Nx::piece_for(na, n.u0, n.hi, s * P + p, coff[0]); }
             }
             acc = wave_sum_last(acc);
             if (lane == WAVE - 1) sh.part[pb][g][s][w] = acc;
@@ -294,71 +373,6 @@ struct Gemv {
         finish<1>(a, c.u0, c.lo, c.hi, pos, sh, pb);
     }
 
-    // The lazily awaited input of a pass-major phase: raw pieces, which of them are still unset.
-    struct LazyX {
-        __amdgpu_buffer_rsrc_t xres;
-        int c0;                 // this lane's first column of pass 0
-        u32x4 xv[P][XP];
-        unsigned pend;          // bit p * XP + j: that piece is still missing
-        static constexpr unsigned pass_mask(int p) { return ((1u << XP) - 1u) << (p * XP); }
-        // Passes below CACHED_BELOW are read through the L2 (a producer finished them long ago:
-        // a hit costs no trip across the chip; should a word still read unset, the line is stale
-        // in this L2 from then on, which costs later looks a coherent retry and nothing else:
-        // retries are always coherent).
-        template <int CACHED_BELOW = 0>
-        __device__ __forceinline__ void look(unsigned mask) {
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-#pragma unroll
-                for (int j = 0; j < XP; ++j)
-                    if (pend & mask & (1u << (p * XP + j)))
-                        xv[p][j] = p < CACHED_BELOW ? cached_look16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u)
-                                                    : coherent_load16(xres, (uint32_t)(c0 + p * PASS_COLS + 4 * j) * 4u);
-            }
-        }
-        __device__ __forceinline__ void judge(unsigned mask) {
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-#pragma unroll
-                for (int j = 0; j < XP; ++j) {
-                    const u32x4 v = xv[p][j];
-                    if ((mask & (1u << (p * XP + j))) && v.x != ACT_UNSET && v.y != ACT_UNSET && v.z != ACT_UNSET && v.w != ACT_UNSET)
-                        pend &= ~(1u << (p * XP + j));
-                }
-        }
-        // Waits (bounded) until none of the pieces in `mask` is missing.  The answer to the last
-        // look is judged outside the loop: inside it the compiler has to assume the look at the
-        // loop's end and waits for EVERY outstanding load, the weight requests behind it included.
-        __device__ __forceinline__ void await(unsigned mask, int *err) {
-            if (__any((pend & mask) != 0)) judge(mask);
-            for (unsigned spins = 0; __any((pend & mask) != 0); ++spins) {
-                if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                    // bounded: the grid is not co-resident (or a producer gave up): raise the flag and go on
-                    __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(INPUT_SLEEP);
-                look(mask);
-                judge(mask);
-            }
-        }
-        __device__ __forceinline__ void take(int p, float (&xr)[P][VEC]) const {
-#pragma unroll
-            for (int j = 0; j < XP; ++j) {
-                xr[p][4 * j] = __uint_as_float(xv[p][j].x); xr[p][4 * j + 1] = __uint_as_float(xv[p][j].y);
-                xr[p][4 * j + 2] = __uint_as_float(xv[p][j].z); xr[p][4 * j + 3] = __uint_as_float(xv[p][j].w);
-            }
-        }
-    };
-
-    // What the predecessor phase sets up of this phase before its own last tile (see tile, MODE
-    // 2): where the block starts and the look at the first pass of its input.
-    struct Pre {
-        Cursor cur;
-        LazyX lx;
-        float resid;  // this thread's element of the block's residual slice
-        bool valid;   // the block owns units of this phase
-    };
     // Element threadIdx.x of the block's slice of the residual: 2 (hi - lo) <= MAX_EPI = NT values.
     // It has been complete for a whole phase; read coherently all the same.  (Phases with a
     // residual are not cut into chunks.)  Requested before anything else of the phase, so that
@@ -385,20 +399,46 @@ struct Gemv {
     // (a: scalar copies of the arguments)
     static __device__ __forceinline__ void early(const GemvArgs &a, Pre &pre) {
         pre.valid = first_tile(a, pre.cur);
-        if (!pre.valid) return;
+        if (!PM || !pre.valid) return;
         lazy_init(a, pre.lx);
         pre.lx.template look<FUSED_PM_CACHED ? P - 1 : 0>(LazyX::pass_mask(0));
         pre.resid = load_resid(a, pre.cur);
+    }
+
+    // Called by the predecessor right behind its last tile (which requested this phase's first
+    // tile): takes the first pass of x and stages the residual.  Done there, in straight-line
+    // code behind the requests, because the compiler counts outstanding loads per path: after
+    // the merge with the path that requested nothing it would wait for every one of them.
+    static __device__ __forceinline__ void settle(const GemvArgs &a, Pre &pre, FusedShared &sh, int *err) {
+        if (!PM) return;   // (others look at their input when they start)
+        pre.lx.await(LazyX::pass_mask(0), err);
+        stage_resid(a, pre.cur, pre.resid, sh, err);
+    }
+    // The block's slice of the residual goes to LDS for the epilogues (visible to them after
+    // the tile's barrier; the last phase that read this buffer lies at least one barrier back).
+    static __device__ __forceinline__ void stage_resid(const GemvArgs &a, const Cursor &c, float r, FusedShared &sh, int *err) {
+        const int tid = threadIdx.x;
+        if (EPI == EPI_RESID && tid < 2 * (c.hi - c.lo)) {
+            for (unsigned spins = 0; __float_as_uint(r) == ACT_UNSET; ++spins) {   // (never taken unset)
+                if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                    __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(INPUT_SLEEP);
+                r = coherent_load(a.resid + 2 * c.lo + tid);
+            }
+            sh.epi[tid] = r;
+        }
     }
 
     // One pass-major tile.  `first`: the block's first tile of the phase, where passes 1 .. P-1 of
     // x are still to be taken: each is looked at when the pass before it begins, so the answer
     // comes back behind that pass's weight requests and is there when the pass is reached; only
     // a pass that is still incomplete then is waited for.
-    template <bool REFILL>
+    template <int MODE, typename Nx, int NXQ = 0>
     static __device__ __forceinline__ void tile_pm(const GemvArgs &a, const Cursor &c, const Cursor &n, int pos,
                                                    FusedShared &sh, u32x4 (&buf)[NBUF], float (&xr)[P][VEC], LazyX &lx, bool first,
-                                                   int *err, const uint32_t (&coff)[P], int pb) {
+                                                   int *err, const uint32_t (&coff)[P], int pb, const GemvArgs &na) {
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -417,10 +457,11 @@ struct Gemv {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc = fmaf(f[v], xr[p][v], acc);
                 if (p + 1 < P) buf[s] = piece_sp(a, c.u0, c.hi, s, p + 1, coff);
-                else if (REFILL) buf[s] = piece_sp(a, n.u0, n.hi, s, 0, coff);
+                else if (MODE == 1) buf[s] = piece_sp(a, n.u0, n.hi, s, 0, coff);
+                else if constexpr (MODE == 2) { if (s < NXQ) buf[s] = Nx::piece_for(na, n.u0, n.hi, s, coff[0]); }
                 acc = wave_sum_last(acc);
                 if (lane == WAVE - 1) sh.part[pb][g][p * U + s][w] = acc;
-            }
+                }
         }
         __syncthreads();
         finish<P>(a, c.u0, c.lo, c.hi, pos, sh, pb);
@@ -430,34 +471,41 @@ struct Gemv {
     // (prefetch); the others up to QD are requested here, a slice of SL between two looks at x.
     // `pb` (which of the two partial-sum buffers the next tile uses) runs on from phase to
     // phase: wave 0 may still be finishing the previous phase's last tile from the other one.
-    // Nx, na_in: the phase that follows if its first tile is to be requested by this phase's
-    // last tile (HANDOVER; Nx is pass-major), with `npre` left for its run(); PRE: this phase was
-    // set up that way by its predecessor (`pre`), all of its first tile is on its way.
-    template <typename Nx, bool HANDOVER, bool PRE>
+    // Nx, na_in, NXQ > 0: the phase that follows and how many pieces of its first tile this
+    // phase's last tile requests (if `hand`), with `npre` left for its run(); AH > 0: this phase was set up
+    // that way by its predecessor (`pre`), pieces [0, AH) of its first tile are on their way (a
+    // pass-major phase: all of the tile, first pass of the input taken, residual staged).
+    template <typename Nx, int NXQ, int AH>
     static __device__ __forceinline__ void run(const GemvArgs &a_in, int pos, FusedShared &sh, u32x4 (&buf)[NBUF],
                                                int &pb, bool ahead, int *err, const Prof &prof, unsigned point,
-                                               const GemvArgs &na_in, typename Nx::Pre *npre, Pre *pre) {
+                                               const GemvArgs &na_in, bool hand, typename Nx::Pre *npre, Pre *pre) {
+        constexpr bool PRE = PM && AH > 0;
+        static_assert(!PM || AH == 0 || AH == NS, "a pass-major phase is handed over whole");
+        static_assert(AH <= QD, "what is on its way is part of what goes out during the wait");
         const GemvArgs a = uniform(a_in);   // keep every address ingredient in scalar registers
         const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = (tid / WAVE) % NW, g = tid / (WAVE * NW);
         Cursor cur;
-        if (PRE) {
+        if (AH > 0) {
             if (!pre->valid) { prof.go(point); return; }
             cur = pre->cur;
         } else if (!first_tile(a, cur)) {
-            if constexpr (HANDOVER) {   // no unit of this phase: the next phase's first tile is requested at once
+            if constexpr (NXQ > 0) {   // no unit of this phase: the next phase's first tile is requested at once
                 const GemvArgs na = uniform(na_in);
-                Nx::early(na, *npre);
+                npre->valid = false;
+                if (hand) Nx::early(na, *npre);
                 if (npre->valid) {
                     const uint32_t coff0 = col_offset(a, 0);
 #pragma unroll
-                    for (int q = 0; q < Nx::NS; ++q) buf[q] = Nx::piece0(na, npre->cur.u0, npre->cur.hi, q, coff0);
+                    for (int q = 0; q < NXQ; ++q) buf[q] = Nx::piece_for(na, npre->cur.u0, npre->cur.hi, q, coff0);
+                    __syncthreads();   // (as run() has it before the residual is staged)
+                    Nx::settle(na, *npre, sh, err);
                 }
             }
             prof.go(point);
             return;
         }
         float rres = 0.f;
-        if (EPI == EPI_RESID) rres = PRE ? pre->resid : load_resid(a, cur);
+        if (EPI == EPI_RESID && !PRE) rres = load_resid(a, cur);
         // this lane's slice of x (RMS-normalised when a gain is given); the gain does not
         // depend on any activation, so its load goes out first
         uint32_t coff[P];
@@ -476,18 +524,20 @@ struct Gemv {
         constexpr unsigned NEED = PM ? LazyX::pass_mask(0) : ~0u;
         if (!PRE) {
             lx.template look<PM && FUSED_PM_CACHED ? P - 1 : 0>(NEED);
+            // (SL0 pieces first, then SL at a time: an input that arrives soon after the phase
+            // starts is seen by the look behind a short first slice)
 #pragma unroll
-            for (int q0 = 0; q0 < QD; q0 += SL) {
+            for (int q0 = 0; q0 < QD; q0 += (q0 == 0 ? SL0 : SL)) {
 #pragma unroll
-                for (int q = q0; q < q0 + SL && q < QD; ++q)
-                    if (q >= QI || !ahead) buf[q] = piece(a, cur.u0, cur.hi, q, coff);
+                for (int q = q0; q < q0 + (q0 == 0 ? SL0 : SL) && q < QD; ++q)
+                    if (q >= AH && (q >= QI || !ahead)) buf[q] = piece(a, cur.u0, cur.hi, q, coff);
                 if (__any((lx.pend & NEED) != 0)) {   // the look before this slice has come back: whatever is
                     lx.judge(NEED);          // still missing is asked for again, behind the slice
                     if (__any((lx.pend & NEED) != 0)) lx.look(NEED);
                 }
             }
         }
-        lx.await(NEED, err);
+        if (!PRE) lx.await(NEED, err);
         prof.go(point);
         if (!PRE && QD < NS) {   // the rest of the first tile
 #pragma unroll
@@ -500,19 +550,9 @@ struct Gemv {
 #pragma unroll
             for (int p = 0; p < P; ++p) lx.take(p, xr);
         }
-        if (EPI == EPI_RESID) {   // the block's slice of the residual goes to LDS for the epilogues
+        if (EPI == EPI_RESID && !PRE) {
             __syncthreads();   // wave 0 may still be in the epilogue of the last phase that staged a slice
-            if (tid < 2 * (cur.hi - cur.lo)) {
-                for (unsigned spins = 0; __float_as_uint(rres) == ACT_UNSET; ++spins) {   // (never taken unset)
-                    if (spins > SPIN_LIMIT || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                        __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(INPUT_SLEEP);
-                    rres = coherent_load(a.resid + 2 * cur.lo + tid);
-                }
-                sh.epi[tid] = rres;
-            }
+            stage_resid(a, cur, rres, sh, err);
         }
         if (!PM && a.gain != nullptr) {
             float ss = 0.f;
@@ -535,21 +575,26 @@ struct Gemv {
         // for every outstanding load at the loop's back edge: the stream would stop once
         // per tile.)
         Cursor nxt;
-        if (PM) {
-            static_assert(!PM || !HANDOVER, "a pass-major phase hands nothing over");
-            bool first = true;
-            for (; next_tile(a, cur, nxt); cur = nxt, pb ^= 1, first = false) tile_pm<true>(a, cur, nxt, pos, sh, buf, xr, lx, first, err, coff, pb);
-            tile_pm<false>(a, cur, cur, pos, sh, buf, xr, lx, first, err, coff, pb);
-        } else {
-            for (; next_tile(a, cur, nxt); cur = nxt, pb ^= 1) tile<1, Nx>(a, cur, nxt, pos, sh, buf, xr, coff, pb, a);
-            if constexpr (HANDOVER) {
-                const GemvArgs na = uniform(na_in);
-                Nx::early(na, *npre);
-                if (npre->valid) tile<2, Nx>(a, cur, npre->cur, pos, sh, buf, xr, coff, pb, na);
-                else tile<0, Nx>(a, cur, cur, pos, sh, buf, xr, coff, pb, a);
-            } else {
-                tile<0, Nx>(a, cur, cur, pos, sh, buf, xr, coff, pb, a);
+        bool first = true;
+        for (; next_tile(a, cur, nxt); cur = nxt, pb ^= 1, first = false) {
+            if constexpr (PM) tile_pm<1, Nx>(a, cur, nxt, pos, sh, buf, xr, lx, first, err, coff, pb, a);
+            else tile<1, Nx>(a, cur, nxt, pos, sh, buf, xr, coff, pb, a);
+        }
+        bool handed = false;
+        if constexpr (NXQ > 0) {
+            const GemvArgs na = uniform(na_in);
+            npre->valid = false;
+            if (hand) Nx::early(na, *npre);
+            if (npre->valid) {
+                if constexpr (PM) tile_pm<2, Nx, NXQ>(a, cur, npre->cur, pos, sh, buf, xr, lx, first, err, coff, pb, na);
+                else tile<2, Nx, NXQ>(a, cur, npre->cur, pos, sh, buf, xr, coff, pb, na);
+                Nx::settle(na, *npre, sh, err);
+                handed = true;
             }
+        }
+        if (!handed) {
+            if constexpr (PM) tile_pm<0, Nx>(a, cur, cur, pos, sh, buf, xr, lx, first, err, coff, pb, a);
+            else tile<0, Nx>(a, cur, cur, pos, sh, buf, xr, coff, pb, a);
         }
         pb ^= 1;
     }
@@ -653,7 +698,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
-    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL, false, PMD>;
+    using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL, false, PMD, FUSED_SLICE_GATE < SL ? FUSED_SLICE_GATE : SL>;
     using Down = Gemv<WT, PB, PMD ? FUSED_UPM : UB, EPI_RESID, NBUF, SL, PMD>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF, SL>;
     __shared__ FusedShared sh;
@@ -687,6 +732,22 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     }
     if (threadIdx.x < dh / 2) sh.rope[threadIdx.x] = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
     u32x4 buf[NBUF];
+    // The head of the first tile of a layer's QKV phase (and of the LM head, whose rows are laid
+    // out the same way) is requested by whatever comes before it: here for layer 0, by the down
+    // projection's last tile afterwards.
+    constexpr int KQ = FUSED_HAND_QKV < Qkv::NS ? FUSED_HAND_QKV : Qkv::NS;
+    static_assert(Qkv::NS == Head::NS && sizeof(typename Qkv::Pre) == sizeof(typename Head::Pre), "the LM head's first tile is requested as a QKV tile");
+    typename Qkv::Pre qpre;
+    qpre.valid = false;
+    if (KQ > 0) {
+        const GemvArgs q0 = uniform(a.n_layers > 0 ? qkv_args(a, act, 0) : head_args(a, act));
+        Qkv::early(q0, qpre);
+        if (qpre.valid) {
+            const uint32_t coff0 = Qkv::col_offset(q0, 0);
+#pragma unroll
+            for (int q = 0; q < KQ; ++q) buf[q] = Qkv::piece_for(q0, qpre.cur.u0, qpre.cur.hi, q, coff0);
+        }
+    }
     prof.done(point);
 
     for (int l = 0; l < a.n_layers; ++l) {
@@ -694,7 +755,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *q = a.al.vec(act, l, a.al.q), *att = a.al.vec(act, l, a.al.att), *h1 = a.al.vec(act, l, a.al.h1);
         float *u = a.al.vec(act, l, a.al.u), *h2 = a.al.vec(act, l, a.al.h2);
         const GemvArgs cur = qkv_args(a, act, l);
-        Qkv::template run<Qkv, false, false>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, nullptr, nullptr);
+        Qkv::template run<Qkv, 0, KQ>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, false, nullptr, &qpre);
         prof.done(point);
         qkv_arrive(qkv_sync, cur);
         prof.go(point++);
@@ -733,7 +794,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             }
         }
         prof.done(point);
-        Oproj::template run<Oproj, false, false>(o, pos, sh, buf, pb, has_item, err, prof, point++, o, nullptr, nullptr);
+        Oproj::template run<Oproj, 0, 0>(o, pos, sh, buf, pb, has_item, err, prof, point++, o, false, nullptr, nullptr);
         prof.done(point);
 
         GemvArgs f{};
@@ -742,21 +803,25 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         f.chunk_span = PMD ? Down::PASS_COLS : 0;   // the chunks of u are the column passes of the down projection
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn; d.twin = twin;
+        // the first tile of what follows this layer: the next layer's QKV phase or the LM head
+        const bool last = l + 1 == a.n_layers;
+        const GemvArgs nq = last ? head_args(a, act) : qkv_args(a, act, l + 1);
+        const bool hand = !last || a.head;
         if constexpr (PMD) {
             // the last gate/up tile requests the first tile of the down projection, whose first
             // pass of input (the first chunk of u) has been complete since early in this phase
             typename Down::Pre dpre;
-            GateUp::template run<Down, true, false>(f, pos, sh, buf, pb, false, err, prof, point++, d, &dpre, nullptr);
+            GateUp::template run<Down, Down::NS, 0>(f, pos, sh, buf, pb, false, err, prof, point++, d, true, &dpre, nullptr);
             prof.done(point);
-            Down::template run<Down, false, true>(d, pos, sh, buf, pb, false, err, prof, point++, d, nullptr, &dpre);
+            Down::template run<Qkv, KQ, Down::NS>(d, pos, sh, buf, pb, false, err, prof, point++, nq, hand, &qpre, &dpre);
         } else {
-            GateUp::template run<GateUp, false, false>(f, pos, sh, buf, pb, false, err, prof, point++, f, nullptr, nullptr);
+            GateUp::template run<GateUp, 0, 0>(f, pos, sh, buf, pb, false, err, prof, point++, f, false, nullptr, nullptr);
             prof.done(point);
-            Down::template run<Down, false, false>(d, pos, sh, buf, pb, false, err, prof, point++, d, nullptr, nullptr);
+            Down::template run<Qkv, KQ, 0>(d, pos, sh, buf, pb, false, err, prof, point++, nq, hand, &qpre, nullptr);
         }
         prof.done(point);
     }
-    if (a.head) Head::template run<Head, false, false>(head_args(a, act), pos, sh, buf, pb, false, err, prof, point, head_args(a, act), nullptr, nullptr);
+    if (a.head) Head::template run<Head, 0, KQ>(head_args(a, act), pos, sh, buf, pb, false, err, prof, point, head_args(a, act), false, nullptr, &qpre);
     if (prof.p && threadIdx.x == 0) as_global(prof.p)[2 * (point + 1)] = wall_clock64();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         __hip_atomic_store(as_global(a.sync) + SYNC_LAUNCH_WORD, launch0 + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
