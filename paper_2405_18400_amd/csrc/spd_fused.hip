@@ -36,7 +36,6 @@ constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
 constexpr int FUSED_QD = 20;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
 constexpr int FUSED_QD_ITEM = 12;     // of which this many are requested before an attention item (they stay in registers through it)
 constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
-constexpr int FUSED_HAND_QKV = 0;     // pieces of the QKV phase's (LM head's) first tile that the phase before it requests
 constexpr int FUSED_SLICE_GATE = 4;   // the first slice of the gate/up phase (its input follows the attention within a microsecond or two)
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
@@ -692,14 +691,16 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int NA = PA * UO;
     // The down projection walks its tiles pass by pass, and the gate/up phase before it works in
     // chunks of one such pass, where d_model is one block pass wide and d_ffn several.
-    constexpr bool PMD = PA == 1 && PB >= 2;
-    constexpr int ND = PMD ? FUSED_UPM : PB * UB;
+    constexpr bool PMD = PB >= 2 && PB <= 4;
+    // (rows per tile: 16, or 20 where a block's 20 rows -- the 13B shape -- would otherwise spill into a second tile)
+    constexpr int UPM = (PA == 2 && PB == 4) ? 20 : FUSED_UPM;
+    constexpr int ND = PMD ? UPM : PB * UB;
     constexpr int NBUF = (NA > ND) ? NA : ND;
     constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
     using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL, false, PMD, FUSED_SLICE_GATE < SL ? FUSED_SLICE_GATE : SL>;
-    using Down = Gemv<WT, PB, PMD ? FUSED_UPM : UB, EPI_RESID, NBUF, SL, PMD>;
+    using Down = Gemv<WT, PB, PMD ? UPM : UB, EPI_RESID, NBUF, SL, PMD>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF, SL>;
     __shared__ FusedShared sh;
     __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
@@ -732,22 +733,6 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     }
     if (threadIdx.x < dh / 2) sh.rope[threadIdx.x] = rope_cos_sin(a.inv_freq, threadIdx.x, pos);
     u32x4 buf[NBUF];
-    // The head of the first tile of a layer's QKV phase (and of the LM head, whose rows are laid
-    // out the same way) is requested by whatever comes before it: here for layer 0, by the down
-    // projection's last tile afterwards.
-    constexpr int KQ = FUSED_HAND_QKV < Qkv::NS ? FUSED_HAND_QKV : Qkv::NS;
-    static_assert(Qkv::NS == Head::NS && sizeof(typename Qkv::Pre) == sizeof(typename Head::Pre), "the LM head's first tile is requested as a QKV tile");
-    typename Qkv::Pre qpre;
-    qpre.valid = false;
-    if (KQ > 0) {
-        const GemvArgs q0 = uniform(a.n_layers > 0 ? qkv_args(a, act, 0) : head_args(a, act));
-        Qkv::early(q0, qpre);
-        if (qpre.valid) {
-            const uint32_t coff0 = Qkv::col_offset(q0, 0);
-#pragma unroll
-            for (int q = 0; q < KQ; ++q) buf[q] = Qkv::piece_for(q0, qpre.cur.u0, qpre.cur.hi, q, coff0);
-        }
-    }
     prof.done(point);
 
     for (int l = 0; l < a.n_layers; ++l) {
@@ -755,7 +740,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         float *q = a.al.vec(act, l, a.al.q), *att = a.al.vec(act, l, a.al.att), *h1 = a.al.vec(act, l, a.al.h1);
         float *u = a.al.vec(act, l, a.al.u), *h2 = a.al.vec(act, l, a.al.h2);
         const GemvArgs cur = qkv_args(a, act, l);
-        Qkv::template run<Qkv, 0, KQ>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, false, nullptr, &qpre);
+        Qkv::template run<Qkv, 0, 0>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, false, nullptr, nullptr);
         prof.done(point);
         qkv_arrive(qkv_sync, cur);
         prof.go(point++);
@@ -803,25 +788,21 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         f.chunk_span = PMD ? Down::PASS_COLS : 0;   // the chunks of u are the column passes of the down projection
         GemvArgs d{};
         d.W = w.w_down; d.x = u; d.resid = h1; d.y = h2; d.rows = a.d_model; d.cols = a.d_ffn; d.twin = twin;
-        // the first tile of what follows this layer: the next layer's QKV phase or the LM head
-        const bool last = l + 1 == a.n_layers;
-        const GemvArgs nq = last ? head_args(a, act) : qkv_args(a, act, l + 1);
-        const bool hand = !last || a.head;
         if constexpr (PMD) {
             // the last gate/up tile requests the first tile of the down projection, whose first
             // pass of input (the first chunk of u) has been complete since early in this phase
             typename Down::Pre dpre;
             GateUp::template run<Down, Down::NS, 0>(f, pos, sh, buf, pb, false, err, prof, point++, d, true, &dpre, nullptr);
             prof.done(point);
-            Down::template run<Qkv, KQ, Down::NS>(d, pos, sh, buf, pb, false, err, prof, point++, nq, hand, &qpre, &dpre);
+            Down::template run<Down, 0, Down::NS>(d, pos, sh, buf, pb, false, err, prof, point++, d, false, nullptr, &dpre);
         } else {
             GateUp::template run<GateUp, 0, 0>(f, pos, sh, buf, pb, false, err, prof, point++, f, false, nullptr, nullptr);
             prof.done(point);
-            Down::template run<Qkv, KQ, 0>(d, pos, sh, buf, pb, false, err, prof, point++, nq, hand, &qpre, nullptr);
+            Down::template run<Down, 0, 0>(d, pos, sh, buf, pb, false, err, prof, point++, d, false, nullptr, nullptr);
         }
         prof.done(point);
     }
-    if (a.head) Head::template run<Head, 0, KQ>(head_args(a, act), pos, sh, buf, pb, false, err, prof, point, head_args(a, act), false, nullptr, &qpre);
+    if (a.head) Head::template run<Head, 0, 0>(head_args(a, act), pos, sh, buf, pb, false, err, prof, point, head_args(a, act), false, nullptr, nullptr);
     if (prof.p && threadIdx.x == 0) as_global(prof.p)[2 * (point + 1)] = wall_clock64();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         __hip_atomic_store(as_global(a.sync) + SYNC_LAUNCH_WORD, launch0 + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
