@@ -166,6 +166,58 @@ def probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args):
     print(json.dumps({"probe_sweep": rows, "workload": shape.name, "prefix": len(prefix), "steps": n_steps}))
 
 
+def phase_clocks(pkg, shape, weights, prefix, k, args):
+    """Where the fused forward kernel spends a layer: every block stamps a clock when it has
+    finished a phase (its outputs are stored: "arrival" at the synchronisation point behind the
+    phase) and when it has the input of the next one ("release").  Per synchronisation point,
+    averaged over the layers and over `steps` timesteps, in microseconds: how long the phase
+    before it took for the last block, how far apart the blocks finish, how long after the last
+    arrival the first / median / last block is released, and the period from one last arrival to
+    the next (these add up to the layer time).  Prints a table, not JSON."""
+    import torch
+    n_steps = min(args.steps, 16)
+    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 8, k_max=max(k, 8))
+    dc = pkg.SpdDecodeCfg(k, 0.0, 1.0, 0.1)
+    sess.spd_prefill(prefix)
+    for _ in range(1 + args.warmup):
+        sess.spd_step(dc, fetch=False)
+    sess.spd_set_kernel_timing(True)
+    L = shape.n_layers
+    names = ["qkv -> attention", "attention -> o_proj", "o_proj -> gate/up", "gate/up -> down", "down -> next qkv"]
+    agg = {}
+    for _ in range(n_steps):
+        sess.spd_step(dc, fetch=False)
+        st = sess.spd_get_phase_clock().astype(np.float64) / 100.0   # [blocks, stamps], microseconds
+        arr, rel = st[:, 0::2], st[:, 1::2]
+        nb = rel.shape[1]
+        last_arr = arr[:, :nb].max(0)
+        d = {"spread": last_arr - arr[:, :nb].min(0), "med_to_last": last_arr - np.median(arr[:, :nb], 0),
+             "rel_first": rel.min(0) - last_arr, "rel_med": np.median(rel, 0) - last_arr, "rel_last": rel.max(0) - last_arr,
+             "phase": np.concatenate([[0], last_arr[1:] - rel.max(0)[:-1]]),
+             "period": np.concatenate([[0], last_arr[1:] - last_arr[:-1]]),
+             "span": np.array([arr.max() - arr[:, 0].min()])}
+        for key, v in d.items():
+            agg[key] = agg.get(key, 0) + v / n_steps
+    t = sess.spd_get_kernel_timing()
+    sess.close()
+    ctx0 = len(prefix) + 2 + args.warmup
+    print(f"# {shape.name}, k = {k}, context {ctx0}..{ctx0 + n_steps - 1}, {n_steps} timesteps; microseconds, averaged over the {L} layers")
+    print(f"# kernel span by the blocks' clocks: {agg['span'][0]:.1f}; fused_forward by HIP events: "
+          f"{t['fused_forward'][0] * 1e3 / t['fused_forward'][1]:.1f} per launch")
+    print(f"{'synchronisation point':<22} {'phase before it':>16} {'arrival spread':>15} {'median->last':>13} "
+          f"{'release first':>14} {'median':>8} {'last':>8} {'period':>8}")
+    tot = 0.0
+    for j, nm in enumerate(names):
+        idx = 1 + 5 * np.arange(L) + j
+        row = [agg[key][idx].mean() for key in ("phase", "spread", "med_to_last", "rel_first", "rel_med", "rel_last", "period")]
+        tot += row[-1]
+        print(f"{nm:<22} {row[0]:16.2f} {row[1]:15.2f} {row[2]:13.2f} {row[3]:14.2f} {row[4]:8.2f} {row[5]:8.2f} {row[6]:8.2f}")
+    ab = algorithmic_bytes(shape, 0)
+    layer_bytes = ab["gemv_qkv"] + ab["gemv_o"] + ab["gemv_gateup"] + ab["gemv_down"]
+    print(f"# per layer: {tot:.2f}; streaming a layer's {layer_bytes / 1e6:.1f} MB of weights at the 8 TB/s peak: "
+          f"{layer_bytes / 8e12 * 1e6:.2f}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +235,8 @@ def main():
     ap.add_argument("--probe-sweep", action="store_true",
                     help="instead of the benchmark: time the n-gram stage (expand_prune kernel) against the "
                          "orders loaded (none, 2..3, 2..4, 2..6) and k = 1, 3, 5, 10; prints one JSON line")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="instead of the benchmark: per-phase clock stamps of the fused forward kernel (a table)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the SPD step is a single-GPU, batch-1 path); "
@@ -210,12 +264,13 @@ def main():
         weights = synth.make_weights_device(shape, seed=0)
     else:
         weights = synth.make_weights(shape, seed=0)
+    prefix = synth.make_prefix_uniform(shape.vocab, m, seed=0) if args.workload == "tiny" else synth.make_prefix_zipf(shape.vocab, m, seed=0)
+    if args.phase_clocks:
+        return phase_clocks(pkg, shape, weights, prefix, k, args)
     if args.workload == "tiny":
         tables = synth.make_ngram_tables_uniform(shape.vocab, {2: entries // 2, 3: entries // 2}, seed=0)
-        prefix = synth.make_prefix_uniform(shape.vocab, m, seed=0)
     else:
         tables = synth.make_ngram_tables_zipf(shape.vocab, entries, seed=0)
-        prefix = synth.make_prefix_zipf(shape.vocab, m, seed=0)
     if args.probe_sweep:
         return probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args)
     sess = pkg.Session(shape, weights, max_ctx=max_ctx, k_max=max(k, 8))
