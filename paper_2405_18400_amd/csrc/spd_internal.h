@@ -129,15 +129,18 @@ struct TopkArgs {
     float tau;
     float *pv;    // [n_part, SPD_K_MAX]
     int32_t *pi;  // [n_part, SPD_K_MAX]
-    float *pm, *ps;  // [n_part]
+    float *pm, *ps;  // [n_part]: largest scaled logit of the slice, sum of exp(z - that)
+    float *pn;       // [n_part]: smallest scaled logit of the slice
 };
 
 struct NucleusArgs {
     const float *logits;
     int32_t vocab;
     DevState *st;
-    const float *pm, *ps;   // per-slice max and sum of exp of logit / tau (topk_partial)
-    int32_t n_part;
+    const float *pm, *ps, *pn;   // per-slice max, sum of exp and min of logit / tau (topk_partial)
+    int32_t n_part, per_part;    // one block per slice of per_part entries
+    unsigned long long *sc_pb;   // scratch, [vocab]: first-level bucket above the probability in 40-bit fixed point
+    unsigned *sc_count;          // blocks that have finished their slice; zero between calls
     float top_p, tau;
     int32_t first, advance;
     int32_t *hist_tok, *hist_par;

@@ -219,7 +219,13 @@ __global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
                 if (lo + tid + q * BLOCK < hi) sm += expf(__fdiv_rn(rv[q], a.tau) - mx);
             for (int i = lo + tid + NR * BLOCK; i < hi; i += BLOCK) sm += expf(__fdiv_rn(a.logits[i], a.tau) - mx);
             sm = block_sum<BLOCK>(sm, red);
-            if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; }
+            float lowest = INFINITY;   // of the logits: x -> x / tau is monotonic
+#pragma unroll
+            for (int q = 0; q < NR; ++q)
+                if (lo + tid + q * BLOCK < hi) lowest = fminf(lowest, rv[q]);
+            for (int i = lo + tid + NR * BLOCK; i < hi; i += BLOCK) lowest = fminf(lowest, a.logits[i]);
+            lowest = -block_max<BLOCK>(-lowest, red);
+            if (tid == 0) { a.pm[b] = mx; a.ps[b] = sm; a.pn[b] = lo < hi ? __fdiv_rn(lowest, a.tau) : INFINITY; }
         }
     }
 }

@@ -24,7 +24,7 @@ struct Layout {
     size_t pf_h, pf_h1, pf_q, pf_xhi, pf_xlo, pf_uhi, pf_ulo, pf_rope;   // dense prefix pass arena (0 = none)
     size_t pf_ks_part, pf_ks_count, pf_ks_tiles;
     bool dense;
-    size_t state, sync, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, kv, total;
+    size_t state, sync, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, pn, nuc_pb, nuc_count, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     size_t arena_bytes;      // one activation arena
     int max_splits, n_part, per_part;
@@ -49,6 +49,7 @@ const char *check_cfg(const spd_model_cfg *c) {
     if (c->max_ctx < 2) return "max_ctx must be >= 2";
     if (c->k_max < 1 || c->k_max > SPD_K_MAX) return "k_max out of range";
     if (c->vocab < c->k_max) return "vocab smaller than k_max";
+    if (c->vocab >= (1 << 20)) return "vocab must be below 2^20";   // the sampler counts entries in 20 bits of a histogram word
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return "rms_eps and rope_theta must be positive";
     const int widest = c->d_model > c->d_ffn ? c->d_model : c->d_ffn;
     if (spdk::gemv_lds_bytes(c->dtype, widest) > 160 * 1024 - 1024) return "d_model / d_ffn too large for the LDS staging";
@@ -94,6 +95,9 @@ Layout make_layout(const spd_model_cfg &c) {
     L.pi = take((size_t)L.n_part * SPD_K_MAX * 4);
     L.pm = take((size_t)L.n_part * 4);
     L.ps = take((size_t)L.n_part * 4);
+    L.pn = take((size_t)L.n_part * 4);
+    L.nuc_pb = take((size_t)c.vocab * 8);      // the nucleus sampler's per-entry scratch
+    L.nuc_count = take(4);
     // dense prefix pass (matrix cores): bf16 weights, d_head <= 128, widths the tiles divide,
     // d_model within what its norm kernel keeps in registers
     L.dense = c.dtype == SPD_DTYPE_BF16 && dh <= 128 && c.d_model % 128 == 0 && c.d_model <= 8192 && c.d_ffn % 128 == 0 &&
@@ -279,7 +283,7 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
 
 hipError_t enqueue_decide(spd_ctx *c, const spd_decode_cfg &dc, const float *logits, int first, int advance) {
     TopkArgs t{logits, c->cfg.vocab, dc.k, c->L.n_part, c->L.per_part, dc.tau,
-               c->at<float>(c->L.pv), c->at<int32_t>(c->L.pi), c->at<float>(c->L.pm), c->at<float>(c->L.ps)};
+               c->at<float>(c->L.pv), c->at<int32_t>(c->L.pi), c->at<float>(c->L.pm), c->at<float>(c->L.ps), c->at<float>(c->L.pn)};
     hipError_t e = launch(c, KC_TOPK, [&] { return spdk::topk_partial(c->stream, t); });
     if (e != hipSuccess) return e;
     ExpandArgs x{};
@@ -296,11 +300,14 @@ hipError_t enqueue_decide(spd_ctx *c, const spd_decode_cfg &dc, const float *log
 // Post-forward part of one nucleus-sampling step: slice statistics, then the sampler.
 hipError_t enqueue_sample(spd_ctx *c, const spd_sample_cfg &sc, const float *logits, int first, int advance) {
     TopkArgs t{logits, c->cfg.vocab, 1, c->L.n_part, c->L.per_part, sc.tau,
-               c->at<float>(c->L.pv), c->at<int32_t>(c->L.pi), c->at<float>(c->L.pm), c->at<float>(c->L.ps)};
+               c->at<float>(c->L.pv), c->at<int32_t>(c->L.pi), c->at<float>(c->L.pm), c->at<float>(c->L.ps), c->at<float>(c->L.pn)};
     hipError_t e = launch(c, KC_TOPK, [&] { return spdk::topk_partial(c->stream, t); });
     if (e != hipSuccess) return e;
     NucleusArgs n{};
-    n.logits = logits; n.vocab = c->cfg.vocab; n.st = c->st(); n.pm = t.pm; n.ps = t.ps; n.n_part = c->L.n_part;
+    n.logits = logits; n.vocab = c->cfg.vocab; n.st = c->st(); n.pm = t.pm; n.ps = t.ps; n.pn = t.pn; n.n_part = c->L.n_part;
+    n.per_part = c->L.per_part;
+    n.sc_pb = c->at<unsigned long long>(c->L.nuc_pb);
+    n.sc_count = c->at<unsigned>(c->L.nuc_count);
     n.top_p = sc.top_p; n.tau = sc.tau; n.first = first; n.advance = advance;
     n.hist_tok = c->at<int32_t>(c->L.hist_tok); n.hist_par = c->at<int32_t>(c->L.hist_par);
     n.max_gen = c->cfg.max_ctx;
@@ -470,6 +477,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, (int32_t *)c->st(), 0, sizeof(DevState) / 4);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads * ATTN_COUNTER_STRIDE);
     if (e == hipSuccess && L.dense) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.pf_ks_count), 0, (int)L.pf_ks_tiles);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.nuc_count), 0, 1);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return SPD_EHIP; }
     *out = c;

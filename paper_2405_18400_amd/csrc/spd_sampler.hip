@@ -3,150 +3,336 @@
 // Superposed Decoding is timed against.  Section 2: keep the smallest set of most probable
 // tokens whose cumulative probability reaches p, renormalise, sample.
 //
-// No sort: with the vocabulary ordered by probability (descending, lower id first among
-// equals) both questions -- where does the nucleus end, which token does the draw u select by
-// inverse CDF -- are "find the largest threshold t such that the probability mass of
-// {tokens >= t} still reaches (exceeds) x", answered by bisection over the 32 bits of an
-// order-preserving integer image of the scaled logit.  One block; every thread keeps its
-// share of the vocabulary in registers; masses are summed in a fixed order.
+// No sort.  With the vocabulary ordered by (probability descending, id ascending) both
+// questions -- where does the nucleus end, which token does the draw u select by inverse CDF --
+// are "the first entry, in that order, whose cumulative probability reaches (exceeds) x".
+// Every entry's probability is a 40-bit fixed-point integer, so that probability masses are
+// sums of integers: exact, and the same in whatever order they are added (the histograms below
+// are built with atomic adds); its 64-bit sort key, ascending in that order, is that integer,
+// inverted, above the token id.
+//
+//   stage A (one block per slice of the vocabulary, all compute units in parallel): scaled
+//     logit z, probability, and a bucket number that is linear in z between the largest and the
+//     smallest z (2048 buckets), stored per entry; the last block to finish goes on alone;
+//   stage B: mass and count per bucket (LDS atomics), prefix sums over the buckets, the bucket
+//     in which the cumulative mass crosses x; should it hold more than a list's worth of
+//     entries it is cut again by key range (2048 sub-buckets per round: at most a few rounds
+//     even where thousands of entries tie); the bucket's entries are then ranked against one
+//     another (all pairs) and the first one whose cumulative mass crosses x is the answer.
+//   The first-level histogram serves both questions.
 #include "spd_device.h"
 
 using namespace spdd;
 
 namespace {
 
-constexpr int SNT = 1024;     // threads
-constexpr int ITEMS = 32;     // vocabulary entries per thread held in registers (vocab <= 32768)
+constexpr int SNT = 1024;          // threads per block
+constexpr int SNW = SNT / WAVE;
+constexpr int NB = 2 * SNT;        // buckets per level: two per thread in the prefix sums
+constexpr int LC = 256;            // entries that are ranked pairwise
+constexpr int ID_BITS = 23;        // token ids in a key (vocab <= 2^23)
+constexpr int ITEMS = 32;          // entries per thread that stage B keeps in registers (vocab <= 32768; else they are re-read)
+constexpr float FX_ONE = 1099511627776.0f;   // 2^40: probability 1 in fixed point
 
-// Order-preserving map float -> uint32 (larger float, larger key).
-__device__ __forceinline__ uint32_t order_key(float z) {
-    const uint32_t b = __float_as_uint(z);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+// Ascending in (probability descending, id ascending); pf < 2^41.
+__device__ __forceinline__ unsigned long long sort_key(unsigned long long pf, int id) {
+    return (((1ull << 41) - 1ull - pf) << ID_BITS) | (unsigned long long)(unsigned)id;
 }
 
-struct Share {                 // one thread's entries i = tid + j * SNT
-    uint32_t key[ITEMS];
-    float p[ITEMS];
+// A sum over the wave that every lane gets (no LDS, no barrier).
+__device__ __forceinline__ float wave_all_sum(float v) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wave_sum_last(v)), WAVE - 1)); }
+__device__ __forceinline__ float wave_all_max(float v) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wave_max_last(v)), WAVE - 1)); }
+
+struct Stage {                                  // LDS of stage B
+    unsigned long long hm[2][NB + 1];          // [level 1 / deeper levels]: per bucket, entry count above mass (one atomic add per
+                                                // entry); then the exclusive prefix sums of both (totals at NB)
+    unsigned long long wm[SNW];                 // per-wave totals of the prefix sums
+    unsigned long long lk[LC], lp[LC], lcum[LC];   // the list: key, probability, mass of the entries up to and including it
+    unsigned lrank[LC];                         // entries of the list before it
+    int lid[LC];
+    unsigned long long kmin, kmax;
+    int found, lastb, n_list, best;
+    int r_id;                                   // result of a search: the entry, its cumulative mass, its position in the order
+    unsigned long long r_mass, r_key;
+    unsigned r_index;
+    int is_last;
 };
 
-// Mass of the entries whose key is >= t.  CACHED: from the registers; else recomputed.
-template <bool CACHED>
-__device__ __forceinline__ float mass_ge(const NucleusArgs &a, const Share &sh, float lse, uint32_t t, float *red) {
-    float m = 0.f;
-    if (CACHED) {
+// A histogram word: entry count (20 bits: vocab <= 2^20... the sums of all masses stay below
+// 2^41) above the mass.
+constexpr int CNT_SHIFT = 44;
+constexpr unsigned long long ONE_ENTRY = 1ull << CNT_SHIFT;
+__device__ __forceinline__ unsigned long long mass_of(unsigned long long w) { return w & (ONE_ENTRY - 1ull); }
+__device__ __forceinline__ unsigned count_of(unsigned long long w) { return (unsigned)(w >> CNT_SHIFT); }
+
+// In place: hm (NB values) -> exclusive prefix sums, totals at index NB.
+__device__ __forceinline__ void prefix_sums(Stage &s, int lv) {
+    const int t = threadIdx.x, lane = t & (WAVE - 1), w = t / WAVE;
+    const unsigned long long a0 = s.hm[lv][2 * t], a1 = s.hm[lv][2 * t + 1];
+    unsigned long long m = a0 + a1;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) m += sh.key[j] >= t ? sh.p[j] : 0.f;
-    } else {
-        for (int i = threadIdx.x; i < a.vocab; i += SNT) {
-            const float z = __fdiv_rn(as_global(a.logits)[i], a.tau);
-            if (order_key(z) >= t) m += expf(z - lse);
-        }
+    for (int o = 1; o < WAVE; o <<= 1) {        // inclusive scan over the wave
+        const unsigned long long um = __shfl_up(m, o, WAVE);
+        if (lane >= o) m += um;
     }
-    return block_sum<SNT>(m, red);
+    if (lane == WAVE - 1) s.wm[w] = m;
+    __syncthreads();
+    unsigned long long pm = 0;
+    for (int q = 0; q < w; ++q) pm += s.wm[q];
+    const unsigned long long em = pm + m - (a0 + a1);
+    s.hm[lv][2 * t] = em; s.hm[lv][2 * t + 1] = em + a0;
+    if (t == SNT - 1) s.hm[lv][NB] = em + a0 + a1;
+    __syncthreads();
 }
 
-// Largest t with mass(>= t) >= x (STRICT: > x).  mass(>= 0) is the whole vocabulary.
-template <bool CACHED, bool STRICT>
-__device__ __forceinline__ uint32_t threshold(const NucleusArgs &a, const Share &sh, float lse, float x, float *red) {
-    uint32_t t = 0u;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = t | (1u << bit);
-        const float m = mass_ge<CACHED>(a, sh, lse, cand, red);
-        if (STRICT ? m > x : m >= x) t = cand;
+// The bucket in which the cumulative mass first reaches x (STRICT: exceeds x), or, if the
+// total does not get there, the last bucket that holds an entry.  Every thread gets it.
+template <bool STRICT>
+__device__ __forceinline__ int crossing(Stage &s, int lv, unsigned long long x) {
+    const int t = threadIdx.x;
+    if (t == 0) { s.found = -1; s.lastb = 0; }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int b = 2 * t + q;
+        const unsigned long long e = mass_of(s.hm[lv][b]), i = mass_of(s.hm[lv][b + 1]);
+        if (STRICT ? (e <= x && i > x) : (e < x && i >= x)) s.found = b;     // one bucket at most
+        if (count_of(s.hm[lv][b + 1]) > count_of(s.hm[lv][b])) atomicMax(&s.lastb, b);
     }
-    return t;
+    __syncthreads();
+    const int b = s.found >= 0 ? s.found : s.lastb;
+    __syncthreads();
+    return b;
 }
 
-// Number of entries with key == t, their (common) probability, and the smallest id > after among them.
+// Per entry, written by stage A: one word with the first-level bucket above the probability
+// (x 2^40).  Written through to memory and read back coherently (the writers sit behind other
+// L2 caches; a device-wide fence would write back and invalidate whole caches -- tens of
+// microseconds -- where this is 8 bytes per entry).
+constexpr int PB_SHIFT = 48;
+constexpr unsigned long long P_MASK = (1ull << PB_SHIFT) - 1ull;
+constexpr unsigned long long NO_ENTRY = ~0ull;
+__device__ __forceinline__ unsigned long long load_pb(const unsigned long long *pb, int i) {
+    return __hip_atomic_load(as_global(pb) + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The entries i = tid, tid + SNT, ... that stage B walks several times.  The first walk reads
+// their words, CH at a time (one dependent trip to memory per CH entries: these walks are
+// chains of latencies, not bandwidth).  CACHED: it leaves the bucket numbers in registers, two
+// per register, and the later walks -- which look for the entries of ONE bucket -- read only
+// the words of those; otherwise every walk reads all words again.
+constexpr int CH = 16;
 template <bool CACHED>
-__device__ __forceinline__ void ties(const NucleusArgs &a, const Share &sh, float lse, uint32_t t, int after,
-                                     int &count, float &p_each, int &next_id, float *red, int *ired) {
-    int c = 0, best = INT_MAX;
-    float pe = 0.f;
-    if (CACHED) {
+struct Entries {
+    const unsigned long long *pb;
+    int vocab;
+    unsigned bk[CACHED ? ITEMS / 2 : 1];
+    // f(i, bucket of entry i, its probability) for every entry of this thread
+    template <typename F>
+    __device__ __forceinline__ void first_walk(F &&f) {
+        const int rounds = CACHED ? ITEMS / CH : (vocab + SNT * CH - 1) / (SNT * CH);
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = threadIdx.x + j * SNT;
-            if (i < a.vocab && sh.key[j] == t) { ++c; pe = sh.p[j]; if (i > after) best = min(best, i); }
-        }
-    } else {
-        for (int i = threadIdx.x; i < a.vocab; i += SNT) {
-            const float z = __fdiv_rn(as_global(a.logits)[i], a.tau);
-            if (order_key(z) == t) { ++c; pe = expf(z - lse); if (i > after) best = min(best, i); }
+        for (int r = 0; r < (CACHED ? ITEMS / CH : 1); ++r) {
+            for (int rr = CACHED ? r : 0; rr < (CACHED ? r + 1 : rounds); ++rr) {
+                unsigned long long w[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int i = threadIdx.x + (rr * CH + c) * SNT;
+                    w[c] = i < vocab ? load_pb(pb, i) : NO_ENTRY;
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int i = threadIdx.x + (rr * CH + c) * SNT;
+                    const unsigned b = (unsigned)(w[c] >> PB_SHIFT);      // NO_ENTRY: 0xFFFF, no bucket
+                    if (CACHED) {
+                        if (c & 1) bk[(r * CH + c) / 2] |= b << 16;
+                        else bk[(r * CH + c) / 2] = b;
+                    }
+                    if (w[c] != NO_ENTRY) f(i, (int)b, w[c] & P_MASK);
+                }
+            }
         }
     }
-    count = (int)(block_sum<SNT>((float)c, red) + 0.5f);
-    p_each = block_max<SNT>(pe, red);
-    // block-wide minimum of `best`
-    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    // f(i, its probability) for every entry of this thread in bucket b1
+    template <typename F>
+    __device__ __forceinline__ void walk_bucket(int b1, F &&f) {
+        if (CACHED) {
+            static_assert(ITEMS <= 32, "one bit per entry");
+            unsigned hits = 0u;
 #pragma unroll
-    for (int o = WAVE / 2; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o, WAVE));
+            for (int c = 0; c < ITEMS; ++c) {
+                const unsigned b = (c & 1) ? bk[c / 2] >> 16 : bk[c / 2] & 0xFFFFu;
+                hits |= (unsigned)((int)b == b1) << c;
+            }
+            while (hits) {   // (few: a bucket holds some dozens of the block's entries)
+                const int c = __ffs(hits) - 1;
+                hits &= hits - 1u;
+                const int i = threadIdx.x + c * SNT;
+                f(i, load_pb(pb, i) & P_MASK);
+            }
+        } else {
+            for (int i0 = threadIdx.x; i0 < vocab; i0 += SNT * CH) {
+                unsigned long long w[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int i = i0 + c * SNT;
+                    w[c] = i < vocab ? load_pb(pb, i) : NO_ENTRY;
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if ((int)(w[c] >> PB_SHIFT) == b1) f(i0 + c * SNT, w[c] & P_MASK);
+            }
+        }
+    }
+};
+
+// The first entry in the order whose cumulative mass reaches (STRICT: exceeds) x; the last
+// entry if none does.  Level-1 prefix sums are in s.hm[0].  Result in s.r_*.
+template <bool STRICT, bool CACHED>
+__device__ __forceinline__ void search(Stage &s, Entries<CACHED> &en, unsigned long long x) {
+    const int t = threadIdx.x;
+    const int b1 = crossing<STRICT>(s, 0, x);
+    unsigned long long base_m = mass_of(s.hm[0][b1]);
+    unsigned base_c = count_of(s.hm[0][b1]);
+    unsigned n = count_of(s.hm[0][b1 + 1]) - base_c;
+    // the candidates: level-1 bucket b1, and within it the key range [klo, khi] once it has been cut
+    unsigned long long klo = 0ull, khi = ~0ull;
+    bool cut = false;
+    while (n > (unsigned)LC) {
+        if (!cut) {   // the key range of the bucket's entries
+            if (t == 0) { s.kmin = ~0ull; s.kmax = 0ull; }
+            __syncthreads();
+            en.walk_bucket(b1, [&](int i, unsigned long long pf) {
+                const unsigned long long k = sort_key(pf, i);
+                atomicMin(&s.kmin, k);
+                atomicMax(&s.kmax, k);
+            });
+            __syncthreads();
+            klo = s.kmin; khi = s.kmax;
+            cut = true;
+        }
+        const unsigned long long width = khi - klo;                 // > 0: more than one entry, keys are distinct
+        const int bits = 64 - __clzll((long long)width);
+        const int sh = bits > 11 ? bits - 11 : 0;                  // (k - klo) >> sh < 2048
+        s.hm[1][2 * t] = 0ull; s.hm[1][2 * t + 1] = 0ull;
+        __syncthreads();
+        en.walk_bucket(b1, [&](int i, unsigned long long pf) {
+            const unsigned long long k = sort_key(pf, i);
+            if (k >= klo && k <= khi) {
+                const int b2 = (int)((k - klo) >> sh);
+                atomicAdd(&s.hm[1][b2], pf + ONE_ENTRY);
+            }
+        });
+        __syncthreads();
+        prefix_sums(s, 1);
+        const int b2 = crossing<STRICT>(s, 1, x - base_m);          // (x >= base_m: the crossing lies in this range or beyond everything)
+        base_m += mass_of(s.hm[1][b2]);
+        base_c += count_of(s.hm[1][b2]);
+        n = count_of(s.hm[1][b2 + 1]) - count_of(s.hm[1][b2]);
+        const unsigned long long lo2 = klo + ((unsigned long long)b2 << sh);
+        const unsigned long long hi2 = lo2 + ((1ull << sh) - 1ull);
+        klo = lo2;
+        khi = hi2 < khi ? hi2 : khi;
+        __syncthreads();
+    }
+    // the candidates into the list (in any order: they are ranked below)
+    if (t == 0) { s.n_list = 0; s.best = INT_MAX; }
+    if (t < LC) { s.lrank[t] = 0u; s.lcum[t] = 0ull; }
     __syncthreads();
-    if (lane == 0) ired[w] = best;
+    en.walk_bucket(b1, [&](int i, unsigned long long pf) {
+        const unsigned long long k = sort_key(pf, i);
+        if (k >= klo && k <= khi) {
+            const int at = atomicAdd(&s.n_list, 1);
+            s.lk[at] = k; s.lp[at] = pf; s.lid[at] = i;
+        }
+    });
     __syncthreads();
-    int r = ired[0];
-    for (int q = 1; q < SNT / WAVE; ++q) r = min(r, ired[q]);
-    next_id = r;
+    const int nl = s.n_list;   // == n
+    {   // all pairs: entry i against a quarter of the list each
+        const int i = t % LC, part = t / LC;
+        constexpr int PARTS = SNT / LC;
+        if (i < nl) {
+            const unsigned long long ki = s.lk[i];
+            unsigned cnt = 0u;
+            unsigned long long mass = 0ull;
+            for (int j = part; j < nl; j += PARTS) {
+                const unsigned long long kj = s.lk[j];
+                if (kj < ki) ++cnt;
+                if (kj <= ki) mass += s.lp[j];
+            }
+            atomicAdd(&s.lrank[i], cnt);
+            atomicAdd(&s.lcum[i], mass);
+        }
+    }
+    __syncthreads();
+    if (t < nl) {
+        const unsigned long long tot = base_m + s.lcum[t];
+        if (STRICT ? tot > x : tot >= x) atomicMin(&s.best, (int)s.lrank[t]);
+    }
+    __syncthreads();
+    const int pick = s.best == INT_MAX ? nl - 1 : s.best;   // nothing reaches x: the last entry
+    if (t < nl && (int)s.lrank[t] == pick) {
+        s.r_id = s.lid[t]; s.r_key = s.lk[t];
+        s.r_mass = base_m + s.lcum[t];
+        s.r_index = base_c + (unsigned)pick;
+    }
+    __syncthreads();
 }
 
 template <bool CACHED>
 __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
-    __shared__ float red[SNT / WAVE];
-    __shared__ int ired[SNT / WAVE];
-    __shared__ float s_lse;
-    const int tid = threadIdx.x;
+    __shared__ Stage s;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     global_ptr<DevState> st = as_global(a.st);
-    if (tid == 0) {   // log-sum-exp of the scaled logits from the per-slice statistics
-        float M = -INFINITY;
-        for (int b = 0; b < a.n_part; ++b) M = fmaxf(M, as_global(a.pm)[b]);
-        float S = 0.f;
-        for (int b = 0; b < a.n_part; ++b) S += as_global(a.ps)[b] * expf(as_global(a.pm)[b] - M);
-        s_lse = M + logf(S);
+    // log-sum-exp, largest and smallest scaled logit from the per-slice statistics (every wave for itself)
+    float M = -INFINITY, mn = INFINITY;
+    for (int b = lane; b < a.n_part; b += WAVE) { M = fmaxf(M, as_global(a.pm)[b]); mn = fminf(mn, as_global(a.pn)[b]); }
+    M = wave_all_max(M);
+    mn = -wave_all_max(-mn);
+    float S = 0.f;
+    for (int b = lane; b < a.n_part; b += WAVE) S += as_global(a.ps)[b] * expf(as_global(a.pm)[b] - M);
+    const float lse = M + logf(wave_all_sum(S));
+    const float range = M - mn;
+    const float scale = range > 0.f ? (float)NB / range : 0.f;
+
+    // ---- stage A: this block's slice
+    const int lo = blockIdx.x * a.per_part, hi = min(a.vocab, lo + a.per_part);
+    for (int i = lo + tid; i < hi; i += SNT) {
+        const float z = __fdiv_rn(as_global(a.logits)[i], a.tau);
+        const float p = expf(z - lse);
+        const float fb = (M - z) * scale;                          // monotonic in z; anything beyond lands in the last bucket
+        const int b = fb < (float)(NB - 1) ? (int)fb : NB - 1;
+        const unsigned long long pf = (unsigned long long)(p * FX_ONE);   // <= 2^40 (1 + a few ulp)
+        __hip_atomic_store(as_global(a.sc_pb) + i, ((unsigned long long)(b < 0 ? 0 : b) << PB_SHIFT) | pf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's write-through stores have been acknowledged
     __syncthreads();
-    const float lse = s_lse;
-    Share sh;
-    if (CACHED) {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = tid + j * SNT;
-            sh.key[j] = 0u; sh.p[j] = 0.f;
-            if (i < a.vocab) {
-                const float z = __fdiv_rn(as_global(a.logits)[i], a.tau);
-                sh.key[j] = order_key(z);
-                sh.p[j] = expf(z - lse);
-            }
-        }
-    }
-    // 1. the nucleus: keys > T entirely, of the keys == T the `need` lowest ids
-    const uint32_t T = threshold<CACHED, false>(a, sh, lse, a.top_p, red);
-    const float above_T = T == 0xFFFFFFFFu ? 0.f : mass_ge<CACHED>(a, sh, lse, T + 1u, red);
-    int n_T, dummy;
-    float p_T;
-    ties<CACHED>(a, sh, lse, T, -1, n_T, p_T, dummy, red, ired);
-    int need = 1;
-    while (need < n_T && above_T + (float)need * p_T < a.top_p) ++need;
-    const float mass = above_T + (float)need * p_T;
-    // 2. the draw: first token, in that order, whose cumulative probability exceeds u * mass
-    const float target = st->sample_u * mass;
-    uint32_t S = threshold<CACHED, true>(a, sh, lse, target, red);
-    if (S < T) S = T;                                   // (only rounding could take it below)
-    const float above_S = S == 0xFFFFFFFFu ? 0.f : mass_ge<CACHED>(a, sh, lse, S + 1u, red);
-    int n_S, tok;
-    float p_S;
-    ties<CACHED>(a, sh, lse, S, -1, n_S, p_S, tok, red, ired);
-    int skip = p_S > 0.f ? (int)floorf(fmaxf(target - above_S, 0.f) / p_S) : 0;
-    skip = min(skip, (S == T ? need : n_S) - 1);
-    for (int r = 0; r < skip; ++r) ties<CACHED>(a, sh, lse, S, tok, n_S, p_S, tok, red, ired);
-    // nucleus size = entries with key > T plus `need`
-    float cnt = 0.f;
-    if (CACHED) {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) cnt += (tid + j * SNT < a.vocab && sh.key[j] > T) ? 1.f : 0.f;
-    } else {
-        for (int i = tid; i < a.vocab; i += SNT) cnt += order_key(__fdiv_rn(as_global(a.logits)[i], a.tau)) > T ? 1.f : 0.f;
-    }
-    const int size = (int)(block_sum<SNT>(cnt, red) + 0.5f) + need;
+    if (tid == 0) s.is_last = (__hip_atomic_fetch_add(as_global(a.sc_count), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(gridDim.x - 1));
+    __syncthreads();
+    if (!s.is_last) return;
+
+    // ---- stage B: first-level histogram
+    Entries<CACHED> en;
+    en.pb = a.sc_pb; en.vocab = a.vocab;
+    s.hm[0][2 * tid] = 0ull; s.hm[0][2 * tid + 1] = 0ull;
+    __syncthreads();
+    en.first_walk([&](int, int b, unsigned long long pf) {
+        atomicAdd(&s.hm[0][b], pf + ONE_ENTRY);
+    });
+    __syncthreads();
+    prefix_sums(s, 0);
+
+    // 1. the nucleus: the first entry whose cumulative probability reaches top_p, and all before it
+    const unsigned long long x_p = (unsigned long long)((double)a.top_p * (double)FX_ONE);
+    search<false, CACHED>(s, en, x_p);
+    const unsigned long long mass_fx = s.r_mass, key_T = s.r_key;
+    const unsigned size = s.r_index + 1u;
+    const int id_T = s.r_id;
+    __syncthreads();
+    // 2. the draw: the first entry whose cumulative probability exceeds u * mass (within the nucleus)
+    const unsigned long long x_u = (unsigned long long)((double)st->sample_u * (double)mass_fx);
+    search<true, CACHED>(s, en, x_u);
+    int tok = s.r_id;
+    if (s.r_key > key_T) tok = id_T;   // (only rounding could take it past the nucleus)
 
     if (tid == 0) {   // the pass's state: one draft (k = 1, gamma = 1)
         const float logp = __fdiv_rn(as_global(a.logits)[tok], a.tau) - lse;
@@ -162,11 +348,12 @@ __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
         st->top_logp[0] = logp;
         const int gen = a.first ? 0 : st->n_gen;
         if (gen < a.max_gen) { as_global(a.hist_tok)[(size_t)gen * SPD_K_MAX] = tok; as_global(a.hist_par)[(size_t)gen * SPD_K_MAX] = a.first ? -1 : 0; }
-        st->nucleus_size = size;
-        st->nucleus_mass = mass;
+        st->nucleus_size = (int)size;
+        st->nucleus_mass = (float)((double)mass_fx / (double)FX_ONE);
         st->k = 1;
         st->n_gen = gen + 1;
         if (a.advance) st->pos += 1;
+        __hip_atomic_store(as_global(a.sc_count), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
     }
 }
 
@@ -175,8 +362,8 @@ __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
 namespace spdk {
 
 hipError_t nucleus(hipStream_t s, const NucleusArgs &a) {
-    if (a.vocab <= SNT * ITEMS) hipLaunchKernelGGL(nucleus_kernel<true>, dim3(1), dim3(SNT), 0, s, a);
-    else hipLaunchKernelGGL(nucleus_kernel<false>, dim3(1), dim3(SNT), 0, s, a);
+    if (a.vocab <= SNT * ITEMS) hipLaunchKernelGGL(nucleus_kernel<true>, dim3(a.n_part), dim3(SNT), 0, s, a);
+    else hipLaunchKernelGGL(nucleus_kernel<false>, dim3(a.n_part), dim3(SNT), 0, s, a);
     return hipGetLastError();
 }
 
