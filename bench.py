@@ -373,8 +373,11 @@ def main():
     assert 0 <= ntok < shape.vocab and np.isfinite(nlp)
 
     # the prefix pass alone (the first-timestep forward over M), dense on the matrix cores where
-    # the model allows it: tokens/s, and model flops (2 x parameters of the layers x tokens; the
-    # matrix cores do twice that, each activation being fed as a hi + lo bf16 pair)
+    # the model allows it: tokens/s, and the two rooflines by ALGORITHMIC work -- model flops
+    # (2 x parameters of the layers x tokens) against the dense bf16 MFMA peak, and one pass over
+    # the weights against the HBM peak (short chunks are bound by the latter).  The kernels feed
+    # every activation as a hi + lo bf16 pair, i.e. issue twice the model's products: that is
+    # their own overhead and is not counted.
     sess.spd_prefill(prefix)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -382,12 +385,13 @@ def main():
     torch.cuda.synchronize()
     prefill_ms = (time.perf_counter() - t2) * 1e3
     layer_params = shape.streamed_params() - shape.vocab * shape.d_model
+    es = 2 if shape.dtype == "bf16" else 4
     prefill = {"tokens": m, "ms": prefill_ms, "tokens_per_s": m / prefill_ms * 1e3,
                "dense": bool(sess.spd_get_dense_prefill()),
-               "model_tflops": 2.0 * layer_params * m / (prefill_ms * 1e-3) / 1e12}
-    if prefill["dense"]:
-        prefill["mfma_tflops"] = 2.0 * prefill["model_tflops"]
-        prefill["mfma_frac_of_bf16_peak"] = prefill["mfma_tflops"] / 2500.0
+               "model_tflops": 2.0 * layer_params * m / (prefill_ms * 1e-3) / 1e12,
+               "weight_pass_GBps": shape.streamed_params() * es / (prefill_ms * 1e-3) / 1e9}
+    prefill["frac_of_bf16_mfma_peak"] = prefill["model_tflops"] / 2500.0
+    prefill["frac_of_hbm_peak"] = prefill["weight_pass_GBps"] / HBM_PEAK_GBS
 
     # end-to-end generation as the paper times it: prefix pass + 10 tokens
     torch.cuda.synchronize()
