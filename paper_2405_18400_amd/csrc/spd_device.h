@@ -269,9 +269,15 @@ __device__ __forceinline__ float group_sum_last(float v, int lpp) {
     return v;
 }
 
+// a.k_new / a.v_new (the persistent kernel): the newest position's key and value rows are not
+// read from the cache but from activation vectors [n_kv_heads * d_head] that the QKV phase of
+// this very launch is writing, and so is the query: all three are awaited as data (looked at
+// coherently until no word reads ACT_UNSET; bounded, the error word is raised past the limit)
+// -- after the cached rows of the earlier positions have been requested, so that the wait and
+// that fetch overlap.  The newest position is handled by the first lanes of wave 0.
 template <typename KT, int NT, bool COH = false>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
-                                          float *dyn, int *s_last, int hq0 = 0, int hq1 = INT_MAX) {
+                                          float *dyn, int *s_last, int hq0 = 0, int hq1 = INT_MAX, int *err = nullptr) {
     constexpr int VEC = Store<KT>::VEC;
     constexpr int NWAVE = NT / WAVE;
     int tid = threadIdx.x;
@@ -287,6 +293,10 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     const int sub = lane / LPP, li = lane % LPP;
     const int t0 = s * a.chunk;
     const int t1 = min(n_ctx, t0 + a.chunk);
+    const bool awaited = COH && a.k_new != nullptr;              // q (and the newest k, v) are awaited as data
+    const bool has_new = awaited && t1 == n_ctx && t1 > t0;      // this chunk ends with the newest position
+    const int t1c = has_new ? t1 - 1 : t1;                       // cached rows: [t0, t1c)
+    const bool new_lanes = has_new && wid == 0 && sub == 0;      // the lanes that handle the newest position
     const int n_splits = (n_ctx + a.chunk - 1) / a.chunk;
     const int group = a.n_heads / a.n_kv_heads;
     const float scale = 1.0f / sqrtf((float)dh);
@@ -303,24 +313,63 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     for (int hq = hq0; hq < min(hq1, group); ++hq) {
         const int h = g * group + hq;
         float qv[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) qv[v] = as_global(a.q)[(size_t)h * dh + li * VEC + v];
         float lmax = -INFINITY;
-        u32x4 vb[ATTN_BATCH];
-        for (int b0 = tbase; b0 - sub < t1; b0 += ATTN_BATCH * PPB) {   // b0 - sub is wave-uniform
-            u32x4 kb[ATTN_BATCH];
+        u32x4 vb[ATTN_BATCH], kb[ATTN_BATCH];
+        auto first_batch = [&]() {
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
-                const int t = b0 + i * PPB;
+                const int t = tbase + i * PPB;
                 kb[i] = u32x4{0u, 0u, 0u, 0u};
-                if (t < t1) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                if (t < t1c) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
             }
-            if (b0 == tbase) {
+#pragma unroll
+            for (int i = 0; i < ATTN_BATCH; ++i) {
+                const int t = tbase + i * PPB;
+                vb[i] = u32x4{0u, 0u, 0u, 0u};
+                if (t < t1c) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+            }
+        };
+        float knew[VEC], vnew[VEC];
+        if (awaited) {
+            static_assert(!COH || VEC == 4, "awaited vectors are fp32: one 16-byte piece per lane");
+            // the three looks go out together (one trip, not three); whatever is incomplete is looked at again
+            const __amdgpu_buffer_rsrc_t qrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.q), 0, a.n_heads * dh * 4, 0x00020000);
+            const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.k_new), 0, a.n_kv_heads * dh * 4, 0x00020000);
+            const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.v_new), 0, a.n_kv_heads * dh * 4, 0x00020000);
+            const uint32_t qat = (uint32_t)(h * dh + li * VEC) * 4u, kat = (uint32_t)(g * dh + li * VEC) * 4u;
+            auto unset = [](const u32x4 v) { return v.x == ACT_UNSET || v.y == ACT_UNSET || v.z == ACT_UNSET || v.w == ACT_UNSET; };
+            // a first look, then the first batch of cached keys and values right behind it (they are needed
+            // whatever the look says; a look that has to be repeated comes back behind them)
+            u32x4 qraw = coherent_load16(qrs, qat), kr = u32x4{0u, 0u, 0u, 0u}, vr = u32x4{0u, 0u, 0u, 0u};
+            if (new_lanes) { kr = coherent_load16(krs, kat); vr = coherent_load16(vrs, kat); }
+            first_batch();
+            for (unsigned spins = 0; unset(qraw) || unset(kr) || unset(vr); ++spins) {
+                if (spins > (1u << 22) || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                    __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // bounded: give up, the host reports it
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                if (unset(qraw)) qraw = coherent_load16(qrs, qat);
+                if (unset(kr)) kr = coherent_load16(krs, kat);
+                if (unset(vr)) vr = coherent_load16(vrs, kat);
+            }
+            qv[0] = __uint_as_float(qraw.x); qv[1] = __uint_as_float(qraw.y); qv[2] = __uint_as_float(qraw.z); qv[3] = __uint_as_float(qraw.w);
+            if (new_lanes) {
+                knew[0] = __uint_as_float(kr.x); knew[1] = __uint_as_float(kr.y); knew[2] = __uint_as_float(kr.z); knew[3] = __uint_as_float(kr.w);
+                vnew[0] = __uint_as_float(vr.x); vnew[1] = __uint_as_float(vr.y); vnew[2] = __uint_as_float(vr.z); vnew[3] = __uint_as_float(vr.w);
+            }
+        } else {
+            first_batch();
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) qv[v] = as_global(a.q)[(size_t)h * dh + li * VEC + v];
+        }
+        for (int b0 = tbase; b0 - sub < t1c; b0 += ATTN_BATCH * PPB) {   // b0 - sub is wave-uniform
+            if (b0 != tbase) {
 #pragma unroll
                 for (int i = 0; i < ATTN_BATCH; ++i) {
                     const int t = b0 + i * PPB;
-                    vb[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                    kb[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (t < t1c) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
             }
 #pragma unroll
@@ -332,10 +381,22 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
                 d = group_sum_last(d, LPP) * scale;   // complete in the group's last lane
-                if (t < t1 && li == LPP - 1) {
+                if (t < t1c && li == LPP - 1) {
                     sc[t - t0] = d;
                     lmax = fmaxf(lmax, d);
                 }
+            }
+        }
+        if (has_new && wid == 0) {   // (whole wave: the lane-crossing sum needs every lane's turn)
+            float d = 0.f;
+            if (new_lanes) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) d = fmaf(knew[v], qv[v], d);
+            }
+            d = group_sum_last(d, LPP) * scale;
+            if (new_lanes && li == LPP - 1) {
+                sc[t1c - t0] = d;
+                lmax = fmaxf(lmax, d);
             }
         }
         const float m = block_max<NT>(lmax, red);   // includes a barrier after the sc writes
@@ -349,19 +410,19 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         float acc[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-        for (int b0 = tbase; b0 < t1; b0 += ATTN_BATCH * PPB) {
+        for (int b0 = tbase; b0 < t1c; b0 += ATTN_BATCH * PPB) {
             if (b0 != tbase) {
 #pragma unroll
                 for (int i = 0; i < ATTN_BATCH; ++i) {
                     const int t = b0 + i * PPB;
                     vb[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (t < t1) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                    if (t < t1c) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
             }
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
                 const int t = b0 + i * PPB;
-                if (t < t1) {
+                if (t < t1c) {
                     float vf[VEC];
                     Store<KT>::unpack(vb[i], vf);
                     const float p = sc[t - t0];
@@ -369,6 +430,11 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
                 }
             }
+        }
+        if (new_lanes) {
+            const float p = sc[t1c - t0];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vnew[v], acc[v]);
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];

@@ -11,6 +11,8 @@
 // computes" lies one trip to memory, not the chain store acknowledged -> arrival counted ->
 // release polled -> vector loaded, each link of which queues behind the compute unit's own
 // outstanding weight requests (a compute unit serves its memory operations in order).
+// (The query and the newest key and value rows are such vectors too: attention awaits its
+// head's slices of them.)
 // Two activation arenas alternate from launch to launch: whoever stores an element of this
 // launch's arena stores ACT_UNSET to the same element of the other one, which the next launch
 // finds unset throughout (the host sets both when a prefix pass begins).
@@ -41,7 +43,6 @@ constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
 static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
 constexpr int INPUT_SLEEP = 2;        // s_sleep units (64 cycles) between two looks at an input that is not complete yet
-constexpr int QKV_SLEEP = 1;          // the same between two polls of a head's arrival counter
 constexpr int NT = 512;               // threads per block
 constexpr int NW = 8;                 // waves side by side on one row
 constexpr int MAX_U = 32;
@@ -85,6 +86,7 @@ __device__ __forceinline__ GemvArgs uniform(const GemvArgs &a) {
     r.kcache = uniform(a.kcache); r.vcache = uniform(a.vcache);
     r.n_q_rows = uniform(a.n_q_rows); r.n_kv_rows = uniform(a.n_kv_rows); r.d_head = uniform(a.d_head);
     r.cap_ctx = uniform(a.cap_ctx); r.first_block = uniform(a.first_block); r.chunk_span = uniform(a.chunk_span);
+    r.k_new = uniform(a.k_new); r.v_new = uniform(a.v_new);
     return r;
 }
 
@@ -108,6 +110,46 @@ struct Prof {
     __device__ __forceinline__ void done(unsigned point) const { if (p && threadIdx.x == 0) as_global(p)[2 * point] = wall_clock64(); }
     __device__ __forceinline__ void go(unsigned point) const { if (p && threadIdx.x == 0) as_global(p)[2 * point + 1] = wall_clock64(); }
 };
+
+// After the QKV phase nothing but attention needs the new q, k and v, and attention for one
+// head needs only that head's rows.  Like every other vector they are awaited as data: the
+// query in its activation vector, the newest key and value rows in two more (k_new, v_new;
+// the cache gets them too, for the launches to come), each element unset until its producer has
+// stored it.  A block with an attention item requests the cached rows of the earlier positions
+// and then looks at its head's slices until they are complete; blocks without an item do not
+// wait at all.
+// The two finished dot products of row pair `unit` of the QKV matrix: rotary on q and k pairs
+// (the arithmetic of gemv_epilogue, bit for bit), stores as above.
+template <typename WT>
+__device__ __forceinline__ void qkv_store(const GemvArgs &a, int unit, float acc0, float acc1, int pos, float2 cs) {
+    const int r0 = 2 * unit;
+    if (r0 < a.n_q_rows + a.n_kv_rows) {
+        const float c = cs.x, s = cs.y;
+        const float e = __fsub_rn(__fmul_rn(acc0, c), __fmul_rn(acc1, s));
+        const float o = __fadd_rn(__fmul_rn(acc0, s), __fmul_rn(acc1, c));
+        if (r0 < a.n_q_rows) {
+            act_store<true>(a.y + r0, e);
+            act_store<true>(a.y + r0 + 1, o);
+            if (a.twin) { twin_unset(a.y + r0, a.twin); twin_unset(a.y + r0 + 1, a.twin); }
+        } else {
+            const int rr = r0 - a.n_q_rows;
+            const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+            Store<KvT>::store1_coherent(a.kcache, at, e);
+            Store<KvT>::store1_coherent(a.kcache, at + 1, o);
+            act_store<true>(a.k_new + rr, e);
+            act_store<true>(a.k_new + rr + 1, o);
+            if (a.twin) { twin_unset(a.k_new + rr, a.twin); twin_unset(a.k_new + rr + 1, a.twin); }
+        }
+    } else {
+        const int rr = r0 - a.n_q_rows - a.n_kv_rows;
+        const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
+        Store<KvT>::store1_coherent(a.vcache, at, acc0);
+        Store<KvT>::store1_coherent(a.vcache, at + 1, acc1);
+        act_store<true>(a.v_new + rr, acc0);
+        act_store<true>(a.v_new + rr + 1, acc1);
+        if (a.twin) { twin_unset(a.v_new + rr, a.twin); twin_unset(a.v_new + rr + 1, a.twin); }
+    }
+}
 
 // Where a block stands in its walk through a phase: chunk j, of which it owns units [lo, hi),
 // tile at unit u0.
@@ -326,9 +368,10 @@ struct Gemv {
                 act_store<true>(a.y + 2 * eu, sh.epi[2 * (eu - lo)] + r0);
                 act_store<true>(a.y + 2 * eu + 1, sh.epi[2 * (eu - lo) + 1] + r1);
                 if (a.twin) { twin_unset(a.y + 2 * eu, a.twin); twin_unset(a.y + 2 * eu + 1, a.twin); }
+            } else if (EPI == EPI_QKV) {
+                qkv_store<WT>(a, eu, r0, r1, pos, sh.rope[((2 * eu) % a.d_head) / 2]);
             } else {
-                const float2 cs = EPI == EPI_QKV ? sh.rope[((2 * eu) % a.d_head) / 2] : make_float2(1.f, 0.f);
-                gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos, cs);
+                gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos);
                 if (EPI == EPI_SWIGLU && a.twin) twin_unset(a.y + eu, a.twin);
             }
         }
@@ -629,46 +672,8 @@ __device__ __forceinline__ GemvArgs qkv_args(const FusedArgs &a, char *act, int 
     g.vcache = (char *)a.kv + (size_t)(2 * l + 1) * a.kv_layer_bytes;
     g.inv_freq = a.inv_freq;
     g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = a.cap_ctx;
+    g.k_new = a.al.vec(act, l, a.al.kn); g.v_new = a.al.vec(act, l, a.al.vn);
     return g;
-}
-
-// After the QKV phase nothing but attention needs the new q, k and v, and attention for one
-// head needs only that head's rows: an arrival counter per key/value head counts finished row
-// pairs.  A block adds, for every head, how many of its row pairs belong to the head's query,
-// key or value rows (one lane of wave 0 per head, one atomic instruction per 64 heads), and a
-// block about to run an attention item waits until the head's counter shows all of its row
-// pairs.  Blocks without an item do not wait at all.  The counters run on from layer to layer
-// and launch to launch; the host zeroes them when a prefix pass begins.  The arriving wave has
-// waited for its write-through stores (only wave 0 stores in a phase); the wait is bounded.
-__device__ __forceinline__ void qkv_arrive(unsigned *sync, const GemvArgs &q) {
-    if (is_wave0()) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's stores of q, k, v have been acknowledged
-        int lo, hi;
-        block_range(q.rows / 2, blockIdx.x, gridDim.x, lo, hi, q.first_block);
-        const int dh2 = q.d_head / 2, n_kv = q.n_kv_rows / q.d_head;
-        const int tq = (q.n_q_rows / q.n_kv_rows) * dh2, kb = q.n_q_rows / 2, vb = (q.n_q_rows + q.n_kv_rows) / 2;
-        auto overlap = [&](int a0, int a1) { return max(0, min(hi, a1) - max(lo, a0)); };
-        for (int g = threadIdx.x; g < n_kv; g += WAVE) {
-            const int mine = overlap(g * tq, (g + 1) * tq) + overlap(kb + g * dh2, kb + (g + 1) * dh2) + overlap(vb + g * dh2, vb + (g + 1) * dh2);
-            if (mine > 0)
-                __hip_atomic_fetch_add(as_global(sync) + 64 * g, (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-__device__ __forceinline__ void qkv_wait(unsigned *sync, int kv_head, unsigned target, int *err) {
-    if (threadIdx.x == 0) {
-        unsigned spins = 0;
-        while (__hip_atomic_load(as_global(sync) + 64 * kv_head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(QKV_SLEEP);
-            ++spins;
-            if ((spins & 255u) == 0 && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
-            if (spins > SPIN_LIMIT) {
-                __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-        }
-    }
-    __syncthreads();
 }
 
 __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a, char *act) {
@@ -711,14 +716,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     const int pos = uniform(as_global(st)->pos);
     const int dh = a.d_model / a.n_heads;
     const int nq = a.n_heads * dh;
-    // The arenas alternate from launch to launch and the per-head counters run on: block 0 leaves
-    // the number of launches and of layers passed behind when it ends.
+    // The arenas alternate from launch to launch: block 0 leaves the number of launches behind
+    // when it ends.
     const unsigned launch0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.sync) + SYNC_LAUNCH_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    const unsigned layers0 = (unsigned)uniform((int)__hip_atomic_load(as_global(a.sync) + SYNC_LAYER_WORD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     char *act = a.act + (size_t)(launch0 & 1u) * a.arena_bytes;
     const long long twin = (launch0 & 1u) ? -(long long)a.arena_bytes : (long long)a.arena_bytes;
-    unsigned *qkv_sync = a.sync + QKV_SYNC_WORD0;
-    const unsigned head_units = (unsigned)((a.n_heads / a.n_kv_heads + 2) * (dh / 2));   // row pairs of one key/value head's q, k, v
     unsigned point = 0;   // synchronisation points passed: one after the input phase, five per layer
     int pb = 0;
 
@@ -739,11 +741,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         const spd_layer_weights w = uniform(a.layers[l]);
         float *q = a.al.vec(act, l, a.al.q), *att = a.al.vec(act, l, a.al.att), *h1 = a.al.vec(act, l, a.al.h1);
         float *u = a.al.vec(act, l, a.al.u), *h2 = a.al.vec(act, l, a.al.h2);
-        const GemvArgs cur = qkv_args(a, act, l);
+        GemvArgs cur = qkv_args(a, act, l);
+        cur.twin = twin;
         Qkv::template run<Qkv, 0, 0>(cur, pos, sh, buf, pb, false, err, prof, point++, cur, false, nullptr, nullptr);
         prof.done(point);
-        qkv_arrive(qkv_sync, cur);
-        prof.go(point++);
+        prof.go(point++);   // (nobody waits here: attention awaits its head's q, k, v as data)
 
         // Attention items: one per (query head, chunk of cached positions).  Up to
         // FUSED_ONE_CHUNK positions a head is ONE item (one or two batches of loads in one
@@ -769,13 +771,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         if (has_item) {   // attention over pos + 1 cached positions with the head of the O-projection tile in flight
             Oproj::prefetch(o, buf);
             AttnArgs t{q, cur.kcache, cur.vcache, att, a.part, a.counters, nullptr, n_ctx,
-                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, chunk, a.max_splits, twin};
+                       a.n_heads, a.n_kv_heads, dh, a.cap_ctx, chunk, a.max_splits, twin, cur.k_new, cur.v_new};
             const int group = a.n_heads / a.n_kv_heads;
             for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
-                qkv_wait(qkv_sync, h / group, (layers0 + l + 1) * head_units, err);
                 attn_item<KvT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                         h % group, h % group + 1);
+                                         h % group, h % group + 1, err);
             }
         }
         prof.done(point);
@@ -806,7 +807,6 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     if (prof.p && threadIdx.x == 0) as_global(prof.p)[2 * (point + 1)] = wall_clock64();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         __hip_atomic_store(as_global(a.sync) + SYNC_LAUNCH_WORD, launch0 + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(as_global(a.sync) + SYNC_LAYER_WORD, layers0 + (unsigned)a.n_layers, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

@@ -93,6 +93,7 @@ struct GemvArgs {
     const double *inv_freq;     // [d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
     int32_t first_block;        // fused kernel: blocks below this index take no rows of this phase
+    float *k_new, *v_new;       // fused kernel, EPI_QKV: [n_kv_rows] the new key and value rows also go here (see AttnArgs)
     int32_t chunk_span;         // fused kernel: the phase's units are cut into chunks of this many, every block owns a
                                 // share of each chunk and walks them in order; 0 = one chunk
     long long twin;             // fused kernel: byte offset from y to the same vector in the other activation arena
@@ -112,6 +113,8 @@ struct AttnArgs {
     int32_t n_ctx;       // used when st is null
     int32_t n_heads, n_kv_heads, d_head, cap_ctx, chunk, max_splits;
     long long out_twin;  // fused kernel: byte offset from out to its twin in the other activation arena; 0 = none
+    const float *k_new, *v_new;  // fused kernel: [n_kv_heads, d_head] key and value rows of the newest position as the QKV phase
+                                 // of this launch writes them (awaited as data, like q); null: everything is read from the cache
 };
 
 struct SuperposeArgs {
@@ -169,6 +172,7 @@ struct ActLayout {
     size_t layer0, stride;     // layer l's block starts at layer0 + l * stride
     size_t q, att, h1, u, h2;  // within a layer block: query, attention output, residual stream
                                // after attention, SwiGLU output, residual stream after the FFN
+    size_t kn, vn;             // and the newest position's key and value rows
     __host__ __device__ __forceinline__ float *at(char *base, size_t off) const { return (float *)(base + off); }
     __host__ __device__ __forceinline__ float *h_in(char *base, int l) const { return l == 0 ? at(base, h0) : at(base, layer0 + (size_t)(l - 1) * stride + h2); }
     __host__ __device__ __forceinline__ float *vec(char *base, int l, size_t which) const { return at(base, layer0 + (size_t)l * stride + which); }
@@ -195,7 +199,7 @@ struct FusedArgsHost {
     int32_t *counters;
     const double *inv_freq;
     long long *prof;                   // optional [blocks][2 * (5 n_layers + 2)] clock stamps
-    unsigned *sync;                    // SYNC_WORDS words: launch and layer counts, per-head arrival counters
+    unsigned *sync;                    // SYNC_WORDS words: the launch count
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
     float eps;
 };
@@ -225,10 +229,7 @@ constexpr int FUSED_MAX_EPI = 512;     // residual values one block of the fused
 constexpr int FUSED_PROF_BLOCKS = 512;  // blocks of the fused kernel whose phase clocks are kept
 constexpr int FUSED_MAX_BLOCKS = 1024;                      // largest grid of the fused kernel
 constexpr int SYNC_LAUNCH_WORD = 0;                         // launches of the fused kernel since the last reset (its parity picks the arena)
-constexpr int SYNC_LAYER_WORD = 16;                         // layers passed by all launches since the last reset
-constexpr int QKV_SYNC_WORD0 = 64;                          // one arrival counter per key/value head, 256 bytes apart
-constexpr int QKV_SYNC_MAX = 256;                           // key/value heads the fused kernel has counters for
-constexpr int SYNC_WORDS = 64 * (1 + QKV_SYNC_MAX);
+constexpr int SYNC_WORDS = 64;
 constexpr int TOPK_PART_MAX = 128;
 constexpr int ATTN_CHUNK = 128;        // cached positions per attention item (one kernel per operator; short contexts)
 constexpr int ATTN_CHUNK_MIN = 64;    // the fused kernel picks the chunk per step within these bounds

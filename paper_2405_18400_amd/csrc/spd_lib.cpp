@@ -53,12 +53,6 @@ const char *check_cfg(const spd_model_cfg *c) {
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return "rms_eps and rope_theta must be positive";
     const int widest = c->d_model > c->d_ffn ? c->d_model : c->d_ffn;
     if (spdk::gemv_lds_bytes(c->dtype, widest) > 160 * 1024 - 1024) return "d_model / d_ffn too large for the LDS staging";
-    // The persistent kernel's per-head arrival counters are 32-bit and count on from launch to
-    // launch until the next prefix pass zeroes them (one per row pair of a head's q, k and v
-    // rows per layer); at most max_ctx launches lie between two prefix passes.
-    const uint64_t per_head = (uint64_t)(c->n_heads / c->n_kv_heads + 2) * (uint64_t)(dh / 2);
-    if ((uint64_t)c->max_ctx * (uint64_t)(c->n_layers > 0 ? c->n_layers : 1) * per_head >= (1ull << 32))
-        return "max_ctx too large for the 32-bit arrival counters of the persistent kernel";
     return nullptr;
 }
 
@@ -79,8 +73,10 @@ Layout make_layout(const spd_model_cfg &c) {
         const size_t vd = up((size_t)c.d_model * 4), vq = up((size_t)c.n_heads * dh * 4), vu = up((size_t)c.d_ffn * 4);
         L.al.h0 = 0;
         L.al.layer0 = vd;
+        const size_t vk = up((size_t)c.n_kv_heads * dh * 4);
         L.al.q = 0; L.al.att = vq; L.al.h1 = 2 * vq; L.al.u = 2 * vq + vd; L.al.h2 = 2 * vq + vd + vu;
-        L.al.stride = 2 * vq + 2 * vd + vu;
+        L.al.kn = 2 * vq + 2 * vd + vu; L.al.vn = L.al.kn + vk;
+        L.al.stride = 2 * vq + 2 * vd + vu + 2 * vk;
         L.arena_bytes = up(vd + (size_t)c.n_layers * L.al.stride);
         L.act = take(2 * L.arena_bytes);   // the fused kernel alternates between two arenas (see ACT_UNSET)
     }
@@ -460,7 +456,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
         int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
         if (per_cu > 1) per_cu = 1;
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
-        if (c->fused_blocks > FUSED_MAX_BLOCKS || cfg->n_kv_heads > QKV_SYNC_MAX) c->fused_blocks = 0;
+        if (c->fused_blocks > FUSED_MAX_BLOCKS) c->fused_blocks = 0;
         if (c->fused_blocks > 0 && (4 * cfg->d_model) / (3 * c->fused_blocks) + 4 > FUSED_MAX_EPI) c->fused_blocks = 0;   // residual slice per block (a quarter of the blocks may sit a phase out)
     }
 

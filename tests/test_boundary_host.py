@@ -121,20 +121,6 @@ def test_device_error_word_maps_to_ehip(pkg):
     assert pkg.lib().spd_test_state_status(None, words) == -1
 
 
-def test_max_ctx_is_bounded_by_the_32_bit_arrival_counters(pkg):
-    """The persistent kernel's per-head arrival counters count on from launch to launch between
-    two prefix passes: a context so long that they could wrap is refused when the context is
-    sized, not found out at run time."""
-    ok = pkg.binding.model_cfg(synth.LLAMA7B, 690_000, 8)
-    assert pkg.spd_workspace_bytes(ok) > 0
-    with pytest.raises(pkg.SpdError) as e:     # 32 layers x 192 row pairs per head x 700k launches > 2^32
-        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA7B, 700_000, 8))
-    assert e.value.code == -1
-    with pytest.raises(pkg.SpdError):
-        pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 84_000, 8))
-    assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA70B, 83_000, 8)) > 0
-
-
 def test_static_scratch_variant_refuses_oversized_shapes_before_any_gpu_work(pkg):
     """spd_op_attention_static: argument errors and a scratch need beyond the static array are
     refused on the host (no GPU is touched: this runs without one)."""

@@ -142,9 +142,9 @@ def test_vocabulary_of_140k_tokens(forward_path):
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 5, 0.0, 4, path=forward_path)
 
 
-def test_more_kv_heads_than_arrival_counters(forward_path):
-    """128 key/value heads: more than the fused kernel has per-head arrival counters for, so it
-    keeps the device-wide barrier after the QKV phase; small heads (d_head 16)."""
+def test_many_small_kv_heads(forward_path):
+    """128 key/value heads of d_head 16: four lanes per cached position, and more heads than a
+    wave has lanes."""
     shape = synth.ModelShape("heads128-fp32", 2, 2048, 128, 128, 1024, 1024, "fp32")
     w = synth.make_weights(shape, seed=12)
     prefix = synth.make_prefix_uniform(shape.vocab, 19, seed=12)
