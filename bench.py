@@ -132,7 +132,7 @@ def probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args):
     (k^2 options x orders probes of the hash tables, interpolation, prune) and of the whole step."""
     import torch
     n_steps = min(args.steps, 24)
-    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 4, k_max=16)
+    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 4, k_max=16, kv_dtype=args.kv_dtype)
     rows = []
     for orders in (None, (2, 3), (2, 3, 4), (2, 3, 4, 5, 6)):
         alpha = 0.0
@@ -176,7 +176,7 @@ def phase_clocks(pkg, shape, weights, prefix, k, args):
     the next (these add up to the layer time).  Prints a table, not JSON."""
     import torch
     n_steps = min(args.steps, 16)
-    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 8, k_max=max(k, 8))
+    sess = pkg.Session(shape, weights, max_ctx=len(prefix) + args.warmup + n_steps + 8, k_max=max(k, 8), kv_dtype=args.kv_dtype)
     dc = pkg.SpdDecodeCfg(k, 0.0, 1.0, 0.1)
     sess.spd_prefill(prefix)
     for _ in range(1 + args.warmup):
@@ -226,6 +226,9 @@ def main():
     ap.add_argument("--workload", default="7b", choices=["7b", "tiny", "13b", "70b"])
     ap.add_argument("--prefix", type=int, default=None)
     ap.add_argument("--k", type=int, default=3)
+    ap.add_argument("--kv-dtype", default=None, choices=["fp16", "fp32"],
+                    help="element type of the key/value cache (default: fp16 for the bf16 workloads, whose algorithmic "
+                         "bytes count a cached element at 2 bytes; fp32 for the fp32 one)")
     ap.add_argument("--ngram-entries", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -242,6 +245,8 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the SPD step is a single-GPU, batch-1 path); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.kv_dtype is None:
+        args.kv_dtype = "fp32" if args.workload == "tiny" else "fp16"
 
     import torch
 
@@ -273,7 +278,7 @@ def main():
         tables = synth.make_ngram_tables_zipf(shape.vocab, entries, seed=0)
     if args.probe_sweep:
         return probe_sweep(pkg, shape, weights, tables, lambdas, prefix, tau, delta, args)
-    sess = pkg.Session(shape, weights, max_ctx=max_ctx, k_max=max(k, 8))
+    sess = pkg.Session(shape, weights, max_ctx=max_ctx, k_max=max(k, 8), kv_dtype=args.kv_dtype)
     sess.spd_load_ngrams(tables, lambdas)
     if args.no_graph:
         sess.spd_set_graph(False)
@@ -434,7 +439,8 @@ def main():
                                f"alpha={alpha}, tau={tau}, delta={delta}, n-gram tables n=2..6 with "
                                f"{sum(len(v[1]) for v in tables.values())} entries; {K} consecutive timesteps "
                                f"(context {m + 1 + W}..{m + W + K})",
-                   "k": k, "prefix": m, "graph": not args.no_graph, "fused_forward": sess.spd_get_fused()},
+                   "k": k, "prefix": m, "graph": not args.no_graph, "fused_forward": sess.spd_get_fused(),
+                   "kv_cache": args.kv_dtype},
         "pct_peak_hbm": 100.0 * step_gbs / HBM_PEAK_GBS,
         "gpu_ms_per_step_events": gpu_ms / K,
         "roofline": roofline,

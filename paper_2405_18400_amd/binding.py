@@ -13,7 +13,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SPD_K_MAX, SPD_TAIL, SPD_N_ORDERS = 16, 5, 5
-SPD_DTYPE = {"fp32": 0, "bf16": 1}
+SPD_DTYPE = {"fp32": 0, "bf16": 1, "fp16": 2}   # fp16: key/value cache only
 _lib = None
 
 
@@ -25,7 +25,8 @@ class SpdError(RuntimeError):
 
 class SpdModelCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "d_ffn", "vocab",
-                                          "max_ctx", "k_max", "dtype")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+                                          "max_ctx", "k_max", "dtype")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                                                                      ("kv_dtype", C.c_int32)]
 
 
 class SpdLayerWeights(C.Structure):
@@ -116,9 +117,9 @@ def _np_ptr(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 
 
-def model_cfg(shape, max_ctx: int, k_max: int) -> SpdModelCfg:
+def model_cfg(shape, max_ctx: int, k_max: int, kv_dtype: str = "fp32") -> SpdModelCfg:
     return SpdModelCfg(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn, shape.vocab,
-                       max_ctx, k_max, SPD_DTYPE[shape.dtype], shape.rms_eps, shape.rope_theta)
+                       max_ctx, k_max, SPD_DTYPE[shape.dtype], shape.rms_eps, shape.rope_theta, SPD_DTYPE[kv_dtype])
 
 
 def spd_workspace_bytes(cfg: SpdModelCfg) -> int:
@@ -176,13 +177,13 @@ class Session:
     """Owns the device tensors (weights, workspace, n-gram buffer), the stream and the spd_ctx.
     Methods carry the C function names and only marshal arguments."""
 
-    def __init__(self, shape, weights: dict, max_ctx: int, k_max: int = 8, device="cuda", stream=None):
+    def __init__(self, shape, weights: dict, max_ctx: int, k_max: int = 8, device="cuda", stream=None, kv_dtype: str = "fp32"):
         torch = _torch()
         if not torch.cuda.is_available():
             raise RuntimeError("libspd needs a GPU: no HIP device is visible")
         self.shape, self.device, self.L = shape, device, lib()
         self.stream = stream if stream is not None else torch.cuda.Stream(device=device)
-        self.cfg = model_cfg(shape, max_ctx, k_max)
+        self.cfg = model_cfg(shape, max_ctx, k_max, kv_dtype)
         dev = lambda a: to_device(a, shape.dtype, device)
         self.t = {"embed": dev(weights["embed"]), "final_norm": dev(weights["final_norm"]), "lm_head": dev(weights["lm_head"])}
         self.layers = (SpdLayerWeights * max(shape.n_layers, 1))()

@@ -14,9 +14,14 @@ constexpr int WAVE = 64;
 // ------------------------------------------------------------------ storage types
 struct bf16_t { uint16_t b; };
 
+struct half_t { uint16_t b; };   // IEEE binary16 (key/value cache of bf16 models, if asked for)
+struct half4_t { uint16_t b; };
+
 template <typename T> struct Store;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <> struct Store<float> {
     static constexpr int VEC = 4;  // elements per 16-byte load
+    typedef u32x4 piece_t;
     static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
@@ -29,6 +34,7 @@ template <> struct Store<float> {
 };
 template <> struct Store<bf16_t> {
     static constexpr int VEC = 8;
+    typedef u32x4 piece_t;
     static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
         f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
         f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
@@ -47,6 +53,42 @@ template <> struct Store<bf16_t> {
         uint32_t u = __float_as_uint(v);
         u += 0x7FFFu + ((u >> 16) & 1u);
         __hip_atomic_store((uint16_t __attribute__((address_space(1))) *)p + i, (uint16_t)(u >> 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
+
+template <> struct Store<half_t> {
+    static constexpr int VEC = 8;
+    typedef u32x4 piece_t;
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void unpack(const u32x4 v, float *f) {
+        // (bit casts of copies: cast straight from a vector's element, every one reads element 0)
+        const uint32_t x = v.x, y = v.y, z = v.z, w = v.w;
+        const h2 a = __builtin_bit_cast(h2, x), b = __builtin_bit_cast(h2, y);
+        const h2 c = __builtin_bit_cast(h2, z), d = __builtin_bit_cast(h2, w);
+        f[0] = (float)a.x; f[1] = (float)a.y; f[2] = (float)b.x; f[3] = (float)b.y;
+        f[4] = (float)c.x; f[5] = (float)c.y; f[6] = (float)d.x; f[7] = (float)d.y;
+    }
+    static __device__ __forceinline__ uint16_t bits(float v) { return __builtin_bit_cast(uint16_t, (_Float16)v); }   // round to nearest even
+    static __device__ __forceinline__ float load1(const void *p, size_t i) {
+        return (float)__builtin_bit_cast(_Float16, ((const uint16_t __attribute__((address_space(1))) *)p)[i]);
+    }
+    static __device__ __forceinline__ void store1(void *p, size_t i, float v) {
+        ((uint16_t __attribute__((address_space(1))) *)p)[i] = bits(v);
+    }
+    static __device__ __forceinline__ void store1_coherent(void *p, size_t i, float v) {
+        __hip_atomic_store((uint16_t __attribute__((address_space(1))) *)p + i, bits(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
+
+// The same cache read four elements (8 bytes) per lane: the lane layout of an fp32 cache.
+template <> struct Store<half4_t> {
+    static constexpr int VEC = 4;
+    typedef u32x2 piece_t;
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void unpack(const u32x2 v, float *f) {
+        const uint32_t x = v.x, y = v.y;
+        const h2 a = __builtin_bit_cast(h2, x), b = __builtin_bit_cast(h2, y);
+        f[0] = (float)a.x; f[1] = (float)a.y; f[2] = (float)b.x; f[3] = (float)b.y;
     }
 };
 
@@ -88,6 +130,10 @@ __device__ __forceinline__ u32x4 stream_load16(const void *uniform_base, uint32_
     return __builtin_nontemporal_load((global_u32x4_ptr)(b + lane_offset));
 }
 __device__ __forceinline__ u32x4 global_load16(const void *p) { return *(global_u32x4_ptr)p; }
+// One lane's piece of a cached row (16 bytes, or 8 for half4_t).
+template <typename KT> __device__ __forceinline__ typename Store<KT>::piece_t kv_piece(const void *p) {
+    return *(const typename Store<KT>::piece_t __attribute__((address_space(1))) *)p;
+}
 __device__ __forceinline__ u32x4 global_load16(const void *uniform_base, uint32_t lane_offset) {
     return *(global_u32x4_ptr)((global_char_ptr)uniform_base + lane_offset);
 }
@@ -198,10 +244,26 @@ __device__ __forceinline__ float block_max(float v, float *red) {
 }
 
 
-// The key/value cache is kept in fp32 whatever the weight type: rounding cached keys and
+// The key/value cache holds fp32 by default whatever the weight type: rounding cached keys and
 // values to bf16 alone costs about 2e-2 of the logit scale over 32 layers, the whole error
-// budget, while the cache is under 1 % of the bytes of a short-context step.
-typedef float KvT;
+// budget.  A bf16 model may ask for an fp16 cache (11 significant bits: an eighth of that
+// error, half the bytes of the fp32 cache per cached position).
+// Two adjacent elements (at, at + 1; at is even) of a cache row, as the cache stores them;
+// returns through e, o the values a later read of the cache will see.
+template <bool COH, bool HALF>
+__device__ __forceinline__ void kv_store_pair(void *cache, size_t at, float &e, float &o) {
+    if (HALF) {
+        const uint32_t w = (uint32_t)Store<half_t>::bits(e) | ((uint32_t)Store<half_t>::bits(o) << 16);
+        global_ptr<uint32_t> p = (global_ptr<uint32_t>)((global_ptr<uint16_t>)cache + at);
+        if (COH) __hip_atomic_store(p, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *p = w;
+        e = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu));
+        o = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    } else {
+        if (COH) { Store<float>::store1_coherent(cache, at, e); Store<float>::store1_coherent(cache, at + 1, o); }
+        else { Store<float>::store1(cache, at, e); Store<float>::store1(cache, at + 1, o); }
+    }
+}
 
 // ------------------------------------------------------------------ GEMV epilogues
 // What happens to the two finished dot products of one work unit (a row pair, or for
@@ -239,14 +301,15 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs &a, int unit, float
             } else {
                 const int rr = r0 - a.n_q_rows;
                 const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-                if (COH) { Store<KvT>::store1_coherent(a.kcache, at, e); Store<KvT>::store1_coherent(a.kcache, at + 1, o); }
-                else { Store<KvT>::store1(a.kcache, at, e); Store<KvT>::store1(a.kcache, at + 1, o); }
+                float ke = e, ko = o;
+                if (a.kv_half) kv_store_pair<COH, true>(a.kcache, at, ke, ko);
+                else kv_store_pair<COH, false>(a.kcache, at, ke, ko);
             }
         } else {
             const int rr = r0 - a.n_q_rows - a.n_kv_rows;
             const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-            if (COH) { Store<KvT>::store1_coherent(a.vcache, at, acc0); Store<KvT>::store1_coherent(a.vcache, at + 1, acc1); }
-            else { Store<KvT>::store1(a.vcache, at, acc0); Store<KvT>::store1(a.vcache, at + 1, acc1); }
+            if (a.kv_half) kv_store_pair<COH, true>(a.vcache, at, acc0, acc1);
+            else kv_store_pair<COH, false>(a.vcache, at, acc0, acc1);
         }
     }
 }
@@ -275,7 +338,9 @@ __device__ __forceinline__ float group_sum_last(float v, int lpp) {
 // coherently until no word reads ACT_UNSET; bounded, the error word is raised past the limit)
 // -- after the cached rows of the earlier positions have been requested, so that the wait and
 // that fetch overlap.  The newest position is handled by the first lanes of wave 0.
-template <typename KT, int NT, bool COH = false>
+// ROWS: cached rows a lane keeps in flight per batch of loads (0: 10); every row of a batch costs
+// its arithmetic whether the chunk reaches it or not.
+template <typename KT, int NT, bool COH = false, int ROWS = 0>
 __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n_ctx, float *sc, float *red,
                                           float *dyn, int *s_last, int hq0 = 0, int hq1 = INT_MAX, int *err = nullptr) {
     constexpr int VEC = Store<KT>::VEC;
@@ -307,32 +372,34 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
     // 160 positions, which is what contexts up to 1280 give on 256 blocks and 32 heads; 12 spills
     // registers in the persistent kernel), and the first batch of value
     // rows together with the keys: this phase is a chain of memory latencies, not bandwidth.
-    constexpr int ATTN_BATCH = 10;
+    constexpr int ATTN_BATCH = ROWS ? ROWS : 10;
     const int tbase = t0 + wid * PPW + sub;
     // query heads [hq0, hq1) of the group that shares key/value head g
     for (int hq = hq0; hq < min(hq1, group); ++hq) {
         const int h = g * group + hq;
         float qv[VEC];
         float lmax = -INFINITY;
-        u32x4 vb[ATTN_BATCH], kb[ATTN_BATCH];
+        typedef typename Store<KT>::piece_t piece_t;
+        piece_t vb[ATTN_BATCH], kb[ATTN_BATCH];
         auto first_batch = [&]() {
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
                 const int t = tbase + i * PPB;
-                kb[i] = u32x4{0u, 0u, 0u, 0u};
-                if (t < t1c) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                kb[i] = (piece_t)(0u);
+                if (t < t1c) kb[i] = kv_piece<KT>(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
             }
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
                 const int t = tbase + i * PPB;
-                vb[i] = u32x4{0u, 0u, 0u, 0u};
-                if (t < t1c) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                vb[i] = (piece_t)(0u);
+                if (t < t1c) vb[i] = kv_piece<KT>(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
             }
         };
         float knew[VEC], vnew[VEC];
         if (awaited) {
-            static_assert(!COH || VEC == 4, "awaited vectors are fp32: one 16-byte piece per lane");
-            // the three looks go out together (one trip, not three); whatever is incomplete is looked at again
+            // the awaited vectors are fp32: a lane's VEC elements are NP pieces of 16 bytes
+            constexpr int NP = VEC / 4;
+            // the looks go out together (one trip, not three); whatever is incomplete is looked at again
             const __amdgpu_buffer_rsrc_t qrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.q), 0, a.n_heads * dh * 4, 0x00020000);
             const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.k_new), 0, a.n_kv_heads * dh * 4, 0x00020000);
             const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.v_new), 0, a.n_kv_heads * dh * 4, 0x00020000);
@@ -340,23 +407,43 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
             auto unset = [](const u32x4 v) { return v.x == ACT_UNSET || v.y == ACT_UNSET || v.z == ACT_UNSET || v.w == ACT_UNSET; };
             // a first look, then the first batch of cached keys and values right behind it (they are needed
             // whatever the look says; a look that has to be repeated comes back behind them)
-            u32x4 qraw = coherent_load16(qrs, qat), kr = u32x4{0u, 0u, 0u, 0u}, vr = u32x4{0u, 0u, 0u, 0u};
-            if (new_lanes) { kr = coherent_load16(krs, kat); vr = coherent_load16(vrs, kat); }
+            u32x4 qraw[NP], kr[NP], vr[NP];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                qraw[p] = coherent_load16(qrs, qat + 16u * p);
+                kr[p] = u32x4{0u, 0u, 0u, 0u}; vr[p] = u32x4{0u, 0u, 0u, 0u};
+                if (new_lanes) { kr[p] = coherent_load16(krs, kat + 16u * p); vr[p] = coherent_load16(vrs, kat + 16u * p); }
+            }
             first_batch();
-            for (unsigned spins = 0; unset(qraw) || unset(kr) || unset(vr); ++spins) {
+            auto any_unset = [&]() {
+                bool r = false;
+#pragma unroll
+                for (int p = 0; p < NP; ++p) r = r || unset(qraw[p]) || unset(kr[p]) || unset(vr[p]);
+                return r;
+            };
+            for (unsigned spins = 0; any_unset(); ++spins) {
                 if (spins > (1u << 22) || ((spins & 255u) == 255u && __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
                     __hip_atomic_store(as_global(err), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // bounded: give up, the host reports it
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
-                if (unset(qraw)) qraw = coherent_load16(qrs, qat);
-                if (unset(kr)) kr = coherent_load16(krs, kat);
-                if (unset(vr)) vr = coherent_load16(vrs, kat);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    if (unset(qraw[p])) qraw[p] = coherent_load16(qrs, qat + 16u * p);
+                    if (unset(kr[p])) kr[p] = coherent_load16(krs, kat + 16u * p);
+                    if (unset(vr[p])) vr[p] = coherent_load16(vrs, kat + 16u * p);
+                }
             }
-            qv[0] = __uint_as_float(qraw.x); qv[1] = __uint_as_float(qraw.y); qv[2] = __uint_as_float(qraw.z); qv[3] = __uint_as_float(qraw.w);
-            if (new_lanes) {
-                knew[0] = __uint_as_float(kr.x); knew[1] = __uint_as_float(kr.y); knew[2] = __uint_as_float(kr.z); knew[3] = __uint_as_float(kr.w);
-                vnew[0] = __uint_as_float(vr.x); vnew[1] = __uint_as_float(vr.y); vnew[2] = __uint_as_float(vr.z); vnew[3] = __uint_as_float(vr.w);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                qv[4 * p] = __uint_as_float(qraw[p].x); qv[4 * p + 1] = __uint_as_float(qraw[p].y);
+                qv[4 * p + 2] = __uint_as_float(qraw[p].z); qv[4 * p + 3] = __uint_as_float(qraw[p].w);
+                if (new_lanes) {
+                    knew[4 * p] = __uint_as_float(kr[p].x); knew[4 * p + 1] = __uint_as_float(kr[p].y);
+                    knew[4 * p + 2] = __uint_as_float(kr[p].z); knew[4 * p + 3] = __uint_as_float(kr[p].w);
+                    vnew[4 * p] = __uint_as_float(vr[p].x); vnew[4 * p + 1] = __uint_as_float(vr[p].y);
+                    vnew[4 * p + 2] = __uint_as_float(vr[p].z); vnew[4 * p + 3] = __uint_as_float(vr[p].w);
+                }
             }
         } else {
             first_batch();
@@ -368,8 +455,8 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 #pragma unroll
                 for (int i = 0; i < ATTN_BATCH; ++i) {
                     const int t = b0 + i * PPB;
-                    kb[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (t < t1c) kb[i] = global_load16(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                    kb[i] = (piece_t)(0u);
+                    if (t < t1c) kb[i] = kv_piece<KT>(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
             }
 #pragma unroll
@@ -415,8 +502,8 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 #pragma unroll
                 for (int i = 0; i < ATTN_BATCH; ++i) {
                     const int t = b0 + i * PPB;
-                    vb[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (t < t1c) vb[i] = global_load16(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
+                    vb[i] = (piece_t)(0u);
+                    if (t < t1c) vb[i] = kv_piece<KT>(Vg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
             }
 #pragma unroll

@@ -40,8 +40,13 @@ constexpr int FUSED_QD_ITEM = 12;     // of which this many are requested before
 constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
 constexpr int FUSED_SLICE_GATE = 4;   // the first slice of the gate/up phase (its input follows the attention within a microsecond or two)
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
+constexpr int FUSED_HALF_NARROW_UPTO = 160;   // an fp16 cache is read 8 bytes (4 elements) per lane, like the fp32 one, up to this
+                                              // many positions (one batch of loads), 16 bytes per lane beyond
+constexpr int FUSED_HALF_ROWS_ONE = 8;        // 16 bytes per lane: rows in flight per lane where a head is one item (256 positions per batch)
+constexpr int FUSED_HALF_ROWS_CUT = 6;        // ... and where the context is cut into chunks (192 per batch: chunks of contexts up to 1536)
+constexpr int FUSED_ONE_CHUNK_HALF = 512;     // FUSED_ONE_CHUNK for an fp16 cache: half the bytes per position
 constexpr int FUSED_ONE_CHUNK = 256;  // contexts up to this long are one attention item per head (no merge across blocks)
-static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
+static_assert(FUSED_ONE_CHUNK <= ATTN_CHUNK_MAX && FUSED_ONE_CHUNK_HALF <= ATTN_CHUNK_MAX, "one attention item must fit the score buffer");
 constexpr int INPUT_SLEEP = 2;        // s_sleep units (64 cycles) between two looks at an input that is not complete yet
 constexpr int NT = 512;               // threads per block
 constexpr int NW = 8;                 // waves side by side on one row
@@ -120,7 +125,7 @@ struct Prof {
 // wait at all.
 // The two finished dot products of row pair `unit` of the QKV matrix: rotary on q and k pairs
 // (the arithmetic of gemv_epilogue, bit for bit), stores as above.
-template <typename WT>
+template <typename WT, typename KT>
 __device__ __forceinline__ void qkv_store(const GemvArgs &a, int unit, float acc0, float acc1, int pos, float2 cs) {
     const int r0 = 2 * unit;
     if (r0 < a.n_q_rows + a.n_kv_rows) {
@@ -134,17 +139,16 @@ __device__ __forceinline__ void qkv_store(const GemvArgs &a, int unit, float acc
         } else {
             const int rr = r0 - a.n_q_rows;
             const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-            Store<KvT>::store1_coherent(a.kcache, at, e);
-            Store<KvT>::store1_coherent(a.kcache, at + 1, o);
-            act_store<true>(a.k_new + rr, e);
-            act_store<true>(a.k_new + rr + 1, o);
+            float ke = e, ko = o;   // (as the cache holds them: this step sees what later steps will read)
+            kv_store_pair<true, sizeof(KT) == 2>(a.kcache, at, ke, ko);
+            act_store<true>(a.k_new + rr, ke);
+            act_store<true>(a.k_new + rr + 1, ko);
             if (a.twin) { twin_unset(a.k_new + rr, a.twin); twin_unset(a.k_new + rr + 1, a.twin); }
         }
     } else {
         const int rr = r0 - a.n_q_rows - a.n_kv_rows;
         const size_t at = ((size_t)(rr / a.d_head) * a.cap_ctx + pos) * a.d_head + rr % a.d_head;
-        Store<KvT>::store1_coherent(a.vcache, at, acc0);
-        Store<KvT>::store1_coherent(a.vcache, at + 1, acc1);
+        kv_store_pair<true, sizeof(KT) == 2>(a.vcache, at, acc0, acc1);
         act_store<true>(a.v_new + rr, acc0);
         act_store<true>(a.v_new + rr + 1, acc1);
         if (a.twin) { twin_unset(a.v_new + rr, a.twin); twin_unset(a.v_new + rr + 1, a.twin); }
@@ -247,7 +251,7 @@ struct PreT {
 // pass 0 is complete and looks at the later passes, a tile's pass ahead each, while it streams.
 // With a producer that works in chunks of one pass width, only the last pass's chunk is still
 // being written when the phase starts, and it is needed a tile's (P - 1) / P later.
-template <typename WT, int P, int U, int EPI, int NBUF, int SL, bool PM = false, bool CHUNKS = false, int SL0 = SL>
+template <typename WT, int P, int U, int EPI, int NBUF, int SL, bool PM = false, bool CHUNKS = false, int SL0 = SL, typename KT = float>
 struct Gemv {
     static constexpr int VEC = Store<WT>::VEC;
     static constexpr int XP = VEC / 4;   // 16-byte pieces of x per pass and lane
@@ -369,7 +373,7 @@ struct Gemv {
                 act_store<true>(a.y + 2 * eu + 1, sh.epi[2 * (eu - lo) + 1] + r1);
                 if (a.twin) { twin_unset(a.y + 2 * eu, a.twin); twin_unset(a.y + 2 * eu + 1, a.twin); }
             } else if (EPI == EPI_QKV) {
-                qkv_store<WT>(a, eu, r0, r1, pos, sh.rope[((2 * eu) % a.d_head) / 2]);
+                qkv_store<WT, KT>(a, eu, r0, r1, pos, sh.rope[((2 * eu) % a.d_head) / 2]);
             } else {
                 gemv_epilogue<WT, EPI, true, true>(a, eu, r0, r1, pos);
                 if (EPI == EPI_SWIGLU && a.twin) twin_unset(a.y + eu, a.twin);
@@ -657,7 +661,7 @@ struct FusedArgs {
     const double *inv_freq;
     long long *prof;                   // optional: every block stamps wall_clock64() around every synchronisation point
     unsigned *sync;
-    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head, kv_half;
     float eps;
 };
 
@@ -687,7 +691,8 @@ __device__ __forceinline__ GemvArgs head_args(const FusedArgs &a, char *act) {
 // them so that a tile stays at about 16 pieces (16 bytes each) per lane.
 constexpr int tile_rows(int passes) { return passes == 1 ? FUSED_UA : passes == 2 ? FUSED_UA / 2 : passes <= 4 ? 4 : 2; }
 
-template <typename WT, int PA, int PB>
+// KT: element type of the key/value cache (float, or half_t for a bf16 model that asked for it).
+template <typename WT, typename KT, int PA, int PB>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int UA = tile_rows(PA), UB = tile_rows(PB);
     // The O projection is one tile per block; its tile is a little taller so that it still is
@@ -702,13 +707,13 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     constexpr int ND = PMD ? UPM : PB * UB;
     constexpr int NBUF = (NA > ND) ? NA : ND;
     constexpr int SL = PA == 1 ? FUSED_SLICE : FUSED_SLICE_WIDE;
-    using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL>;
+    using Qkv = Gemv<WT, PA, UA, EPI_QKV, NBUF, SL, false, false, SL, KT>;
     using Oproj = Gemv<WT, PA, UO, EPI_RESID, NBUF, SL>;
     using GateUp = Gemv<WT, PA, UA, EPI_SWIGLU, NBUF, SL, false, PMD, FUSED_SLICE_GATE < SL ? FUSED_SLICE_GATE : SL>;
     using Down = Gemv<WT, PB, PMD ? UPM : UB, EPI_RESID, NBUF, SL, PMD>;
     using Head = Gemv<WT, PA, UA, EPI_PLAIN, NBUF, SL>;
     __shared__ FusedShared sh;
-    __shared__ __align__(16) float dyn[NT * Store<KvT>::VEC];
+    __shared__ __align__(16) float dyn[NT * Store<KT>::VEC];
 
     DevState *st = a.sup.st;
     int *err = &st->err;
@@ -758,8 +763,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
         GemvArgs o{};
         o.W = w.wo; o.x = att; o.resid = a.al.h_in(act, l); o.y = h1; o.rows = a.d_model; o.cols = nq; o.twin = twin;
         const int n_ctx = pos + 1;
-        int chunk = FUSED_ONE_CHUNK;
-        if (n_ctx > FUSED_ONE_CHUNK) {
+        constexpr int ONE_CHUNK = sizeof(KT) == 2 ? FUSED_ONE_CHUNK_HALF : FUSED_ONE_CHUNK;
+        int chunk = ONE_CHUNK;
+        if (n_ctx > ONE_CHUNK) {
             const int per_head = max(1, (int)gridDim.x / a.n_heads);
             chunk = ((n_ctx + per_head - 1) / per_head + 15) & ~15;
             chunk = min(ATTN_CHUNK_MAX, max(ATTN_CHUNK_MIN, chunk));
@@ -775,8 +781,20 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             const int group = a.n_heads / a.n_kv_heads;
             for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
-                attn_item<KvT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                         h % group, h % group + 1, err);
+                if constexpr (sizeof(KT) == 2) {
+                    if (n_ctx <= FUSED_HALF_NARROW_UPTO)
+                        attn_item<half4_t, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                     h % group, h % group + 1, err);
+                    else if (n_splits == 1)
+                        attn_item<half_t, NT, true, FUSED_HALF_ROWS_ONE>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                                         h % group, h % group + 1, err);
+                    else
+                        attn_item<half_t, NT, true, FUSED_HALF_ROWS_CUT>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                                         h % group, h % group + 1, err);
+                } else {
+                    attn_item<KT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                            h % group, h % group + 1, err);
+                }
             }
         }
         prof.done(point);
@@ -810,14 +828,14 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
     }
 }
 
-template <typename WT, int PA, int PB> struct Variant {
+template <typename WT, typename KT, int PA, int PB> struct Variant {
     static hipError_t launch(hipStream_t s, const FusedArgs &a, int blocks) {
-        hipLaunchKernelGGL((fused_forward_kernel<WT, PA, PB>), dim3(blocks), dim3(NT), 0, s, a);
+        hipLaunchKernelGGL((fused_forward_kernel<WT, KT, PA, PB>), dim3(blocks), dim3(NT), 0, s, a);
         return hipGetLastError();
     }
     static int blocks_per_cu() {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)fused_forward_kernel<WT, PA, PB>, NT, 0) != hipSuccess) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)fused_forward_kernel<WT, KT, PA, PB>, NT, 0) != hipSuccess) {
             (void)hipGetLastError();
             return 0;
         }
@@ -828,21 +846,28 @@ template <typename WT, int PA, int PB> struct Variant {
 // The instantiations that exist: passes needed to cover d_model and d_ffn with NW waves
 // (bf16: 4096 columns per pass).  (1,1) and (1,2): small models; (1,3): the Llama-2-7B shape;
 // (2,4): 13B; (2,7): 70B.  Calls f(Variant<...>{}) for the one that serves the shape.
+// The cache is fp32, or fp16 for a bf16 model that asked for it.
 template <typename F>
-bool with_variant(int dtype, int d_model, int d_ffn, F &&f) {
+bool with_variant(int dtype, int kv_half, int d_model, int d_ffn, F &&f) {
     const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
     const int span = NW * WAVE * vec;
     const int pa = (d_model + span - 1) / span, pb = (d_ffn + span - 1) / span;
-    if (dtype == SPD_DTYPE_BF16) {
-        if (pa == 1 && pb == 1) return f(Variant<bf16_t, 1, 1>{}), true;
-        if (pa == 1 && pb == 2) return f(Variant<bf16_t, 1, 2>{}), true;
-        if (pa == 1 && pb == 3) return f(Variant<bf16_t, 1, 3>{}), true;
-        if (pa == 2 && pb == 4) return f(Variant<bf16_t, 2, 4>{}), true;
-        if (pa == 2 && pb == 7) return f(Variant<bf16_t, 2, 7>{}), true;
-    } else {
-        if (pa == 1 && pb == 1) return f(Variant<float, 1, 1>{}), true;
-        if (pa == 1 && pb == 2) return f(Variant<float, 1, 2>{}), true;
-        if (pa == 1 && pb == 3) return f(Variant<float, 1, 3>{}), true;
+    if (dtype == SPD_DTYPE_BF16 && kv_half) {
+        if (pa == 1 && pb == 1) return f(Variant<bf16_t, half_t, 1, 1>{}), true;
+        if (pa == 1 && pb == 2) return f(Variant<bf16_t, half_t, 1, 2>{}), true;
+        if (pa == 1 && pb == 3) return f(Variant<bf16_t, half_t, 1, 3>{}), true;
+        if (pa == 2 && pb == 4) return f(Variant<bf16_t, half_t, 2, 4>{}), true;
+        if (pa == 2 && pb == 7) return f(Variant<bf16_t, half_t, 2, 7>{}), true;
+    } else if (dtype == SPD_DTYPE_BF16) {
+        if (pa == 1 && pb == 1) return f(Variant<bf16_t, float, 1, 1>{}), true;
+        if (pa == 1 && pb == 2) return f(Variant<bf16_t, float, 1, 2>{}), true;
+        if (pa == 1 && pb == 3) return f(Variant<bf16_t, float, 1, 3>{}), true;
+        if (pa == 2 && pb == 4) return f(Variant<bf16_t, float, 2, 4>{}), true;
+        if (pa == 2 && pb == 7) return f(Variant<bf16_t, float, 2, 7>{}), true;
+    } else if (!kv_half) {
+        if (pa == 1 && pb == 1) return f(Variant<float, float, 1, 1>{}), true;
+        if (pa == 1 && pb == 2) return f(Variant<float, float, 1, 2>{}), true;
+        if (pa == 1 && pb == 3) return f(Variant<float, float, 1, 3>{}), true;
     }
     return false;
 }
@@ -851,9 +876,9 @@ bool with_variant(int dtype, int d_model, int d_ffn, F &&f) {
 
 namespace spdk {
 
-int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn) {
+int fused_max_blocks_per_cu(int dtype, int kv_half, int d_model, int d_ffn) {
     int n = 0;
-    with_variant(dtype, d_model, d_ffn, [&](auto v) { n = decltype(v)::blocks_per_cu(); });
+    with_variant(dtype, kv_half, d_model, d_ffn, [&](auto v) { n = decltype(v)::blocks_per_cu(); });
     return n;
 }
 
@@ -865,9 +890,9 @@ hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &h, int b
     a.inv_freq = h.inv_freq; a.prof = h.prof; a.sync = h.sync;
     a.n_layers = h.n_layers; a.d_model = h.d_model; a.n_heads = h.n_heads; a.n_kv_heads = h.n_kv_heads;
     a.d_ffn = h.d_ffn; a.vocab = h.vocab; a.cap_ctx = h.cap_ctx; a.max_splits = h.max_splits; a.head = h.head;
-    a.eps = h.eps;
+    a.eps = h.eps; a.kv_half = h.kv_half;
     hipError_t e = hipErrorInvalidValue;
-    with_variant(dtype, h.d_model, h.d_ffn, [&](auto v) { e = decltype(v)::launch(s, a, blocks); });
+    with_variant(dtype, h.kv_half, h.d_model, h.d_ffn, [&](auto v) { e = decltype(v)::launch(s, a, blocks); });
     return e;
 }
 

@@ -88,7 +88,8 @@ struct GemvArgs {
     float *y;            // EPI_PLAIN/RESID/SWIGLU: [rows]; EPI_QKV: q buffer [n_q_rows]
     int32_t rows, cols;
     // EPI_QKV
-    void *kcache, *vcache;      // [n_kv_heads, cap_ctx, d_head] in weight dtype
+    void *kcache, *vcache;      // [n_kv_heads, cap_ctx, d_head], fp32 or (kv_half) fp16
+    int32_t kv_half;
     const DevState *st;         // position
     const double *inv_freq;     // [d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx;
@@ -201,6 +202,7 @@ struct FusedArgsHost {
     long long *prof;                   // optional [blocks][2 * (5 n_layers + 2)] clock stamps
     unsigned *sync;                    // SYNC_WORDS words: the launch count
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, cap_ctx, max_splits, head;
+    int32_t kv_half;                   // the cache holds fp16 (bf16 models only), not fp32
     float eps;
 };
 
@@ -216,6 +218,7 @@ struct PrefillChunk {
     const double *inv_freq;
     char *kv;
     size_t kv_layer_bytes;
+    int32_t kv_half;                   // the cache holds fp16, not fp32
     float *h, *h1;                     // [PREFILL_CHUNK, d_model] residual stream (in / out) and after attention
     float *q;                          // [PREFILL_CHUNK, n_heads * d_head]
     uint16_t *xhi, *xlo;               // [PREFILL_CHUNK, max(d_model, n_heads * d_head)] bf16 pair
@@ -249,7 +252,7 @@ hipError_t advance(hipStream_t s, DevState *st);
 hipError_t renorm(hipStream_t s, DevState *st, int k);
 hipError_t fill_i32(hipStream_t s, int32_t *p, int32_t v, int n);
 // Fused forward: 0 if no instantiation serves this shape, else resident blocks per CU.
-int fused_max_blocks_per_cu(int dtype, int d_model, int d_ffn);
+int fused_max_blocks_per_cu(int dtype, int kv_half, int d_model, int d_ffn);
 hipError_t fused_forward(hipStream_t s, int dtype, const FusedArgsHost &a, int blocks);
 hipError_t init();  // raise the dynamic-LDS limit of the kernels that need it
 // stand-alone attention: argument check (an spd_status) and the launch on a given scratch buffer

@@ -493,10 +493,11 @@ hipError_t gemv(hipStream_t s, int dtype, int epi, const GemvArgs &a, int num_cu
 
 hipError_t attention(hipStream_t s, int dtype, const AttnArgs &a) {
     const dim3 grid(a.n_kv_heads, (a.cap_ctx + a.chunk - 1) / a.chunk);
-    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    const int vec = dtype == SPD_DTYPE_FP32 ? 4 : 8;
     const int lpp = a.d_head / vec;
     const size_t lds = (size_t)(BLOCK / lpp) * a.d_head * sizeof(float);
     if (dtype == SPD_DTYPE_BF16) hipLaunchKernelGGL(attn_kernel<bf16_t>, grid, dim3(BLOCK), lds, s, a);
+    else if (dtype == SPD_DTYPE_FP16) hipLaunchKernelGGL(attn_kernel<half_t>, grid, dim3(BLOCK), lds, s, a);
     else hipLaunchKernelGGL(attn_kernel<float>, grid, dim3(BLOCK), lds, s, a);
     return hipGetLastError();
 }

@@ -35,6 +35,8 @@ struct Layout {
 const char *check_cfg(const spd_model_cfg *c) {
     if (!c) return "cfg is null";
     if (c->dtype != SPD_DTYPE_FP32 && c->dtype != SPD_DTYPE_BF16) return "dtype must be fp32 or bf16";
+    if (c->kv_dtype != SPD_DTYPE_FP32 && c->kv_dtype != SPD_DTYPE_FP16) return "kv_dtype must be fp32 or fp16";
+    if (c->kv_dtype == SPD_DTYPE_FP16 && c->dtype != SPD_DTYPE_BF16) return "an fp16 key/value cache needs bf16 weights";
     if (c->n_layers < 0 || c->d_model <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->d_ffn <= 0 || c->vocab <= 0)
         return "non-positive model dimension";
     if (c->d_model % c->n_heads) return "d_model must be a multiple of n_heads";
@@ -113,7 +115,7 @@ Layout make_layout(const spd_model_cfg &c) {
         L.pf_ks_part = take(L.pf_ks_tiles * 2 * 2 * 16 * 64 * 4);
         L.pf_ks_count = take(L.pf_ks_tiles * 4);
     }
-    L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * sizeof(float));   // fp32 cache
+    L.kv_layer_bytes = up((size_t)c.n_kv_heads * c.max_ctx * dh * (c.kv_dtype == SPD_DTYPE_FP16 ? 2 : 4));
     L.kv = take(L.kv_layer_bytes * 2 * (size_t)c.n_layers);
     L.total = o;
     return L;
@@ -232,7 +234,7 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         f.sync = c->at<unsigned>(c->L.sync);
         f.n_layers = m.n_layers; f.d_model = m.d_model; f.n_heads = m.n_heads; f.n_kv_heads = m.n_kv_heads;
         f.d_ffn = m.d_ffn; f.vocab = m.vocab; f.cap_ctx = m.max_ctx; f.max_splits = c->L.max_splits;
-        f.head = head ? 1 : 0; f.eps = m.rms_eps;
+        f.head = head ? 1 : 0; f.eps = m.rms_eps; f.kv_half = m.kv_dtype == SPD_DTYPE_FP16;
         return launch(c, KC_FUSED, [&] { return spdk::fused_forward(c->stream, m.dtype, f, c->fused_blocks); });
     }
     e = launch(c, KC_SUPERPOSE, [&] { return spdk::superpose(c->stream, m.dtype, sa); });
@@ -247,11 +249,12 @@ hipError_t enqueue_forward(spd_ctx *c, int mode, int k, bool head) {
         g.kcache = c->kcache(l); g.vcache = c->vcache(l); g.st = c->st();
         g.inv_freq = c->at<double>(c->L.inv_freq);
         g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = m.max_ctx;
+        g.kv_half = m.kv_dtype == SPD_DTYPE_FP16;
         e = launch(c, KC_QKV, [&] { return spdk::gemv(c->stream, m.dtype, EPI_QKV, g, c->num_cu); });
         if (e != hipSuccess) return e;
         AttnArgs a{q, c->kcache(l), c->vcache(l), att, c->at<float>(c->L.part), c->at<int32_t>(c->L.counters),
                    c->st(), 0, m.n_heads, m.n_kv_heads, dh, m.max_ctx, ATTN_CHUNK, c->L.max_splits};
-        e = launch(c, KC_ATTN, [&] { return spdk::attention(c->stream, SPD_DTYPE_FP32, a); });   // the cache is fp32
+        e = launch(c, KC_ATTN, [&] { return spdk::attention(c->stream, m.kv_dtype, a); });
         if (e != hipSuccess) return e;
         GemvArgs o{};
         o.W = w.wo; o.x = att; o.resid = h; o.y = h1; o.rows = m.d_model; o.cols = nq;
@@ -360,8 +363,8 @@ namespace spdk {
 int attention_args_status(int dtype, const float *q, const void *K, const void *V, const float *out, int n_heads,
                           int n_kv_heads, int d_head, int n_ctx, int cap_ctx) {
     if (!q || !K || !V || !out) return SPD_EINVAL;
-    if (dtype != SPD_DTYPE_FP32 && dtype != SPD_DTYPE_BF16) return SPD_EINVAL;
-    const int vec = dtype == SPD_DTYPE_BF16 ? 8 : 4;
+    if (dtype != SPD_DTYPE_FP32 && dtype != SPD_DTYPE_BF16 && dtype != SPD_DTYPE_FP16) return SPD_EINVAL;
+    const int vec = dtype == SPD_DTYPE_FP32 ? 4 : 8;
     if (n_heads <= 0 || n_kv_heads <= 0 || n_heads % n_kv_heads || d_head <= 0 || d_head % vec || d_head > 256) return SPD_EINVAL;
     const int lpp = d_head / vec;
     if (lpp > 64 || (lpp & (lpp - 1))) return SPD_EINVAL;
@@ -453,7 +456,7 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     if (e != hipSuccess) { delete c; return SPD_EHIP; }
     c->num_cu = prop.multiProcessorCount;
     {   // the fused forward needs its whole grid resident at once: size it from the occupancy
-        int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->d_model, cfg->d_ffn);
+        int per_cu = spdk::fused_max_blocks_per_cu(cfg->dtype, cfg->kv_dtype == SPD_DTYPE_FP16, cfg->d_model, cfg->d_ffn);
         if (per_cu > 1) per_cu = 1;
         c->fused_blocks = per_cu > 0 ? per_cu * c->num_cu : 0;
         if (c->fused_blocks > FUSED_MAX_BLOCKS) c->fused_blocks = 0;
@@ -553,7 +556,7 @@ static int run_prefix_pass(spd_ctx *c, int p0, int m) {
         pc.embed = c->embed; pc.prefix = c->at<int32_t>(c->L.prefix); pc.layers = c->layers.data();
         pc.n_layers = mc.n_layers; pc.d_model = mc.d_model; pc.n_heads = mc.n_heads; pc.n_kv_heads = mc.n_kv_heads;
         pc.d_ffn = mc.d_ffn; pc.cap_ctx = mc.max_ctx; pc.eps = mc.rms_eps; pc.num_cu = c->num_cu;
-        pc.inv_freq = c->at<double>(c->L.inv_freq); pc.kv = c->ws + c->L.kv; pc.kv_layer_bytes = c->L.kv_layer_bytes;
+        pc.inv_freq = c->at<double>(c->L.inv_freq); pc.kv = c->ws + c->L.kv; pc.kv_layer_bytes = c->L.kv_layer_bytes; pc.kv_half = mc.kv_dtype == SPD_DTYPE_FP16;
         pc.h = c->at<float>(c->L.pf_h); pc.h1 = c->at<float>(c->L.pf_h1); pc.q = c->at<float>(c->L.pf_q);
         pc.xhi = c->at<uint16_t>(c->L.pf_xhi); pc.xlo = c->at<uint16_t>(c->L.pf_xlo);
         pc.uhi = c->at<uint16_t>(c->L.pf_uhi); pc.ulo = c->at<uint16_t>(c->L.pf_ulo);

@@ -22,6 +22,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
+// One element of the key/value cache (fp32, or fp16 rounded to nearest even).
+__device__ __forceinline__ void kv_put(void *cache, int kv_half, size_t at, float v) {
+    if (kv_half) Store<half_t>::store1(cache, at, v);
+    else as_global((float *)cache)[at] = v;
+}
+
 constexpr int KSTEP = 64;         // k per pipeline step (4 MFMAs of k = 16)
 
 __device__ __forceinline__ uint16_t bf16_rn(float v) {
@@ -121,7 +127,8 @@ struct PrefillGemmArgs {
     float *out;                  // [T, N]
     // PE_QKV
     float *q;                    // [T, n_q_rows]
-    float *kcache, *vcache;      // [n_kv_heads, cap_ctx, d_head] fp32
+    void *kcache, *vcache;       // [n_kv_heads, cap_ctx, d_head] fp32, or fp16 (kv_half)
+    int32_t kv_half;
     const float2 *rope;          // [T, d_head / 2]
     int32_t n_q_rows, n_kv_rows, d_head, cap_ctx, p0;
     // PE_SWIGLU
@@ -276,11 +283,11 @@ __global__ __launch_bounds__(64 * NWV) void prefill_gemm_kernel(const PrefillGem
                         if (nc < a.n_q_rows) as_global(a.q)[(size_t)t * a.n_q_rows + nc] = rot;
                         else {
                             const int rr = nc - a.n_q_rows;
-                            as_global(a.kcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = rot;
+                            kv_put(a.kcache, a.kv_half, ((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head, rot);
                         }
                     } else {
                         const int rr = nc - a.n_q_rows - a.n_kv_rows;
-                        as_global(a.vcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = v;
+                        kv_put(a.vcache, a.kv_half, ((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head, v);
                     }
                 }
             } else if (t < a.T && nc < a.N) {
@@ -469,11 +476,11 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
                     if (nc < a.n_q_rows) as_global(a.q)[(size_t)t * a.n_q_rows + nc] = rot;
                     else {
                         const int rr = nc - a.n_q_rows;
-                        as_global(a.kcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = rot;
+                        kv_put(a.kcache, a.kv_half, ((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head, rot);
                     }
                 } else {
                     const int rr = nc - a.n_q_rows - a.n_kv_rows;
-                    as_global(a.vcache)[((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head] = v;
+                    kv_put(a.vcache, a.kv_half, ((size_t)(rr / a.d_head) * a.cap_ctx + a.p0 + t) * a.d_head + rr % a.d_head, v);
                 }
             }
         } else if (t < a.T && nc < a.N) {
@@ -488,18 +495,40 @@ __global__ __launch_bounds__(64 * NWV) void prefill_skinny_kernel(const PrefillG
 }
 
 // ------------------------------------------------------------------ causal attention over the chunk
+// Four (two) consecutive elements of the key/value cache, element type KT, from element `at`.
+template <typename KT> __device__ __forceinline__ float4 kv_load4(const void *base, size_t at);
+template <> __device__ __forceinline__ float4 kv_load4<float>(const void *base, size_t at) { return global_load_float4((const float *)base + at); }
+template <> __device__ __forceinline__ float4 kv_load4<half_t>(const void *base, size_t at) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const u32x2 w = *(const u32x2 __attribute__((address_space(1))) *)((const uint16_t *)base + at);
+    const uint32_t x = w.x, y = w.y;   // (bit casts of copies, not of the vector's elements)
+    const h2 lo = __builtin_bit_cast(h2, x), hi = __builtin_bit_cast(h2, y);
+    return make_float4((float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y);
+}
+template <typename KT> __device__ __forceinline__ float2 kv_load2(const void *base, size_t at);
+template <> __device__ __forceinline__ float2 kv_load2<float>(const void *base, size_t at) {
+    return make_float2(as_global((const float *)base)[at], as_global((const float *)base)[at + 1]);
+}
+template <> __device__ __forceinline__ float2 kv_load2<half_t>(const void *base, size_t at) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const uint32_t x = *(const uint32_t __attribute__((address_space(1))) *)((const uint16_t *)base + at);
+    const h2 v = __builtin_bit_cast(h2, x);
+    return make_float2((float)v.x, (float)v.y);
+}
 // One block: one query head, AQ queries of the chunk; keys / values streamed through LDS in
 // chunks of AK cached positions (fp32 cache), online softmax.  Output as the (hi, lo) pair.
 constexpr int ANT = 256, AQ = 32, AK = 64;
 
 struct PrefillAttnArgs {
     const float *q;               // [T, n_heads * d_head]
-    const float *kcache, *vcache; // [n_kv_heads, cap_ctx, d_head]
+    const void *kcache, *vcache;  // [n_kv_heads, cap_ctx, d_head] in the kernel's KT
     uint16_t *ohi, *olo;          // [T_pad, n_heads * d_head]
     int32_t T, p0, n_heads, n_kv_heads, d_head, cap_ctx;
     bool tiled;                   // layout of ohi / olo: see act_at
 };
 
+template <typename KT>
 __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs a) {
     extern __shared__ __align__(16) float lds[];
     // row strides: 16-byte aligned, and consecutive rows 4 banks apart (no conflicts for the
@@ -527,15 +556,15 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) acc[g4] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int last = min(a.p0 + q0 + AQ - 1, a.p0 + a.T - 1);   // last position any query of the tile sees
-    const float *Kg = a.kcache + (size_t)g * a.cap_ctx * dh, *Vg = a.vcache + (size_t)g * a.cap_ctx * dh;
+    const size_t head_at = (size_t)g * a.cap_ctx * dh;
     for (int c0 = 0; c0 <= last; c0 += AK) {
         __syncthreads();
         for (int e = tid; e < AK * dh4; e += ANT) {
             const int j = e / dh4, c = 4 * (e % dh4), pos = c0 + j;
             float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
             if (pos <= last) {
-                kv = global_load_float4(Kg + (size_t)pos * dh + c);
-                vv = global_load_float4(Vg + (size_t)pos * dh + c);
+                kv = kv_load4<KT>(a.kcache, head_at + (size_t)pos * dh + c);
+                vv = kv_load4<KT>(a.vcache, head_at + (size_t)pos * dh + c);
             }
             *(float4 *)(Ks + j * ldk + c) = kv;
             *(float4 *)(Vs + j * dh + c) = vv;
@@ -622,7 +651,7 @@ __global__ __launch_bounds__(ANT) void prefill_attn_kernel(const PrefillAttnArgs
 // Q sits in LDS in operand order; K and V come straight from the cache into the same registers,
 // one after the other, which keeps a wave under half the register file: two waves share a
 // SIMD and one computes while the other waits for its loads.
-template <int DH>
+template <int DH, typename KT>
 __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const PrefillAttnArgs a) {
     constexpr int HALF = DH / 2, NT = DH / 32, NWV = 4;
     constexpr int SLOT = (2 + 16 * NT) * WAVE;               // one wave's partial result: m, sum, O^T
@@ -648,7 +677,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
             q_lds[(i + 2) * WAVE + lane] = v.z; q_lds[(i + 3) * WAVE + lane] = v.w;
         }
     }
-    const float *Kb = a.kcache + (size_t)kvh * a.cap_ctx * DH, *Vb = a.vcache + (size_t)kvh * a.cap_ctx * DH;
+    const size_t head_at = (size_t)kvh * a.cap_ctx * DH;
     const int qpos = a.p0 + q0 + c;                          // cached positions 0 .. qpos are visible to this lane's query
     const int last_key = a.p0 + min(q0 + 31, a.T - 1);       // last position any query of the tile sees
     float m = -INFINITY, lsum = 0.f;
@@ -665,10 +694,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
         for (int r = 0; r < 16; ++r) st[r] = 0.f;
         {
             float kreg[HALF];
-            const float *krow = Kb + (size_t)min(k0 + c, last_key) * DH + HALF * h;
+            const size_t krow = head_at + (size_t)min(k0 + c, last_key) * DH + HALF * h;
 #pragma unroll
             for (int i = 0; i < HALF; i += 4) {
-                const float4 v = global_load_float4(krow + i);
+                const float4 v = kv_load4<KT>(a.kcache, krow + i);
                 kreg[i] = v.x; kreg[i + 1] = v.y; kreg[i + 2] = v.z; kreg[i + 3] = v.w;
             }
 #pragma unroll
@@ -680,12 +709,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_mfma_kernel(const Prefill
         float vreg[NT][16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {   // one 16-byte piece per key: features NT c .. NT c + NT - 1, one for each product tile
-            const float *vrow = Vb + (size_t)min(k0 + 8 * (i / 4) + 4 * h + i % 4, last_key) * DH + NT * c;
+            const size_t vrow = head_at + (size_t)min(k0 + 8 * (i / 4) + 4 * h + i % 4, last_key) * DH + NT * c;
             if (NT == 4) {
-                const float4 v = global_load_float4(vrow);
+                const float4 v = kv_load4<KT>(a.vcache, vrow);
                 vreg[0][i] = v.x; vreg[1][i] = v.y; vreg[2][i] = v.z; vreg[3 % NT][i] = v.w;
             } else {
-                vreg[0][i] = as_global(vrow)[0]; vreg[1 % NT][i] = as_global(vrow)[1];
+                const float2 v = kv_load2<KT>(a.vcache, vrow);
+                vreg[0][i] = v.x; vreg[1 % NT][i] = v.y;
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -803,7 +833,8 @@ static void launch_gemm(hipStream_t s, const PrefillGemmArgs &g, int num_cu) {
 }
 
 hipError_t prefill_init() {
-    hipError_t e = hipFuncSetAttribute((const void *)prefill_attn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
+    hipError_t e = hipFuncSetAttribute((const void *)prefill_attn_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)prefill_attn_kernel<half_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_attn_lds(128));
     const int big = (2 * 2 * 128 + 4 * 2 * 32) * A_ROW;     // at least what any instantiation asks for
 #define SPD_LDS(K, B) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)(K), hipFuncAttributeMaxDynamicSharedMemorySize, B)
     SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 4>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 2>), big); SPD_LDS((prefill_gemm_kernel<PE_QKV, GEMM_TT, 1>), big);
@@ -830,18 +861,22 @@ hipError_t prefill_chunk(hipStream_t s, const PrefillChunk &c) {
         hipLaunchKernelGGL(rmsnorm_split_kernel, dim3(T), dim3(256), 0, s, h, (const uint16_t *)w.attn_norm, c.eps, d, c.xhi, c.xlo, tiled);
         PrefillGemmArgs g{};
         g.xhi = c.xhi; g.xlo = c.xlo; g.W = (const uint16_t *)w.wqkv; g.T = T; g.N = nq + 2 * nkv; g.K = d;
-        g.q = c.q; g.kcache = (float *)(c.kv + (size_t)(2 * l) * c.kv_layer_bytes);
-        g.vcache = (float *)(c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes);
+        g.q = c.q; g.kcache = c.kv + (size_t)(2 * l) * c.kv_layer_bytes;
+        g.vcache = c.kv + (size_t)(2 * l + 1) * c.kv_layer_bytes; g.kv_half = c.kv_half;
         g.tiled = tiled; g.ks_part = c.ks_part; g.ks_count = c.ks_count; g.rope = c.rope; g.n_q_rows = nq; g.n_kv_rows = nkv; g.d_head = dh; g.cap_ctx = c.cap_ctx; g.p0 = c.p0;
         launch_gemm<PE_QKV, GEMM_TT>(s, g, c.num_cu);
 
         PrefillAttnArgs at{c.q, g.kcache, g.vcache, c.xhi, c.xlo, T, c.p0, c.n_heads, c.n_kv_heads, dh, c.cap_ctx, tiled};
-        if (dh == 128)
-            hipLaunchKernelGGL(prefill_attn_mfma_kernel<128>, dim3(((T + 31) / 32) * ((c.n_heads + 7) / 8) * 8), dim3(256), 0, s, at);
-        else if (dh == 64)
-            hipLaunchKernelGGL(prefill_attn_mfma_kernel<64>, dim3(((T + 31) / 32) * ((c.n_heads + 7) / 8) * 8), dim3(256), 0, s, at);
-        else
-            hipLaunchKernelGGL(prefill_attn_kernel, dim3((T + AQ - 1) / AQ, c.n_heads), dim3(ANT), prefill_attn_lds(dh), s, at);
+        const dim3 mfma_grid(((T + 31) / 32) * ((c.n_heads + 7) / 8) * 8), plain_grid((T + AQ - 1) / AQ, c.n_heads);
+        if (c.kv_half) {
+            if (dh == 128) hipLaunchKernelGGL((prefill_attn_mfma_kernel<128, half_t>), mfma_grid, dim3(256), 0, s, at);
+            else if (dh == 64) hipLaunchKernelGGL((prefill_attn_mfma_kernel<64, half_t>), mfma_grid, dim3(256), 0, s, at);
+            else hipLaunchKernelGGL(prefill_attn_kernel<half_t>, plain_grid, dim3(ANT), prefill_attn_lds(dh), s, at);
+        } else {
+            if (dh == 128) hipLaunchKernelGGL((prefill_attn_mfma_kernel<128, float>), mfma_grid, dim3(256), 0, s, at);
+            else if (dh == 64) hipLaunchKernelGGL((prefill_attn_mfma_kernel<64, float>), mfma_grid, dim3(256), 0, s, at);
+            else hipLaunchKernelGGL(prefill_attn_kernel<float>, plain_grid, dim3(ANT), prefill_attn_lds(dh), s, at);
+        }
 
         PrefillGemmArgs o{};
         o.xhi = c.xhi; o.xlo = c.xlo; o.W = (const uint16_t *)w.wo; o.T = T; o.N = d; o.K = nq; o.resid = h; o.out = h1; o.tiled = tiled; o.ks_part = c.ks_part; o.ks_count = c.ks_count;

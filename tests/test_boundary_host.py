@@ -55,6 +55,12 @@ def test_workspace_bytes_and_config_validation(pkg):
         assert e.value.code == -1
     for shape in (synth.TINY, synth.LLAMA13B, synth.LLAMA70B):
         assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(shape, 1100, 8)) > 0
+    # an fp16 cache: half the cache bytes, bf16 models only, nothing but fp32 / fp16 is a cache type
+    assert pkg.spd_workspace_bytes(pkg.binding.model_cfg(synth.LLAMA7B, 128, 8, "fp16")) == need - kv // 2
+    for shape, kv_dtype in [(synth.TINY, "fp16"), (synth.LLAMA7B, "bf16")]:
+        with pytest.raises(pkg.SpdError) as e:
+            pkg.spd_workspace_bytes(pkg.binding.model_cfg(shape, 128, 8, kv_dtype))
+        assert e.value.code == -1
 
 
 def test_create_rejects_null_arguments_before_any_gpu_work(pkg):

@@ -21,10 +21,15 @@ def mat(rows, cols, dtype, seed, std=0.02):
     if dtype == "bf16":
         bits = synth.bf16_bits(w).reshape(rows, cols)
         return bits, synth.bf16_widen(bits)
+    if dtype == "fp16":      # key/value cache only: numpy's own binary16 rounding (to nearest even)
+        h = w.astype(np.float16)
+        return h, h.astype(np.float32)
     return w, w
 
 
 def dev(a, dtype):
+    if dtype == "fp16":
+        return torch.from_numpy(a).cuda()
     return P().binding.to_device(a, dtype)
 
 
@@ -61,7 +66,7 @@ def test_swiglu(dtype, rows, cols):
     assert_close_scaled(u.cpu().numpy(), want, 2e-5, "swiglu")
 
 
-@pytest.mark.parametrize("dtype,dh", [("bf16", 128), ("fp32", 64), ("bf16", 64), ("fp32", 128)])
+@pytest.mark.parametrize("dtype,dh", [("bf16", 128), ("fp32", 64), ("bf16", 64), ("fp32", 128), ("fp16", 128), ("fp16", 64), ("fp16", 32)])
 @pytest.mark.parametrize("heads,kv", [(4, 4), (8, 1), (8, 2)])
 @pytest.mark.parametrize("n_ctx,cap", [(1, 8), (7, 300), (128, 128), (129, 300), (256, 256), (257, 600), (1044, 1100)])
 def test_attention(dtype, dh, heads, kv, n_ctx, cap):

@@ -161,15 +161,17 @@ def test_greedy_draft_commit_keeps_the_cache(tiny):
         sess.close()
 
 
+@pytest.mark.parametrize("kv_dtype", ["fp32", "fp16"])
 @pytest.mark.parametrize("dense", [True, False])
-def test_commit_through_the_dense_prefix_pass(dense):
+def test_commit_through_the_dense_prefix_pass(dense, kv_dtype):
     """A 12-token segment on a bf16 model: the committed tokens are passed again as one chunk on
-    the matrix cores, starting at a cache position that is no multiple of any tile."""
+    the matrix cores, starting at a cache position that is no multiple of any tile (an odd one:
+    with an fp16 cache, rows that start in the middle of a 16-byte piece)."""
     shape = synth.ModelShape("small-bf16", 2, 512, 8, 2, 1408, 2048, "bf16")
     w = synth.make_weights(shape, seed=5)
     prefix = synth.make_prefix_zipf(shape.vocab, 37, seed=5)
     pkg = P()
-    sess = pkg.Session(shape, w, max_ctx=128, k_max=8)
+    sess = pkg.Session(shape, w, max_ctx=128, k_max=8, kv_dtype=kv_dtype)
     try:
         sess.spd_set_dense_prefill(dense)
         assert sess.spd_get_dense_prefill() == dense

@@ -15,8 +15,8 @@ def P():
     return pkg
 
 
-def session(shape, weights, max_ctx=64, k_max=8):
-    return P().Session(shape, weights, max_ctx=max_ctx, k_max=k_max)
+def session(shape, weights, max_ctx=64, k_max=8, kv_dtype="fp32"):
+    return P().Session(shape, weights, max_ctx=max_ctx, k_max=k_max, kv_dtype=kv_dtype)
 
 
 def planted_tables(shape, weights, base, prefix, k, n_tokens, seed=0, tau=1.0):
@@ -56,9 +56,9 @@ def select_path(sess, path):
 
 
 def run_teacher_forced(shape, w, tabs, lambdas, prefix, k, alpha, n_tokens, tau=1.0, delta=0.1, max_ctx=64,
-                       path="fused"):
+                       path="fused", kv_dtype="fp32"):
     pkg = P()
-    sess = session(shape, w, max_ctx=max_ctx)
+    sess = session(shape, w, max_ctx=max_ctx, kv_dtype=kv_dtype)
     try:
         select_path(sess, path)
         if tabs is not None:
@@ -168,7 +168,7 @@ def test_two_pass_ffn_rows(forward_path):
     run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 2, 0.0, 4, path=forward_path)
 
 
-def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_path, alpha=0.54):
+def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_path, alpha=0.54, kv_dtype="fp32"):
     """A published shape with its real widths and head layout but few layers (the oracle runs on
     the host): weights drawn on the GPU, n-gram tables planted along the oracle's path."""
     pkg = P()
@@ -180,7 +180,7 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
     lm = make_oracle(shape, host)
     _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(k, 0.0), n_tokens)
     tabs = plant_both_forms(base, recs0, k, shape.vocab, seed + 1)
-    sess = pkg.Session(shape, wdev, max_ctx=prefix_len + n_tokens + 8, k_max=8)
+    sess = pkg.Session(shape, wdev, max_ctx=prefix_len + n_tokens + 8, k_max=8, kv_dtype=kv_dtype)
     try:
         select_path(sess, forward_path)
         sess.spd_load_ngrams(tabs, synth.PAPER_LAMBDAS)
@@ -188,7 +188,9 @@ def _layer_truncated(shape, n_layers, prefix_len, k, n_tokens, seed, forward_pat
         cfg = O.DecodeCfg(k, alpha, 1.0, 0.1, synth.PAPER_LAMBDAS)
         _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, n_tokens, RTOL["bf16"], dc)
         print(shape.name, "scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats if "logit_err" in s])
-        report_decisions(shape.name, stats, n_tokens)
+        name = shape.name + (" (fp16 cache)" if kv_dtype == "fp16" else "")
+        report_decisions(name, stats, n_tokens)
+        return stats
     finally:
         sess.close()
 
@@ -280,6 +282,80 @@ def test_dense_prefix_pass_matches_the_oracle_and_the_token_by_token_pass(m):
         finally:
             sess.close()
     assert np.max(np.abs(logits[True] - logits[False])) <= 1e-4 * np.max(np.abs(logits[False]))
+
+
+# ---- the fp16 key/value cache a bf16 model may ask for (spd_model_cfg.kv_dtype): every kernel that
+# writes or reads the cache, against the same oracle (which keeps its keys and values unrounded), to
+# the bf16 tolerance; the rounding of the cache is the only difference to the fp32-cache cases above,
+# whose tighter bounds pin the logic.
+FP16_CACHE_LOGIT_ERR = 8e-3   # of the largest |logit|: 11 significant bits in every cached key and value
+
+
+def test_fp16_cache_small_model_gqa(forward_path):
+    shape = synth.ModelShape("small-bf16", 3, 512, 8, 2, 1408, 2048, "bf16")
+    w = synth.make_weights(shape, seed=5)
+    prefix = synth.make_prefix_zipf(shape.vocab, 37, seed=5)
+    base = synth.make_ngram_tables_zipf(shape.vocab, 30_000, seed=5)
+    planted = planted_tables(shape, w, base, prefix, 3, 8)
+    _, _, stats = run_teacher_forced(shape, w, planted, synth.PAPER_LAMBDAS, prefix, 3, 0.54, 8, path=forward_path, kv_dtype="fp16")
+    assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("prefix_len,k", [(40, 3), (200, 3), (300, 5), (1030, 8)])
+def test_fp16_cache_7b_shape_two_layers(forward_path, prefix_len, k):
+    """Llama-2-7B widths, two layers, fp16 cache: a short context, one attention item per head in
+    two batches of loads (200), chunks merged across blocks (300, and BASELINE config 3's 1030
+    with k = 8, whose prefix also crosses a chunk of the dense prefix pass)."""
+    stats = _layer_truncated(synth.LLAMA7B, 2, prefix_len, k, 3, 8, forward_path, kv_dtype="fp16")
+    assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
+
+
+@pytest.mark.timeout(600)
+def test_fp16_cache_13b_shape_two_layers():
+    stats = _layer_truncated(synth.LLAMA13B, 2, 140, 5, 4, 13, "fused", kv_dtype="fp16")
+    assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
+
+
+@pytest.mark.timeout(600)
+def test_fp16_cache_70b_shape_one_layer():
+    """Grouped key/value heads (8 query heads per cached head) over an attention chunk boundary."""
+    stats = _layer_truncated(synth.LLAMA70B, 1, 131, 3, 3, 70, "fused", kv_dtype="fp16")
+    assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
+
+
+@pytest.mark.parametrize("m", [8, 33, 96, 300, 1043])
+def test_fp16_cache_dense_prefix_pass(m):
+    """The prefix pass on the matrix cores and the token-by-token pass fill the fp16 cache with the
+    same roundings of (nearly) the same values: their logits agree far more closely than either
+    agrees with the oracle."""
+    shape = synth.ModelShape("small-bf16-dense", 3, 512, 8, 2, 1408, 2048, "bf16")
+    w = synth.make_weights(shape, seed=21)
+    prefix = synth.make_prefix_zipf(shape.vocab, m, seed=m)
+    lm = make_oracle(shape, w)
+    cfg = O.DecodeCfg(3, 0.0)
+    dc = P().SpdDecodeCfg(3, 0.0, 1.0, 0.1)
+    logits = {}
+    for dense in (True, False):
+        sess = session(shape, w, max_ctx=m + 16, kv_dtype="fp16")
+        try:
+            sess.spd_set_dense_prefill(dense)
+            state, recs, stats = teacher_forced(sess, lm, None, synth.PAPER_LAMBDAS, prefix, cfg, 4, RTOL["bf16"], dc)
+            assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
+            sess.spd_prefill(prefix)
+            logits[dense] = sess.spd_read_logits()
+        finally:
+            sess.close()
+    assert np.max(np.abs(logits[True] - logits[False])) <= 1e-3 * np.max(np.abs(logits[False]))
+
+
+def test_fp16_cache_head_width_32_plain_prefix_attention():
+    """d_head 32: the prefix pass uses its plain (not matrix-core) attention kernel."""
+    shape = synth.ModelShape("small-bf16-dh32", 2, 256, 8, 4, 512, 1024, "bf16")
+    w = synth.make_weights(shape, seed=23)
+    prefix = synth.make_prefix_zipf(shape.vocab, 150, seed=23)
+    _, _, stats = run_teacher_forced(shape, w, None, synth.PAPER_LAMBDAS, prefix, 3, 0.0, 4, max_ctx=200, kv_dtype="fp16")
+    assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
 
 
 def test_dense_prefix_pass_is_refused_where_it_does_not_exist(tiny):
@@ -506,11 +582,13 @@ def test_error_paths(tiny):
 
 
 @pytest.mark.timeout(900)
-def test_full_size_7b_shape_teacher_forced():
+@pytest.mark.parametrize("kv_dtype", ["fp16", "fp32"])
+def test_full_size_7b_shape_teacher_forced(kv_dtype):
     """BASELINE config 2 at its real size and in the launch configuration the benchmark times
-    (fused forward, graph replay): Llama-2-7B shape, bf16, 64-token Zipf prefix, k = 3,
-    alpha = 0.54, synthetic n = 2..6 tables.  The oracle runs the full model on the host (a few
-    seconds per step), so three timesteps are compared, teacher-forced."""
+    (fused forward, graph replay, fp16 cache; and with the fp32 cache): Llama-2-7B shape, bf16,
+    64-token Zipf prefix, k = 3, alpha = 0.54, synthetic n = 2..6 tables.  The oracle runs the
+    full model on the host (a few seconds per step), so three timesteps are compared,
+    teacher-forced."""
     pkg = P()
     shape = synth.LLAMA7B
     wdev = synth.make_weights_device(shape, seed=0)
@@ -520,7 +598,7 @@ def test_full_size_7b_shape_teacher_forced():
     lm = make_oracle(shape, host)
     _, recs0 = O.generate(lm, None, prefix, O.DecodeCfg(3, 0.0), 3)
     tabs = plant_both_forms(base, recs0, 3, shape.vocab, 1)
-    sess = pkg.Session(shape, wdev, max_ctx=128, k_max=8)
+    sess = pkg.Session(shape, wdev, max_ctx=128, k_max=8, kv_dtype=kv_dtype)
     try:
         assert sess.spd_get_fused()
         sess.spd_load_ngrams(tabs, synth.PAPER_LAMBDAS)
@@ -529,7 +607,7 @@ def test_full_size_7b_shape_teacher_forced():
         _, recs, stats = teacher_forced(sess, lm, tabs, synth.PAPER_LAMBDAS, prefix, cfg, 3, RTOL["bf16"], dc)
         assert all("logit_err" in s for s in stats)
         print("7B scaled logit errors:", [f"{s['logit_err']:.2e}" for s in stats])
-        report_decisions("7B full size", stats, 3)
+        report_decisions(f"7B full size ({kv_dtype} cache)", stats, 3)
     finally:
         sess.close()
 
