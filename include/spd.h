@@ -287,8 +287,8 @@ int spd_op_swiglu(int32_t dtype, const void *Wg, const void *Wu, const void *gai
                   const float *x, float *u, int32_t rows, int32_t cols, void *hip_stream);
 /* Single-query attention over n_ctx cached positions: out[h] = softmax(q[h] . K / sqrt(d_head)) V
  * with K, V DEVICE [n_kv_heads, cap_ctx, d_head] in `dtype` (head-major, as the library's
- * cache, which itself is always fp32), q and out DEVICE float [n_heads, d_head]; `partials` is DEVICE scratch of
- * spd_op_attention_scratch_bytes() bytes. */
+ * cache, which is fp32 or fp16: SPD_DTYPE_FP16 is accepted here too), q and out DEVICE float
+ * [n_heads, d_head]; `partials` is DEVICE scratch of spd_op_attention_scratch_bytes() bytes. */
 size_t spd_op_attention_scratch_bytes(int32_t n_heads, int32_t d_head, int32_t cap_ctx);
 int spd_op_attention(int32_t dtype, const float *q, const void *K, const void *V, float *out,
                      void *partials, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,

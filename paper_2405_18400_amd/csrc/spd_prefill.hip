@@ -517,7 +517,7 @@ template <> __device__ __forceinline__ float2 kv_load2<half_t>(const void *base,
     return make_float2((float)v.x, (float)v.y);
 }
 // One block: one query head, AQ queries of the chunk; keys / values streamed through LDS in
-// chunks of AK cached positions (fp32 cache), online softmax.  Output as the (hi, lo) pair.
+// chunks of AK cached positions (cache elements of type KT, widened on load), online softmax.  Output as the (hi, lo) pair.
 constexpr int ANT = 256, AQ = 32, AK = 64;
 
 struct PrefillAttnArgs {
