@@ -36,7 +36,7 @@ namespace {
 constexpr int FUSED_UA = 16;          // rows per tile where one pass covers a row
 constexpr int FUSED_UO_EXTRA = 4;     // extra rows per tile of the O projection
 constexpr int FUSED_QD = 20;          // 16-byte pieces per lane of a phase's first tile requested while its input is awaited
-constexpr int FUSED_QD_ITEM = 12;     // of which this many are requested before an attention item (they stay in registers through it)
+constexpr int FUSED_QD_ITEM = 4;      // of which this many are requested before an attention item (they stay in registers through it)
 constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
 constexpr int FUSED_SLICE_GATE = 4;   // the first slice of the gate/up phase (its input follows the attention within a microsecond or two)
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
