@@ -92,14 +92,20 @@ __device__ __forceinline__ int crossing(Stage &s, int lv, unsigned long long x) 
     const int t = threadIdx.x;
     if (t == 0) { s.found = -1; s.lastb = 0; }
     __syncthreads();
+    int last = 0;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const int b = 2 * t + q;
         const unsigned long long e = mass_of(s.hm[lv][b]), i = mass_of(s.hm[lv][b + 1]);
         if (STRICT ? (e <= x && i > x) : (e < x && i >= x)) s.found = b;     // one bucket at most
-        if (count_of(s.hm[lv][b + 1]) > count_of(s.hm[lv][b])) atomicMax(&s.lastb, b);
+        if (count_of(s.hm[lv][b + 1]) > count_of(s.hm[lv][b])) last = b;
     }
     __syncthreads();
+    if (s.found < 0) {   // (the same for every thread) nothing reaches x: one atomic per wave, not one per bucket on one address
+        last = (int)wave_all_max((float)last);   // bucket numbers are exact in a float
+        if ((t & (WAVE - 1)) == 0) atomicMax(&s.lastb, last);
+        __syncthreads();
+    }
     const int b = s.found >= 0 ? s.found : s.lastb;
     __syncthreads();
     return b;
