@@ -145,6 +145,8 @@ struct NucleusArgs {
     int32_t n_part, per_part;    // one block per slice of per_part entries
     unsigned long long *sc_pb;   // scratch, [vocab]: first-level bucket above the probability in 40-bit fixed point
     unsigned *sc_count;          // blocks that have finished their slice; zero between calls
+    unsigned long long *sc_hist; // scratch, [2048]: entry count above probability mass per first-level bucket; zero between calls
+    uint16_t *sc_bk;             // scratch, [32768]: first-level bucket per entry, 0xFFFF past the vocabulary (vocab <= 32768 only)
     float top_p, tau;
     int32_t first, advance;
     int32_t *hist_tok, *hist_par;

@@ -24,7 +24,7 @@ struct Layout {
     size_t pf_h, pf_h1, pf_q, pf_xhi, pf_xlo, pf_uhi, pf_ulo, pf_rope;   // dense prefix pass arena (0 = none)
     size_t pf_ks_part, pf_ks_count, pf_ks_tiles;
     bool dense;
-    size_t state, sync, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, pn, nuc_pb, nuc_count, kv, total;
+    size_t state, sync, layers_dev, prof, act, logits, part, counters, inv_freq, prefix, hist_tok, hist_par, pv, pi, pm, ps, pn, nuc_pb, nuc_count, nuc_hist, nuc_bk, kv, total;
     size_t kv_layer_bytes;   // K (or V) of one layer
     size_t arena_bytes;      // one activation arena
     int max_splits, n_part, per_part;
@@ -96,6 +96,8 @@ Layout make_layout(const spd_model_cfg &c) {
     L.pn = take((size_t)L.n_part * 4);
     L.nuc_pb = take((size_t)c.vocab * 8);      // the nucleus sampler's per-entry scratch
     L.nuc_count = take(4);
+    L.nuc_hist = take(2048 * 8);
+    L.nuc_bk = take(32768 * 2);
     // dense prefix pass (matrix cores): bf16 weights, d_head <= 128, widths the tiles divide,
     // d_model within what its norm kernel keeps in registers
     L.dense = c.dtype == SPD_DTYPE_BF16 && dh <= 128 && c.d_model % 128 == 0 && c.d_model <= 8192 && c.d_ffn % 128 == 0 &&
@@ -307,6 +309,8 @@ hipError_t enqueue_sample(spd_ctx *c, const spd_sample_cfg &sc, const float *log
     n.per_part = c->L.per_part;
     n.sc_pb = c->at<unsigned long long>(c->L.nuc_pb);
     n.sc_count = c->at<unsigned>(c->L.nuc_count);
+    n.sc_hist = c->at<unsigned long long>(c->L.nuc_hist);
+    n.sc_bk = c->at<uint16_t>(c->L.nuc_bk);
     n.top_p = sc.top_p; n.tau = sc.tau; n.first = first; n.advance = advance;
     n.hist_tok = c->at<int32_t>(c->L.hist_tok); n.hist_par = c->at<int32_t>(c->L.hist_par);
     n.max_gen = c->cfg.max_ctx;
@@ -477,6 +481,8 @@ int spd_create(const spd_model_cfg *cfg, const spd_weight_ptrs *w, void *workspa
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.counters), 0, cfg->n_heads * ATTN_COUNTER_STRIDE);
     if (e == hipSuccess && L.dense) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.pf_ks_count), 0, (int)L.pf_ks_tiles);
     if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.nuc_count), 0, 1);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.nuc_hist), 0, 2048 * 2);
+    if (e == hipSuccess) e = spdk::fill_i32(c->stream, c->at<int32_t>(L.nuc_bk), -1, 32768 / 2);   // 0xFFFF: no bucket
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return SPD_EHIP; }
     *out = c;

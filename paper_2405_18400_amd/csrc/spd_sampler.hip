@@ -13,8 +13,11 @@
 //
 //   stage A (one block per slice of the vocabulary, all compute units in parallel): scaled
 //     logit z, probability, and a bucket number that is linear in z between the largest and the
-//     smallest z (2048 buckets), stored per entry; the last block to finish goes on alone;
-//   stage B: mass and count per bucket (LDS atomics), prefix sums over the buckets, the bucket
+//     smallest z (2048 buckets), stored per entry; mass and count per bucket of the slice (LDS
+//     atomics), added to the histogram in memory (one atomic per bucket the slice touches; sums
+//     of integers: the same in any order); the last block to finish goes on alone;
+//   stage B: that histogram (vocabularies beyond 32768 entries: built here from the entries'
+//     words instead), prefix sums over the buckets, the bucket
 //     in which the cumulative mass crosses x; should it hold more than a list's worth of
 //     entries it is cut again by key range (2048 sub-buckets per round: at most a few rounds
 //     even where thousands of entries tie); the bucket's entries are then ranked against one
@@ -132,6 +135,18 @@ struct Entries {
     const unsigned long long *pb;
     int vocab;
     unsigned bk[CACHED ? ITEMS / 2 : 1];
+    // CACHED: entry c of this thread is token 8 (tid + SNT (c / 8)) + c % 8 -- its bucket numbers are
+    // four 16-byte pieces of the per-entry bucket array (0xFFFF past the vocabulary)
+    static __device__ __forceinline__ int entry(int c) { return CACHED ? 8 * ((int)threadIdx.x + (c / 8) * SNT) + (c % 8) : (int)threadIdx.x + c * SNT; }
+    __device__ __forceinline__ void load_buckets(const uint16_t *ids) {
+        static_assert(!CACHED || ITEMS == 32, "four pieces of eight bucket numbers");
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(ids), 0, SNT * ITEMS * 2, 0x00020000);
+#pragma unroll
+        for (int r = 0; r < (CACHED ? 4 : 0); ++r) {
+            const u32x4 v = coherent_load16(rs, 16u * (threadIdx.x + (unsigned)(r * SNT)));
+            bk[4 * r] = v.x; bk[4 * r + 1] = v.y; bk[4 * r + 2] = v.z; bk[4 * r + 3] = v.w;
+        }
+    }
     // f(i, bucket of entry i, its probability) for every entry of this thread
     template <typename F>
     __device__ __forceinline__ void first_walk(F &&f) {
@@ -172,7 +187,7 @@ struct Entries {
             while (hits) {   // (few: a bucket holds some dozens of the block's entries)
                 const int c = __ffs(hits) - 1;
                 hits &= hits - 1u;
-                const int i = threadIdx.x + c * SNT;
+                const int i = entry(c);
                 f(i, load_pb(pb, i) & P_MASK);
             }
         } else {
@@ -302,13 +317,30 @@ __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
 
     // ---- stage A: this block's slice
     const int lo = blockIdx.x * a.per_part, hi = min(a.vocab, lo + a.per_part);
+    if (CACHED) {   // the slice's histogram
+        s.hm[1][2 * tid] = 0ull; s.hm[1][2 * tid + 1] = 0ull;
+        __syncthreads();
+    }
     for (int i = lo + tid; i < hi; i += SNT) {
         const float z = __fdiv_rn(as_global(a.logits)[i], a.tau);
         const float p = expf(z - lse);
         const float fb = (M - z) * scale;                          // monotonic in z; anything beyond lands in the last bucket
         const int b = fb < (float)(NB - 1) ? (int)fb : NB - 1;
         const unsigned long long pf = (unsigned long long)(p * FX_ONE);   // <= 2^40 (1 + a few ulp)
-        __hip_atomic_store(as_global(a.sc_pb) + i, ((unsigned long long)(b < 0 ? 0 : b) << PB_SHIFT) | pf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int bb = b < 0 ? 0 : b;
+        __hip_atomic_store(as_global(a.sc_pb) + i, ((unsigned long long)bb << PB_SHIFT) | pf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (CACHED) {
+            __hip_atomic_store(as_global(a.sc_bk) + i, (uint16_t)bb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            atomicAdd(&s.hm[1][bb], pf + ONE_ENTRY);
+        }
+    }
+    if (CACHED) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const unsigned long long w = s.hm[1][2 * tid + q];
+            if (w) (void)__hip_atomic_fetch_add(as_global(a.sc_hist) + 2 * tid + q, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's write-through stores have been acknowledged
     __syncthreads();
@@ -319,11 +351,22 @@ __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
     // ---- stage B: first-level histogram
     Entries<CACHED> en;
     en.pb = a.sc_pb; en.vocab = a.vocab;
-    s.hm[0][2 * tid] = 0ull; s.hm[0][2 * tid + 1] = 0ull;
-    __syncthreads();
-    en.first_walk([&](int, int b, unsigned long long pf) {
-        atomicAdd(&s.hm[0][b], pf + ONE_ENTRY);
-    });
+    if constexpr (CACHED) {
+        // the histogram all blocks have added to (left at zero for the next call), and this thread's bucket numbers
+        {   // one 16-byte piece: this thread's two words
+            const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(a.sc_hist, 0, NB * 8, 0x00020000);
+            const u32x4 v = coherent_load16(hrs, 16u * (unsigned)tid);
+            en.load_buckets(a.sc_bk);
+            s.hm[0][2 * tid] = ((unsigned long long)v.y << 32) | v.x;
+            s.hm[0][2 * tid + 1] = ((unsigned long long)v.w << 32) | v.z;
+        }
+    } else {
+        s.hm[0][2 * tid] = 0ull; s.hm[0][2 * tid + 1] = 0ull;
+        __syncthreads();
+        en.first_walk([&](int, int b, unsigned long long pf) {
+            atomicAdd(&s.hm[0][b], pf + ONE_ENTRY);
+        });
+    }
     __syncthreads();
     prefix_sums(s, 0);
 
@@ -340,6 +383,10 @@ __global__ __launch_bounds__(SNT) void nucleus_kernel(const NucleusArgs a) {
     int tok = s.r_id;
     if (s.r_key > key_T) tok = id_T;   // (only rounding could take it past the nucleus)
 
+    if (CACHED) {
+        __hip_atomic_store(as_global(a.sc_hist) + 2 * tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(a.sc_hist) + 2 * tid + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (tid == 0) {   // the pass's state: one draft (k = 1, gamma = 1)
         const float logp = __fdiv_rn(as_global(a.logits)[tok], a.tau) - lse;
         int tail[SPD_TAIL];
