@@ -332,6 +332,36 @@ __device__ __forceinline__ float group_sum_last(float v, int lpp) {
     return v;
 }
 
+// The same for N values at once, step by step: the N independent lane-crossing moves of a step sit
+// between two (wave-uniform) branches and overlap, where N calls of group_sum_last run as N chains.
+template <int N>
+__device__ __forceinline__ void group_sums_last(float (&v)[N], int lpp) {
+    if (lpp >= 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0xB1, 0xF>(v[i], 0.f);
+    }
+    if (lpp >= 4) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0x4E, 0xF>(v[i], 0.f);
+    }
+    if (lpp >= 8) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0x141, 0xF>(v[i], 0.f);
+    }
+    if (lpp >= 16) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0x140, 0xF>(v[i], 0.f);
+    }
+    if (lpp >= 32) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0x142, 0xA>(v[i], 0.f);
+    }
+    if (lpp >= 64) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += dpp_move<0x143, 0xC>(v[i], 0.f);
+    }
+}
+
 // a.k_new / a.v_new (the persistent kernel): the newest position's key and value rows are not
 // read from the cache but from activation vectors [n_kv_heads * d_head] that the QKV phase of
 // this very launch is writing, and so is the query: all three are awaited as data (looked at
@@ -459,18 +489,29 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                     if (t < t1c) kb[i] = kv_piece<KT>(Kg + ((size_t)t * dh + li * VEC) * sizeof(KT));
                 }
             }
+            // all rows' dot products first, without a branch between them (their chains of dependent
+            // operations interleave), then the stores
+            float dd[ATTN_BATCH];
 #pragma unroll
             for (int i = 0; i < ATTN_BATCH; ++i) {
-                const int t = b0 + i * PPB;
                 float kf[VEC];
                 Store<KT>::unpack(kb[i], kf);
                 float d = 0.f;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) d = fmaf(kf[v], qv[v], d);
-                d = group_sum_last(d, LPP) * scale;   // complete in the group's last lane
-                if (t < t1c && li == LPP - 1) {
-                    sc[t - t0] = d;
-                    lmax = fmaxf(lmax, d);
+                dd[i] = d;
+            }
+            group_sums_last<ATTN_BATCH>(dd, LPP);   // complete in each group's last lane
+#pragma unroll
+            for (int i = 0; i < ATTN_BATCH; ++i) dd[i] *= scale;
+            if (li == LPP - 1) {
+#pragma unroll
+                for (int i = 0; i < ATTN_BATCH; ++i) {
+                    const int t = b0 + i * PPB;
+                    if (t < t1c) {
+                        sc[t - t0] = dd[i];
+                        lmax = fmaxf(lmax, dd[i]);
+                    }
                 }
             }
         }
@@ -507,15 +548,15 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
                 }
             }
 #pragma unroll
-            for (int i = 0; i < ATTN_BATCH; ++i) {
+            for (int i = 0; i < ATTN_BATCH; ++i) {   // (no branch: a row past the chunk holds zeros and gets weight 0)
                 const int t = b0 + i * PPB;
-                if (t < t1c) {
-                    float vf[VEC];
-                    Store<KT>::unpack(vb[i], vf);
-                    const float p = sc[t - t0];
+                const bool row = t < t1c;
+                float vf[VEC];
+                Store<KT>::unpack(vb[i], vf);
+                const float ps = sc[row ? t - t0 : 0];
+                const float p = row ? ps : 0.f;
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
-                }
+                for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vf[v], acc[v]);
             }
         }
         if (new_lanes) {
@@ -527,8 +568,13 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
         for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
         __syncthreads();
         float o = 0.f;
-        if (tid < dh) {
-            for (int r = 0; r < PPB; ++r) o += dyn[(size_t)r * dh + tid];
+        if (tid < dh) {   // (PPB is a multiple of 4; four sums so that the LDS reads do not wait for one another)
+            float o4[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int r = 0; r < PPB; r += 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o4[j] += dyn[(size_t)(r + j) * dh + tid];
+            }
+            o = (o4[0] + o4[1]) + (o4[2] + o4[3]);
         }
         if (n_splits == 1) {
             if (tid < dh) {
