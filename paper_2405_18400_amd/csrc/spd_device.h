@@ -564,17 +564,24 @@ __device__ __forceinline__ void attn_item(const AttnArgs &a, int g, int s, int n
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[v] = fmaf(p, vnew[v], acc[v]);
         }
+        // the lane groups of a wave hold partial sums for the same features: add them across the wave
+        // (ascending distance, a fixed order), then the waves' sums through LDS
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) dyn[(size_t)(wid * PPW + sub) * dh + li * VEC + v] = acc[v];
+        for (int d = 1; d < WAVE; d <<= 1) {
+            if (d >= LPP) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[v] += __shfl_xor(acc[v], d, WAVE);
+            }
+        }
+        if (sub == 0) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) dyn[(size_t)wid * dh + li * VEC + v] = acc[v];
+        }
         __syncthreads();
         float o = 0.f;
-        if (tid < dh) {   // (PPB is a multiple of 4; four sums so that the LDS reads do not wait for one another)
-            float o4[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int r = 0; r < PPB; r += 4) {
+        if (tid < dh) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o4[j] += dyn[(size_t)(r + j) * dh + tid];
-            }
-            o = (o4[0] + o4[1]) + (o4[2] + o4[3]);
+            for (int r = 0; r < NWAVE; ++r) o += dyn[(size_t)r * dh + tid];
         }
         if (n_splits == 1) {
             if (tid < dh) {

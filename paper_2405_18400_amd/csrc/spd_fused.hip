@@ -40,8 +40,8 @@ constexpr int FUSED_QD_ITEM = 4;      // of which this many are requested before
 constexpr int FUSED_SLICE = 20;        // pieces that go out between two looks at the input
 constexpr int FUSED_SLICE_GATE = 4;   // the first slice of the gate/up phase (its input follows the attention within a microsecond or two)
 constexpr int FUSED_SLICE_WIDE = 4;   // the same for models whose d_model takes two block passes
-constexpr int FUSED_HALF_NARROW_UPTO = 160;   // an fp16 cache is read 8 bytes (4 elements) per lane, like the fp32 one, up to this
-                                              // many positions (one batch of loads), 16 bytes per lane beyond
+// An fp16 cache is read 8 bytes (4 elements) per lane, like the fp32 one, while the context fits one batch of
+// loads (160 positions), 16 bytes per lane beyond:
 constexpr int FUSED_HALF_ROWS_ONE = 8;        // 16 bytes per lane: rows in flight per lane where a head is one item (256 positions per batch)
 constexpr int FUSED_HALF_ROWS_CUT = 6;        // ... and where the context is cut into chunks (192 per batch: chunks of contexts up to 1536)
 constexpr int FUSED_ONE_CHUNK_HALF = 512;     // FUSED_ONE_CHUNK for an fp16 cache: half the bytes per position
@@ -781,19 +781,23 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(const FusedArgs a) {
             const int group = a.n_heads / a.n_kv_heads;
             for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
                 const int h = item / n_splits;
+                // (the 13B class holds a 20-row pass-major tile in registers through the other phases and
+                // spills with the full set: its items keep fewer cached rows in flight)
+                constexpr bool TIGHT = PA == 2 && PMD;
+                constexpr int R4 = TIGHT ? 8 : 10, R8_ONE = TIGHT ? 6 : FUSED_HALF_ROWS_ONE, R8_CUT = TIGHT ? 5 : FUSED_HALF_ROWS_CUT;
                 if constexpr (sizeof(KT) == 2) {
-                    if (n_ctx <= FUSED_HALF_NARROW_UPTO)
-                        attn_item<half4_t, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                                     h % group, h % group + 1, err);
+                    if (n_ctx <= 16 * R4)   // one batch of 8-byte pieces
+                        attn_item<half4_t, NT, true, R4>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                         h % group, h % group + 1, err);
                     else if (n_splits == 1)
-                        attn_item<half_t, NT, true, FUSED_HALF_ROWS_ONE>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                                                         h % group, h % group + 1, err);
+                        attn_item<half_t, NT, true, R8_ONE>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                            h % group, h % group + 1, err);
                     else
-                        attn_item<half_t, NT, true, FUSED_HALF_ROWS_CUT>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                                                         h % group, h % group + 1, err);
+                        attn_item<half_t, NT, true, R8_CUT>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                            h % group, h % group + 1, err);
                 } else {
-                    attn_item<KT, NT, true>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
-                                            h % group, h % group + 1, err);
+                    attn_item<KT, NT, true, R4>(t, h / group, item % n_splits, n_ctx, sh.sc, sh.red, dyn, &sh.s_last,
+                                                h % group, h % group + 1, err);
                 }
             }
         }
