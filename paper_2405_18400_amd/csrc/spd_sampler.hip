@@ -179,10 +179,12 @@ struct Entries {
         if (CACHED) {
             static_assert(ITEMS <= 32, "one bit per entry");
             unsigned hits = 0u;
+            const unsigned both = (unsigned)b1 | ((unsigned)b1 << 16);
 #pragma unroll
-            for (int c = 0; c < ITEMS; ++c) {
-                const unsigned b = (c & 1) ? bk[c / 2] >> 16 : bk[c / 2] & 0xFFFFu;
-                hits |= (unsigned)((int)b == b1) << c;
+            for (int r = 0; r < ITEMS / 2; ++r) {   // two bucket numbers per register
+                const unsigned x = bk[r] ^ both;
+                hits |= (unsigned)((x & 0xFFFFu) == 0u) << (2 * r);
+                hits |= (unsigned)((x >> 16) == 0u) << (2 * r + 1);
             }
             while (hits) {   // (few: a bucket holds some dozens of the block's entries)
                 const int c = __ffs(hits) - 1;
@@ -268,9 +270,10 @@ __device__ __forceinline__ void search(Stage &s, Entries<CACHED> &en, unsigned l
     });
     __syncthreads();
     const int nl = s.n_list;   // == n
-    {   // all pairs: entry i against a quarter of the list each
-        const int i = t % LC, part = t / LC;
-        constexpr int PARTS = SNT / LC;
+    {   // all pairs: entry i against one part of the list each; the shorter the list, the more parts
+        const int slots = nl <= 32 ? 32 : nl <= 64 ? 64 : nl <= 128 ? 128 : LC;
+        const int i = t % slots, part = t / slots;
+        const int PARTS = SNT / slots;
         if (i < nl) {
             const unsigned long long ki = s.lk[i];
             unsigned cnt = 0u;
