@@ -232,10 +232,11 @@ __global__ __launch_bounds__(BLOCK) void topk_partial_kernel(const TopkArgs a) {
 
 // ------------------------------------------------------------------ expand, interpolate, prune
 // Linear probing, NG_PROBE_BATCH consecutive slots per trip to memory (32-byte slots: a batch
-// is one or two cache lines; every trip is a random access into a table far larger than any
-// cache, and the kernel waits for the longest chain of all its probes).  The slots are then
+// is two or three cache lines; every trip is a random access into a table far larger than any
+// cache, and the kernel waits for the longest chain of all its probes: at a load factor of 0.7
+// some of a step's 60..360 probes walk past four slots, few past eight).  The slots are then
 // examined in probing order, so the result is that of a slot-by-slot walk.
-constexpr int NG_PROBE_BATCH = 4;
+constexpr int NG_PROBE_BATCH = 8;
 __device__ __forceinline__ unsigned long long ngram_probe(const NgramDev &ng, const int32_t *key) {
     uint64_t at = ngram_home(ngram_hash(key), ng.capacity);
     for (int p = 0; p <= ng.max_probe; p += NG_PROBE_BATCH) {
