@@ -358,6 +358,41 @@ def test_fp16_cache_head_width_32_plain_prefix_attention():
     assert max(s["logit_err"] for s in stats if "logit_err" in s) < FP16_CACHE_LOGIT_ERR
 
 
+def test_fp16_cache_graph_replay_is_bit_exact_across_the_switch_of_reading_widths():
+    """A free-running generation whose context passes 160 positions (where the persistent kernel
+    goes from 8-byte to 16-byte pieces of the fp16 cache): graph replay, plain launches and a
+    second replayed generation give the same bits; the per-operator forward agrees to rounding."""
+    pkg = P()
+    shape = synth.ModelShape("small-bf16", 3, 512, 8, 2, 1408, 2048, "bf16")
+    w = synth.make_weights(shape, seed=5)
+    prefix = synth.make_prefix_zipf(shape.vocab, 150, seed=9)
+    dc = pkg.SpdDecodeCfg(3, 0.0, 1.0, 0.1)
+    sess = session(shape, w, max_ctx=200, kv_dtype="fp16")
+    try:
+        drafts, scores = sess.spd_generate(prefix, dc, 24)
+        logits = sess.spd_read_logits()
+        sess.spd_set_graph(False)
+        drafts2, scores2 = sess.spd_generate(prefix, dc, 24)
+        assert np.array_equal(drafts, drafts2) and np.array_equal(scores, scores2)
+        assert np.array_equal(logits, sess.spd_read_logits())
+        sess.spd_set_graph(True)
+        drafts3, scores3 = sess.spd_generate(prefix, dc, 24)
+        assert np.array_equal(drafts, drafts3) and np.array_equal(scores, scores3)
+        # the same prefix and the same first timesteps through one kernel per operator
+        sess.spd_prefill(prefix)
+        sess.spd_step(dc)
+        sess.spd_step(dc)
+        fused = sess.spd_read_logits()
+        sess.spd_set_fused(False)
+        sess.spd_prefill(prefix)
+        sess.spd_step(dc)
+        sess.spd_step(dc)
+        per_op = sess.spd_read_logits()
+        np.testing.assert_allclose(fused, per_op, rtol=0, atol=2e-5 * np.abs(per_op).max())
+    finally:
+        sess.close()
+
+
 def test_dense_prefix_pass_is_refused_where_it_does_not_exist(tiny):
     shape, w, tabs, prefix = tiny           # fp32 weights
     sess = session(shape, w)
